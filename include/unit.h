@@ -1,0 +1,192 @@
+/*
+ * libunit -- mixed-precision conv2d / matmul on MI355X (gfx950) MFMA units.
+ *
+ * The operations are the ones the UNIT paper compiles tensorized instructions
+ * for: dense tensor operations whose low-precision elementwise products are
+ * reduced "horizontally" into one high-precision accumulator (Section I;
+ * Section II-A).  int8 x int8 accumulates in int32, fp16 x fp16 accumulates in
+ * fp32 (Section III-A).
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or keeps them.  Scratch comes from the caller's
+ *     workspace `ws` (device memory, 256-byte aligned, at least as large as the
+ *     matching *_workspace query).
+ *   - `stream` is a hipStream_t passed as void* (NULL = default stream).  Calls
+ *     enqueue work on it and return without synchronising.
+ *   - fp16 tensors travel as uint16_t IEEE binary16 bit patterns.
+ *   - Return value: UNIT_OK (0) or a negative unit_status.  Argument errors are
+ *     detected on the host before anything is launched.
+ *   - Concurrent calls are safe if their outputs and workspaces do not overlap.
+ */
+#ifndef UNIT_H
+#define UNIT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum unit_status {
+    UNIT_OK         =  0,
+    UNIT_EINVAL     = -1,   /* NULL pointer, non-positive dimension, empty output, misalignment */
+    UNIT_ENOTSUP    = -2,   /* shape outside what the kernels cover                             */
+    UNIT_EOVERFLOW  = -3,   /* int8 reduction length > 131071: int32 sum not provably exact     */
+    UNIT_EWORKSPACE = -4,   /* workspace NULL or too small                                      */
+    UNIT_EHIP       = -5    /* a HIP runtime call or kernel launch failed                       */
+};
+
+enum unit_dtype { UNIT_I8 = 0, UNIT_F16 = 1 };
+
+/* Longest int8 reduction (c*r*s, or k for matmul) with |sum| <= len * 2^14 < 2^31. */
+#define UNIT_MAX_REDUCTION_I8 131071
+
+/*
+ * conv2d problem (Section III-C.2 index forms: c[x,y,k] += a[x+r,y+s,rc]*b[r,s,k,rc]):
+ * cross-correlation with zero padding, dilation 1, groups 1.
+ *   x: [n,c,h,w] (NCHW)    w: [k,c,r,s] (OIHW)    y: [n,k,p,q]
+ *   p = floor((h + 2*pad_h - r)/stride_h) + 1,  q likewise.
+ */
+typedef struct unit_conv2d_desc {
+    int32_t n, c, h, w;
+    int32_t k, r, s;
+    int32_t stride_h, stride_w, pad_h, pad_w;
+} unit_conv2d_desc;
+
+/*
+ * Fused epilogue back to int8 (the quantised-inference use the paper targets,
+ * Section II-A, Section V-C):
+ *   t = acc + bias[k] + residual[n,k,p,q]           (int32; caller keeps |t| < 2^31)
+ *   g = (float)t * scale[k]                          (RNE conversion, one fp32 multiply)
+ *   i = round-half-to-even(g); if relu: i = max(i,0); clamp to [-128,127]
+ */
+typedef struct unit_requant {
+    const float   *scale;      /* device [k]; finite                    */
+    const int32_t *bias;       /* device [k] or NULL                    */
+    const int32_t *residual;   /* device [n,k,p,q] int32 (NCHW) or NULL */
+    int32_t        relu;       /* 0 or 1                                */
+} unit_requant;
+
+/* Tile choice made by the selector for one problem (introspection / reports). */
+typedef struct unit_tile_info {
+    int32_t block_m, block_n;   /* workgroup tile: block_m output rows (out channels / matmul m),
+                                   block_n output columns (pixels / matmul n)                      */
+    int32_t block_k_bytes;      /* reduction bytes staged per main-loop step                       */
+    int32_t waves_m, waves_n, waves_k;  /* wave grid inside the workgroup (waves_k = in-group split) */
+    int32_t mfma;               /* 32 or 16: MFMA tile edge                                        */
+    int32_t split_k;            /* number of workgroups sharing one output tile (grid split)       */
+    int32_t workgroups;         /* total launched                                                  */
+} unit_tile_info;
+
+int         unit_version(void);
+const char *unit_status_str(int status);
+/* Text of the last HIP error seen by this thread ("" if none). */
+const char *unit_last_hip_error(void);
+
+/* ------------------------------------------------------------------ queries (host only) */
+
+/* Output extent; UNIT_EINVAL if any dimension is non-positive or the output is empty. */
+int unit_conv2d_out_dims(const unit_conv2d_desc *d, int32_t *p, int32_t *q);
+
+/* Bytes of the internal layouts (both multiples of 256):
+ *   activations  [n][h][w][cp]       cp = c rounded up to 16 bytes of channels
+ *   weights      [k][r][s][cp]       reduction-contiguous per output channel            */
+size_t unit_packed_act_bytes(int32_t n, int32_t c, int32_t h, int32_t w, int dtype);
+size_t unit_packed_weights_bytes(const unit_conv2d_desc *d, int dtype);
+
+/* Workspace needed by unit_conv2d_{i8,f16} (packs both operands internally) and by
+ * unit_conv2d_packed_* (split-K partial sums only; may be 0).  0 on invalid input. */
+size_t unit_conv2d_workspace(const unit_conv2d_desc *d, int dtype);
+size_t unit_conv2d_packed_workspace(const unit_conv2d_desc *d, int dtype);
+size_t unit_matmul_workspace(int32_t m, int32_t n, int32_t k, int64_t lda, int64_t ldb, int dtype);
+
+/* What the selector picks (the paper's tuner, Section III-C.3 / IV-B: register window,
+ * fused spatial dims, split reduction).  conv: rows = k, cols = n*p*q, kbytes = r*s*cp. */
+int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out);
+int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_info *out);
+
+/* ------------------------------------------------------------------ plain-layout calls */
+
+/*
+ * int8 conv2d.  x: NCHW int8, w: OIHW int8.
+ *   rq == NULL : y_i32 (NKPQ int32) receives the raw accumulators; y_i8 must be NULL.
+ *   rq != NULL : y_i8 (NKPQ int8) receives the requantised result; y_i32 may also be
+ *                given to receive the raw accumulators (before bias/residual).
+ * Errors: UNIT_EINVAL, UNIT_EOVERFLOW (c*r*s > UNIT_MAX_REDUCTION_I8), UNIT_EWORKSPACE, UNIT_EHIP.
+ */
+int unit_conv2d_i8(const unit_conv2d_desc *d, const int8_t *x, const int8_t *w,
+                   int32_t *y_i32, const unit_requant *rq, int8_t *y_i8,
+                   void *ws, size_t ws_bytes, void *stream);
+
+/* fp16 conv2d with fp32 accumulation.  x: NCHW, w: OIHW (binary16 bits), y: NKPQ float. */
+int unit_conv2d_f16(const unit_conv2d_desc *d, const uint16_t *x, const uint16_t *w,
+                    float *y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * C[m,n] = sum_k A[m,k] * B[k,n].   A row-major (A[m,k] at A[m*lda+k]), B column-major
+ * (B[k,n] at B[n*ldb+k]), C row-major (C[m*ldc+n]); leading dimensions in elements,
+ * lda,ldb >= k, ldc >= n.  Operands whose base or leading dimension is not 16-byte
+ * aligned, or whose k is not a multiple of 16 bytes, are first copied into the
+ * workspace with zero padding (unit_matmul_workspace accounts for it).
+ * Errors: UNIT_EINVAL, UNIT_EOVERFLOW (int8, k > UNIT_MAX_REDUCTION_I8), UNIT_EWORKSPACE, UNIT_EHIP.
+ */
+int unit_matmul_i8(int32_t m, int32_t n, int32_t k,
+                   const int8_t *A, int64_t lda, const int8_t *B, int64_t ldb,
+                   int32_t *C, int64_t ldc, void *ws, size_t ws_bytes, void *stream);
+int unit_matmul_f16(int32_t m, int32_t n, int32_t k,
+                    const uint16_t *A, int64_t lda, const uint16_t *B, int64_t ldb,
+                    float *C, int64_t ldc, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------ packed (steady-state) calls
+ * The paper converts layouts once at graph level and keeps activations in the blocked
+ * layout between layers (Section V-C; Section II-C.1 on tensor padding).  These calls
+ * expose that: weights are packed once, activations stay packed from layer to layer.  */
+
+int unit_pack_act_i8 (int32_t n, int32_t c, int32_t h, int32_t w, const int8_t *x_nchw,
+                      void *x_packed, size_t packed_bytes, void *stream);
+int unit_pack_act_f16(int32_t n, int32_t c, int32_t h, int32_t w, const uint16_t *x_nchw,
+                      void *x_packed, size_t packed_bytes, void *stream);
+int unit_pack_weights_i8 (const unit_conv2d_desc *d, const int8_t *w_oihw,
+                          void *w_packed, size_t packed_bytes, void *stream);
+int unit_pack_weights_f16(const unit_conv2d_desc *d, const uint16_t *w_oihw,
+                          void *w_packed, size_t packed_bytes, void *stream);
+/* Packed int8 activations [n][h][w][cp] back to NCHW (for inspection / tests). */
+int unit_unpack_act_i8(int32_t n, int32_t c, int32_t h, int32_t w, const void *x_packed,
+                       int8_t *x_nchw, void *stream);
+
+/*
+ * conv2d on packed operands.  Outputs (any subset, at least one):
+ *   y_i32    NKPQ int32 raw accumulators
+ *   y_i8     NKPQ int8 requantised            (needs rq)
+ *   y_packed [n][p][q][kp] int8 requantised, kp = k rounded up to 16: the next layer's
+ *            packed input; its padding channels are written as 0   (needs rq)
+ */
+int unit_conv2d_packed_i8(const unit_conv2d_desc *d, const void *x_packed, const void *w_packed,
+                          int32_t *y_i32, const unit_requant *rq, int8_t *y_i8, void *y_packed,
+                          void *ws, size_t ws_bytes, void *stream);
+int unit_conv2d_packed_f16(const unit_conv2d_desc *d, const void *x_packed, const void *w_packed,
+                           float *y, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------ int8 network glue
+ * Operators the chained int8 inference needs around the convolutions.  They work on the
+ * packed int8 layout [n][h][w][cp].                                                        */
+
+/* Max over a window; padded positions never win.  Output packed [n][p][q][cp]. */
+int unit_maxpool_packed_i8(int32_t n, int32_t c, int32_t h, int32_t w,
+                           int32_t window, int32_t stride, int32_t pad,
+                           const void *x_packed, void *y_packed, void *stream);
+/* int32 sum over h*w per (n,c), then the requantise rule with scale[c] (no ReLU).
+ * Output: [n][cp] int8 (row-major, padding channels 0): the A operand of the FC matmul. */
+int unit_global_avgpool_packed_i8(int32_t n, int32_t c, int32_t h, int32_t w,
+                                  const void *x_packed, const float *scale,
+                                  int8_t *y, void *stream);
+/* residual[n,k,p,q] (int32 NCHW) = (int32)x_packed[n,p,q,k] * mult. */
+int unit_widen_residual_i8(int32_t n, int32_t c, int32_t h, int32_t w,
+                           const void *x_packed, int32_t mult, int32_t *residual, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UNIT_H */

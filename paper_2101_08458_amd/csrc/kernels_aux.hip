@@ -1,0 +1,284 @@
+// Layout packing, split-reduction epilogue and the small int8 network operators.
+// All of them are bandwidth-bound permutations / elementwise passes.
+#include "unit_internal.h"
+
+namespace unit {
+
+// ------------------------------------------------------------------ pack_act
+// NCHW -> [n][h*w][cp] with cp = channels padded to 16 bytes (zero filled): the graph
+// level layout change of the paper (Section V-C; Section II-C.1 for the padding) done as
+// one tiled transpose through LDS.  T = int8_t (16 channels per chunk) or uint16_t (8).
+template <typename T>
+__global__ void __launch_bounds__(256)
+pack_act_kernel(const T *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW, int cp)
+{
+    constexpr int CH = 16 / sizeof(T);            // channels per 16-byte chunk
+    constexpr int TP = 64;                        // pixels per tile
+    constexpr int TC = 64;                        // channels per tile
+    __shared__ T tile[TC][TP + 4 / sizeof(T)];
+    const int tid = threadIdx.x;
+    const int hw0 = blockIdx.x * TP, c0 = blockIdx.y * TC, n = blockIdx.z;
+    const T *xn = x + (long)n * C * HW;
+    {
+        const int px = tid & 63;
+#pragma unroll
+        for (int i = 0; i < TC / 4; ++i) {
+            int c = (tid >> 6) + 4 * i;
+            T v = 0;
+            if (c0 + c < C && hw0 + px < HW) v = xn[(long)(c0 + c) * HW + hw0 + px];
+            tile[c][px] = v;
+        }
+    }
+    __syncthreads();
+    constexpr int CHUNKS = TC / CH;               // chunks per pixel inside the tile
+#pragma unroll
+    for (int i = 0; i < TP * CHUNKS / 256; ++i) {
+        int id = tid + i * 256;
+        int px = id / CHUNKS, cc = id % CHUNKS;
+        if (hw0 + px >= HW || c0 + cc * CH >= cp) continue;
+        __attribute__((aligned(16))) T vals[CH];
+#pragma unroll
+        for (int e = 0; e < CH; ++e) vals[e] = tile[cc * CH + e][px];
+        *reinterpret_cast<v4i *>(xp + (((long)n * HW + hw0 + px) * cp + c0 + cc * CH) * sizeof(T)) =
+            *reinterpret_cast<const v4i *>(vals);
+    }
+}
+
+hipError_t launch_pack_act(int dtype, int n, int c, int h, int w, const void *x, void *xp, hipStream_t st)
+{
+    const int hw = h * w;
+    if (dtype == DT_I8) {
+        const int cp = (c + 15) / 16 * 16;
+        dim3 grid((hw + 63) / 64, (cp + 63) / 64, n);
+        hipLaunchKernelGGL(pack_act_kernel<int8_t>, grid, dim3(256), 0, st,
+                           (const int8_t *)x, (uint8_t *)xp, c, hw, cp);
+    } else {
+        const int cp = (c + 7) / 8 * 8;
+        dim3 grid((hw + 63) / 64, (cp + 63) / 64, n);
+        hipLaunchKernelGGL(pack_act_kernel<uint16_t>, grid, dim3(256), 0, st,
+                           (const uint16_t *)x, (uint8_t *)xp, c, hw, cp);
+    }
+    return hipGetLastError();
+}
+
+// packed int8 [n][hw][cp] -> NCHW
+__global__ void unpack_act_i8_kernel(const int8_t *__restrict__ xp, int8_t *__restrict__ x,
+                                     int C, int HW, int cp, long total)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int px = i % HW;
+    long nc = i / HW;
+    int c = nc % C;
+    long n = nc / C;
+    x[i] = xp[(n * HW + px) * cp + c];
+}
+
+hipError_t launch_unpack_act_i8(int n, int c, int h, int w, const void *xp, int8_t *x, hipStream_t st)
+{
+    long total = (long)n * c * h * w;
+    int cp = (c + 15) / 16 * 16;
+    hipLaunchKernelGGL(unpack_act_i8_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const int8_t *)xp, x, c, h * w, cp, total);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ pack_weights
+// OIHW -> [k][r][s][cp]: each output channel's reduction becomes one contiguous,
+// zero-padded row (the "column-major B" of the implicit GEMM).  Done once per layer.
+template <typename T>
+__global__ void pack_weights_kernel(const T *__restrict__ w, T *__restrict__ wp,
+                                    int C, int RS, int cp, long total)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;   // index into wp
+    if (i >= total) return;
+    int c = i % cp;
+    long t = i / cp;
+    int rs = t % RS;
+    long k = t / RS;
+    wp[i] = (c < C) ? w[(k * C + c) * RS + rs] : (T)0;
+}
+
+hipError_t launch_pack_weights(int dtype, int k, int c, int r, int s, const void *w, void *wp, hipStream_t st)
+{
+    if (dtype == DT_I8) {
+        int cp = (c + 15) / 16 * 16;
+        long total = (long)k * r * s * cp;
+        hipLaunchKernelGGL(pack_weights_kernel<int8_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           (const int8_t *)w, (int8_t *)wp, c, r * s, cp, total);
+    } else {
+        int cp = (c + 7) / 8 * 8;
+        long total = (long)k * r * s * cp;
+        hipLaunchKernelGGL(pack_weights_kernel<uint16_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                           (const uint16_t *)w, (uint16_t *)wp, c, r * s, cp, total);
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ pad_rows
+// Copy a [rows][row_bytes] matrix (row pitch ld_bytes, any alignment) into a dense
+// [rows][dst_row_bytes] one, zero filling the tail: matmul operands that do not meet the
+// 16-byte rule of the main kernel.
+__global__ void pad_rows_kernel(const uint8_t *__restrict__ src, long ld_bytes, int row_bytes,
+                                uint8_t *__restrict__ dst, int dst_row_bytes, long total)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int b = i % dst_row_bytes;
+    long r = i / dst_row_bytes;
+    dst[i] = (b < row_bytes) ? src[r * ld_bytes + b] : (uint8_t)0;
+}
+
+hipError_t launch_pad_rows(const void *src, long ld_bytes, int rows, int row_bytes,
+                           void *dst, int dst_row_bytes, hipStream_t st)
+{
+    long total = (long)rows * dst_row_bytes;
+    hipLaunchKernelGGL(pad_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const uint8_t *)src, ld_bytes, row_bytes, (uint8_t *)dst, dst_row_bytes, total);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ split-K reduce + epilogue
+// Sums the per-workgroup partial accumulators in slice order (fixed order: fp32 results
+// are run-to-run identical), then applies the same epilogue as the main kernel.  The
+// split reduction is the paper's "split reduction" tuning step (Section III-C.3) carried
+// across workgroups; the in-group part lives in the main kernel.
+template <typename E>
+__global__ void __launch_bounds__(256)
+splitk_reduce_kernel(const ReduceArgs a)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= a.total) return;
+    const E *p = reinterpret_cast<const E *>(a.partials) + i;
+    E sum = p[0];
+    for (int z = 1; z < a.nsplit; ++z) sum += p[(long)z * a.split_stride];
+    if (a.out) reinterpret_cast<E *>(a.out)[i] = sum;
+    if (a.epi == EPI_REQUANT) {
+        int px = i % a.PQ;
+        long nk = i / a.PQ;
+        int k = nk % a.K;
+        long n = nk / a.K;
+        int t = (int)sum;
+        if (a.bias) t += a.bias[k];
+        if (a.residual) t += a.residual[i];
+        int v = requant_elem(t, a.scale[k], a.relu);
+        if (a.out_i8) a.out_i8[i] = (int8_t)v;
+        if (a.out_packed) a.out_packed[(n * a.PQ + px) * a.packed_ld + k] = (int8_t)v;
+    }
+}
+
+// zero the padding channels [K, packed_ld) of a packed int8 output
+__global__ void zero_pad_channels_kernel(int8_t *yp, int K, int ld, long pixels)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    int npad = ld - K;
+    if (i >= pixels * npad) return;
+    yp[(i / npad) * ld + K + i % npad] = 0;
+}
+
+hipError_t launch_splitk_reduce(const ReduceArgs &a, hipStream_t st)
+{
+    dim3 grid((unsigned)((a.total + 255) / 256)), block(256);
+    if (a.dtype == DT_I8) hipLaunchKernelGGL(splitk_reduce_kernel<int>, grid, block, 0, st, a);
+    else                  hipLaunchKernelGGL(splitk_reduce_kernel<float>, grid, block, 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (a.epi == EPI_REQUANT && a.out_packed && a.packed_ld > a.K) {
+        long pixels = a.total / a.K;
+        long cnt = pixels * (a.packed_ld - a.K);
+        hipLaunchKernelGGL(zero_pad_channels_kernel, dim3((unsigned)((cnt + 255) / 256)), dim3(256), 0, st,
+                           a.out_packed, a.K, a.packed_ld, pixels);
+        e = hipGetLastError();
+    }
+    return e;
+}
+
+// ------------------------------------------------------------------ int8 network glue
+// max-pool on packed int8: one thread per (n, p, q, 16-channel chunk)
+__global__ void maxpool_packed_i8_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y,
+                                         int cp, int H, int W, int P, int Q,
+                                         int window, int stride, int pad, long total)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    const int chunks = cp / 16;
+    int cc = i % chunks;
+    long t = i / chunks;
+    int q = t % Q;  t /= Q;
+    int p = t % P;
+    long n = t / P;
+    int best[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) best[e] = -128;
+    for (int r = 0; r < window; ++r) {
+        int h = p * stride + r - pad;
+        if (h < 0 || h >= H) continue;
+        for (int s = 0; s < window; ++s) {
+            int w = q * stride + s - pad;
+            if (w < 0 || w >= W) continue;
+            v4i raw = *reinterpret_cast<const v4i *>(x + ((n * H + h) * W + w) * cp + cc * 16);
+            const int8_t *b = reinterpret_cast<const int8_t *>(&raw);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) best[e] = (b[e] > best[e]) ? b[e] : best[e];
+        }
+    }
+    __attribute__((aligned(16))) int8_t outv[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) outv[e] = (int8_t)best[e];
+    *reinterpret_cast<v4i *>(y + ((n * P + p) * Q + q) * cp + cc * 16) = *reinterpret_cast<const v4i *>(outv);
+}
+
+hipError_t launch_maxpool_packed_i8(int n, int cp, int h, int w, int window, int stride, int pad,
+                                    int p, int q, const void *x, void *y, hipStream_t st)
+{
+    long total = (long)n * p * q * (cp / 16);
+    hipLaunchKernelGGL(maxpool_packed_i8_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const int8_t *)x, (int8_t *)y, cp, h, w, p, q, window, stride, pad, total);
+    return hipGetLastError();
+}
+
+// global average pool: integer sum then requantise; one thread per (n, channel)
+__global__ void avgpool_packed_i8_kernel(const int8_t *__restrict__ x, const float *__restrict__ scale,
+                                         int8_t *__restrict__ y, int C, int cp, int HW, long total)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= total) return;
+    int c = i % cp;
+    long n = i / cp;
+    if (c >= C) { y[i] = 0; return; }
+    int sum = 0;
+    for (int px = 0; px < HW; ++px) sum += (int)x[(n * HW + px) * cp + c];
+    y[i] = (int8_t)requant_elem(sum, scale[c], 0);
+}
+
+hipError_t launch_avgpool_packed_i8(int n, int c, int cp, int hw, const void *x, const float *scale,
+                                    int8_t *y, hipStream_t st)
+{
+    long total = (long)n * cp;
+    hipLaunchKernelGGL(avgpool_packed_i8_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const int8_t *)x, scale, y, c, cp, hw, total);
+    return hipGetLastError();
+}
+
+__global__ void widen_residual_i8_kernel(const int8_t *__restrict__ x, int32_t *__restrict__ res,
+                                         int C, int cp, int HW, int mult, long total)
+{
+    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;   // NCHW index
+    if (i >= total) return;
+    int px = i % HW;
+    long nc = i / HW;
+    int c = nc % C;
+    long n = nc / C;
+    res[i] = (int)x[(n * HW + px) * cp + c] * mult;
+}
+
+hipError_t launch_widen_residual_i8(int n, int c, int cp, int hw, const void *x, int mult,
+                                    int32_t *res, hipStream_t st)
+{
+    long total = (long)n * c * hw;
+    hipLaunchKernelGGL(widen_residual_i8_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       (const int8_t *)x, res, c, cp, hw, mult, total);
+    return hipGetLastError();
+}
+
+}  // namespace unit

@@ -1,0 +1,73 @@
+// Tile-shape selector: maps (rows, cols, reduction length) of the implicit GEMM to one
+// of the compiled tile shapes plus a grid split of the reduction.  This is the paper's
+// tuner (Section III-C.3 and IV-B: accumulator window size, fused spatial dimensions,
+// split reduction; "profile and pick") reduced to a rule fitted to measurements, since
+// the paper finds that tuning beyond fuse + split adds little (Section VI-B).
+#include <cstdlib>
+
+#include "unit_internal.h"
+
+namespace unit {
+
+#define UNIT_TILE_CASE(ID, BM, BN, BKB, WGM, WGN, WGK, MF) \
+    {BM, BN, BKB, WGM, WGN, WGK, MF},
+const TileCfg g_tiles[NUM_TILES] = {
+#include "tiles.def"
+};
+#undef UNIT_TILE_CASE
+
+static int env_int(const char *name, int dflt)
+{
+    const char *v = std::getenv(name);
+    return (v && *v) ? std::atoi(v) : dflt;
+}
+
+static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
+
+TileChoice select_tile(int rows, int cols, int kchunks, int dtype, bool conv, bool allow_split)
+{
+    (void)dtype; (void)conv;
+    const int CUS = 256;
+    int tile = -1;
+    if (rows <= 16) {
+        tile = 5;
+    } else {
+        // largest tile that still gives every compute unit a workgroup
+        static const int order[] = {0, 1, 2};
+        for (int t : order) {
+            const TileCfg &c = g_tiles[t];
+            long nt = (long)cdiv(rows, c.bm) * cdiv(cols, c.bn);
+            double fill = (double)rows * cols / ((double)nt * c.bm * c.bn);
+            if (nt >= CUS * 3 / 4 && fill >= 0.6) { tile = t; break; }
+        }
+        if (tile < 0) tile = (rows > 32 && cols > 32) ? 2 : 4;
+    }
+    int forced = env_int("UNIT_TILE", -1);
+    if (forced >= 0 && forced < NUM_TILES) tile = forced;
+
+    const TileCfg &c = g_tiles[tile];
+    const int nch = c.bkb / 16;
+    const int ksteps = cdiv(kchunks, nch);
+    const long nt = (long)cdiv(rows, c.bm) * cdiv(cols, c.bn);
+    int split = 1;
+    if (nt < CUS) {
+        split = cdiv(2 * CUS, nt);                 // aim at two workgroups per compute unit
+        int max_split = ksteps / 2;                // keep at least two steps per slice
+        if (split > max_split) split = max_split;
+        if (split < 1) split = 1;
+    }
+    int fs = env_int("UNIT_SPLITK", -1);
+    if (fs >= 1) split = fs;
+    if (!allow_split) split = 1;
+    if (split > ksteps) split = ksteps;
+    int per = cdiv(ksteps, split);
+    split = cdiv(ksteps, per);                     // drop empty slices
+    TileChoice ch;
+    ch.tile = tile;
+    ch.split_k = split;
+    ch.ksteps_per_split = per;
+    ch.workgroups = (int)(nt * split);
+    return ch;
+}
+
+}  // namespace unit

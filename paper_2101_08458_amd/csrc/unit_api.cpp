@@ -1,0 +1,455 @@
+// C boundary of libunit: argument validation, workspace carving, tile selection and
+// kernel dispatch.  Every error path returns before the first HIP call.
+#include <cstdio>
+#include <cstring>
+
+#include "../../include/unit.h"
+#include "unit_internal.h"
+
+namespace unit {
+hipError_t launch_igemm_i8(bool conv, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
+hipError_t launch_igemm_f16(bool conv, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
+
+hipError_t launch_igemm(int dtype, bool conv, int tile, const IgemmArgs &a, int split_k, hipStream_t st)
+{
+    return dtype == DT_I8 ? launch_igemm_i8(conv, tile, a, split_k, st)
+                          : launch_igemm_f16(conv, tile, a, split_k, st);
+}
+}  // namespace unit
+
+using namespace unit;
+
+namespace {
+
+thread_local char g_hip_err[256] = "";
+
+int hip_fail(hipError_t e)
+{
+    std::snprintf(g_hip_err, sizeof g_hip_err, "%s", hipGetErrorString(e));
+    return UNIT_EHIP;
+}
+#define UNIT_HIP(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) return hip_fail(e_); } while (0)
+
+inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+inline int elem_size(int dtype) { return dtype == UNIT_I8 ? 1 : 2; }
+inline int chunk_elems(int dtype) { return 16 / elem_size(dtype); }
+inline int pad_channels(int c, int dtype) { int ch = chunk_elems(dtype); return (c + ch - 1) / ch * ch; }
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+inline bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255) == 0; }
+
+bool desc_ok(const unit_conv2d_desc *d)
+{
+    if (!d) return false;
+    if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->k <= 0 || d->r <= 0 || d->s <= 0) return false;
+    if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return false;
+    if (d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s) return false;
+    return true;
+}
+
+struct ConvGeom {
+    int p, q, cp, kchunks, rows;
+    long cols;
+    long out_elems;
+};
+
+int conv_geom(const unit_conv2d_desc *d, int dtype, ConvGeom *g)
+{
+    if (dtype != UNIT_I8 && dtype != UNIT_F16) return UNIT_EINVAL;
+    if (!desc_ok(d)) return UNIT_EINVAL;
+    g->p = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
+    g->q = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
+    g->cp = pad_channels(d->c, dtype);
+    long red = (long)d->c * d->r * d->s;
+    if (dtype == UNIT_I8 && red > UNIT_MAX_REDUCTION_I8) return UNIT_EOVERFLOW;
+    long kbytes = (long)d->r * d->s * g->cp * elem_size(dtype);
+    g->kchunks = (int)(kbytes / 16);
+    g->rows = d->k;
+    g->cols = (long)d->n * g->p * g->q;
+    g->out_elems = g->cols * d->k;
+    // index arithmetic in the kernels is 32-bit for rows/cols/chunks
+    if (g->cols > 0x7fffffffL || kbytes > 0x7fffffffL || g->out_elems > (1L << 40)) return UNIT_ENOTSUP;
+    if ((long)d->h * d->w * g->cp * elem_size(dtype) > 0x7fffffffL) return UNIT_ENOTSUP;
+    return UNIT_OK;
+}
+
+void fill_tile_info(const TileChoice &ch, unit_tile_info *out)
+{
+    const TileCfg &c = g_tiles[ch.tile];
+    out->block_m = c.bm;  out->block_n = c.bn;  out->block_k_bytes = c.bkb;
+    out->waves_m = c.wgm; out->waves_n = c.wgn; out->waves_k = c.wgk;
+    out->mfma = c.mf;     out->split_k = ch.split_k;  out->workgroups = ch.workgroups;
+}
+
+// Runs the main kernel (+ the split reduce when the selector splits across workgroups).
+int run_igemm(int dtype, bool conv, IgemmArgs a, long out_elems, int K, int PQ,
+              void *ws, size_t ws_bytes, hipStream_t st, bool allow_split = true)
+{
+    TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, conv, allow_split);
+    a.ksteps_per_split = ch.ksteps_per_split;
+    if (ch.split_k == 1) {
+        a.split_stride = 0;
+        UNIT_HIP(launch_igemm(dtype, conv, ch.tile, a, 1, st));
+        return UNIT_OK;
+    }
+    size_t need = (size_t)ch.split_k * out_elems * 4;
+    if (!ws || ws_bytes < need) return UNIT_EWORKSPACE;
+    IgemmArgs m = a;
+    m.out = ws;
+    m.split_stride = out_elems;
+    m.epi = EPI_RAW;
+    m.store_raw = 1;
+    if (!conv) {                                   // partials of a matmul are dense [rows][cols]
+        m.row_stride = a.cols;
+    }
+    UNIT_HIP(launch_igemm(dtype, conv, ch.tile, m, ch.split_k, st));
+    ReduceArgs r;
+    std::memset(&r, 0, sizeof r);
+    r.partials = ws;  r.nsplit = ch.split_k;  r.split_stride = out_elems;
+    r.dtype = dtype;  r.total = out_elems;  r.K = K;  r.PQ = PQ;
+    r.out = (a.epi == EPI_RAW || a.store_raw) ? a.out : nullptr;
+    r.epi = a.epi;  r.scale = a.scale;  r.bias = a.bias;  r.residual = a.residual;  r.relu = a.relu;
+    r.out_i8 = a.out_i8;  r.out_packed = a.out_packed;  r.packed_ld = a.packed_ld;
+    UNIT_HIP(launch_splitk_reduce(r, st));
+    return UNIT_OK;
+}
+
+int conv_packed(const unit_conv2d_desc *d, int dtype, const void *xp, const void *wp,
+                void *y_raw, const unit_requant *rq, int8_t *y_i8, void *y_packed,
+                void *ws, size_t ws_bytes, void *stream)
+{
+    ConvGeom g;
+    int rc = conv_geom(d, dtype, &g);
+    if (rc != UNIT_OK) return rc;
+    if (!xp || !wp) return UNIT_EINVAL;
+    if (!aligned16(xp) || !aligned16(wp)) return UNIT_EINVAL;
+    if (rq) {
+        if (dtype != UNIT_I8 || !rq->scale || (!y_i8 && !y_packed)) return UNIT_EINVAL;
+    } else {
+        if (!y_raw || y_i8 || y_packed) return UNIT_EINVAL;
+    }
+    if (ws && !aligned256(ws)) return UNIT_EINVAL;
+
+    IgemmArgs a;
+    std::memset(&a, 0, sizeof a);
+    const int es = elem_size(dtype);
+    a.A = static_cast<const uint8_t *>(wp);  a.lda = (long)g.kchunks * 16;  a.rows = d->k;
+    a.B = static_cast<const uint8_t *>(xp);  a.ldb = 0;                      a.cols = (int)g.cols;
+    a.kchunks = g.kchunks;
+    a.H = d->h;  a.W = d->w;  a.CB = g.cp * es / 16;  a.P = g.p;  a.Q = g.q;  a.PQ = g.p * g.q;
+    a.R = d->r;  a.S = d->s;  a.sh = d->stride_h;  a.sw = d->stride_w;  a.ph = d->pad_h;  a.pw = d->pad_w;
+    a.out = y_raw;  a.row_stride = a.PQ;  a.img_stride = (long)d->k * a.PQ;  a.cols_per_img = a.PQ;
+    if (rq) {
+        a.epi = EPI_REQUANT;  a.scale = rq->scale;  a.bias = rq->bias;  a.residual = rq->residual;
+        a.relu = rq->relu ? 1 : 0;
+        a.out_i8 = y_i8;  a.out_packed = static_cast<int8_t *>(y_packed);
+        a.packed_ld = pad_channels(d->k, UNIT_I8);
+        a.store_raw = y_raw ? 1 : 0;
+    } else {
+        a.epi = EPI_RAW;  a.store_raw = 1;
+    }
+    return run_igemm(dtype, true, a, g.out_elems, d->k, a.PQ, ws, ws_bytes, static_cast<hipStream_t>(stream));
+}
+
+size_t conv_split_bytes(const ConvGeom &g, int dtype)
+{
+    TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true);
+    return ch.split_k > 1 ? align256((size_t)ch.split_k * g.out_elems * 4) : 0;
+}
+
+int conv_plain(const unit_conv2d_desc *d, int dtype, const void *x, const void *w,
+               void *y_raw, const unit_requant *rq, int8_t *y_i8,
+               void *ws, size_t ws_bytes, void *stream)
+{
+    ConvGeom g;
+    int rc = conv_geom(d, dtype, &g);
+    if (rc != UNIT_OK) return rc;
+    if (!x || !w) return UNIT_EINVAL;
+    if (rq) {
+        if (dtype != UNIT_I8 || !rq->scale || !y_i8) return UNIT_EINVAL;
+    } else if (!y_raw || y_i8) {
+        return UNIT_EINVAL;
+    }
+    size_t act_b = unit_packed_act_bytes(d->n, d->c, d->h, d->w, dtype);
+    size_t wt_b = unit_packed_weights_bytes(d, dtype);
+    size_t split_b = conv_split_bytes(g, dtype);
+    if (!ws || ws_bytes < act_b + wt_b + split_b) return UNIT_EWORKSPACE;
+    if (!aligned256(ws)) return UNIT_EINVAL;
+    uint8_t *xp = static_cast<uint8_t *>(ws);
+    uint8_t *wp = xp + act_b;
+    uint8_t *part = wp + wt_b;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    UNIT_HIP(launch_pack_act(dtype, d->n, d->c, d->h, d->w, x, xp, st));
+    UNIT_HIP(launch_pack_weights(dtype, d->k, d->c, d->r, d->s, w, wp, st));
+    return conv_packed(d, dtype, xp, wp, y_raw, rq, y_i8, nullptr, split_b ? part : nullptr, split_b, stream);
+}
+
+struct MatmulGeom {
+    int kpad_bytes, kchunks;
+    bool pad_a, pad_b;
+    size_t a_bytes, b_bytes, split_bytes;
+};
+
+int matmul_geom(int m, int n, int k, long lda, long ldb, int dtype, MatmulGeom *g)
+{
+    if (dtype != UNIT_I8 && dtype != UNIT_F16) return UNIT_EINVAL;
+    if (m <= 0 || n <= 0 || k <= 0 || lda < k || ldb < k) return UNIT_EINVAL;
+    if (dtype == UNIT_I8 && k > UNIT_MAX_REDUCTION_I8) return UNIT_EOVERFLOW;
+    const int es = elem_size(dtype);
+    if ((long)k * es > 0x7fffff00L) return UNIT_ENOTSUP;
+    g->kpad_bytes = (int)(((long)k * es + 15) / 16 * 16);
+    g->kchunks = g->kpad_bytes / 16;
+    bool ktail = ((long)k * es) % 16 != 0;
+    g->pad_a = ktail || (lda * es) % 16 != 0;
+    g->pad_b = ktail || (ldb * es) % 16 != 0;
+    g->a_bytes = g->pad_a ? align256((size_t)m * g->kpad_bytes) : 0;
+    g->b_bytes = g->pad_b ? align256((size_t)n * g->kpad_bytes) : 0;
+    TileChoice ch = select_tile(m, n, g->kchunks, dtype, false);
+    g->split_bytes = ch.split_k > 1 ? align256((size_t)ch.split_k * m * n * 4) : 0;
+    return UNIT_OK;
+}
+
+int matmul_any(int dtype, int m, int n, int k, const void *A, long lda, const void *B, long ldb,
+               void *C, long ldc, void *ws, size_t ws_bytes, void *stream)
+{
+    MatmulGeom g;
+    int rc = matmul_geom(m, n, k, lda, ldb, dtype, &g);
+    if (rc != UNIT_OK) return rc;
+    if (!A || !B || !C || ldc < n) return UNIT_EINVAL;
+    const int es = elem_size(dtype);
+    if ((!g.pad_a && !aligned16(A)) || (!g.pad_b && !aligned16(B))) return UNIT_EINVAL;
+    if (reinterpret_cast<uintptr_t>(C) & 3) return UNIT_EINVAL;
+    size_t need = g.a_bytes + g.b_bytes + g.split_bytes;
+    if (need && (!ws || ws_bytes < need)) return UNIT_EWORKSPACE;
+    if (need && !aligned256(ws)) return UNIT_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    uint8_t *wsp = static_cast<uint8_t *>(ws);
+    const uint8_t *Ap = static_cast<const uint8_t *>(A);
+    const uint8_t *Bp = static_cast<const uint8_t *>(B);
+    long lda_b = lda * es, ldb_b = ldb * es;
+    if (g.pad_a) {
+        UNIT_HIP(launch_pad_rows(A, lda_b, m, k * es, wsp, g.kpad_bytes, st));
+        Ap = wsp;  lda_b = g.kpad_bytes;  wsp += g.a_bytes;
+    }
+    if (g.pad_b) {
+        UNIT_HIP(launch_pad_rows(B, ldb_b, n, k * es, wsp, g.kpad_bytes, st));
+        Bp = wsp;  ldb_b = g.kpad_bytes;  wsp += g.b_bytes;
+    }
+    IgemmArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.A = Ap;  a.lda = lda_b;  a.rows = m;
+    a.B = Bp;  a.ldb = ldb_b;  a.cols = n;
+    a.kchunks = g.kchunks;
+    a.out = C;  a.row_stride = ldc;  a.img_stride = 0;  a.cols_per_img = n;
+    a.epi = EPI_RAW;  a.store_raw = 1;
+    // the split reduce writes a dense [m][n] result: only usable when ldc == n
+    return run_igemm(dtype, false, a, (long)m * n, 1, n, g.split_bytes ? wsp : nullptr, g.split_bytes, st,
+                     ldc == n);
+}
+
+}  // namespace
+
+extern "C" {
+
+int unit_version(void) { return 100; }
+
+const char *unit_status_str(int status)
+{
+    switch (status) {
+    case UNIT_OK:         return "ok";
+    case UNIT_EINVAL:     return "invalid argument";
+    case UNIT_ENOTSUP:    return "unsupported shape";
+    case UNIT_EOVERFLOW:  return "int8 reduction too long for an exact int32 sum";
+    case UNIT_EWORKSPACE: return "workspace missing or too small";
+    case UNIT_EHIP:       return "HIP runtime error";
+    default:              return "unknown status";
+    }
+}
+
+const char *unit_last_hip_error(void) { return g_hip_err; }
+
+int unit_conv2d_out_dims(const unit_conv2d_desc *d, int32_t *p, int32_t *q)
+{
+    if (!desc_ok(d) || !p || !q) return UNIT_EINVAL;
+    *p = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
+    *q = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
+    return UNIT_OK;
+}
+
+size_t unit_packed_act_bytes(int32_t n, int32_t c, int32_t h, int32_t w, int dtype)
+{
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || (dtype != UNIT_I8 && dtype != UNIT_F16)) return 0;
+    return align256((size_t)n * h * w * pad_channels(c, dtype) * elem_size(dtype));
+}
+
+size_t unit_packed_weights_bytes(const unit_conv2d_desc *d, int dtype)
+{
+    if (!desc_ok(d) || (dtype != UNIT_I8 && dtype != UNIT_F16)) return 0;
+    return align256((size_t)d->k * d->r * d->s * pad_channels(d->c, dtype) * elem_size(dtype));
+}
+
+size_t unit_conv2d_packed_workspace(const unit_conv2d_desc *d, int dtype)
+{
+    ConvGeom g;
+    if (conv_geom(d, dtype, &g) != UNIT_OK) return 0;
+    return conv_split_bytes(g, dtype);
+}
+
+size_t unit_conv2d_workspace(const unit_conv2d_desc *d, int dtype)
+{
+    ConvGeom g;
+    if (conv_geom(d, dtype, &g) != UNIT_OK) return 0;
+    return unit_packed_act_bytes(d->n, d->c, d->h, d->w, dtype) + unit_packed_weights_bytes(d, dtype) +
+           conv_split_bytes(g, dtype);
+}
+
+size_t unit_matmul_workspace(int32_t m, int32_t n, int32_t k, int64_t lda, int64_t ldb, int dtype)
+{
+    MatmulGeom g;
+    if (matmul_geom(m, n, k, lda, ldb, dtype, &g) != UNIT_OK) return 0;
+    return g.a_bytes + g.b_bytes + g.split_bytes;
+}
+
+int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out)
+{
+    ConvGeom g;
+    int rc = conv_geom(d, dtype, &g);
+    if (rc != UNIT_OK) return rc;
+    if (!out) return UNIT_EINVAL;
+    fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true), out);
+    return UNIT_OK;
+}
+
+int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_info *out)
+{
+    MatmulGeom g;
+    int rc = matmul_geom(m, n, k, k, k, dtype, &g);
+    if (rc != UNIT_OK) return rc;
+    if (!out) return UNIT_EINVAL;
+    fill_tile_info(select_tile(m, n, g.kchunks, dtype, false), out);
+    return UNIT_OK;
+}
+
+int unit_conv2d_i8(const unit_conv2d_desc *d, const int8_t *x, const int8_t *w,
+                   int32_t *y_i32, const unit_requant *rq, int8_t *y_i8,
+                   void *ws, size_t ws_bytes, void *stream)
+{
+    return conv_plain(d, UNIT_I8, x, w, y_i32, rq, y_i8, ws, ws_bytes, stream);
+}
+
+int unit_conv2d_f16(const unit_conv2d_desc *d, const uint16_t *x, const uint16_t *w,
+                    float *y, void *ws, size_t ws_bytes, void *stream)
+{
+    return conv_plain(d, UNIT_F16, x, w, y, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+int unit_matmul_i8(int32_t m, int32_t n, int32_t k, const int8_t *A, int64_t lda,
+                   const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc,
+                   void *ws, size_t ws_bytes, void *stream)
+{
+    return matmul_any(UNIT_I8, m, n, k, A, lda, B, ldb, C, ldc, ws, ws_bytes, stream);
+}
+
+int unit_matmul_f16(int32_t m, int32_t n, int32_t k, const uint16_t *A, int64_t lda,
+                    const uint16_t *B, int64_t ldb, float *C, int64_t ldc,
+                    void *ws, size_t ws_bytes, void *stream)
+{
+    return matmul_any(UNIT_F16, m, n, k, A, lda, B, ldb, C, ldc, ws, ws_bytes, stream);
+}
+
+static int pack_act_any(int dtype, int32_t n, int32_t c, int32_t h, int32_t w, const void *x,
+                        void *xp, size_t bytes, void *stream)
+{
+    size_t need = unit_packed_act_bytes(n, c, h, w, dtype);
+    if (!need || !x || !xp) return UNIT_EINVAL;
+    if (bytes < need) return UNIT_EWORKSPACE;
+    if (!aligned16(xp)) return UNIT_EINVAL;
+    UNIT_HIP(launch_pack_act(dtype, n, c, h, w, x, xp, static_cast<hipStream_t>(stream)));
+    return UNIT_OK;
+}
+
+int unit_pack_act_i8(int32_t n, int32_t c, int32_t h, int32_t w, const int8_t *x,
+                     void *xp, size_t bytes, void *stream)
+{
+    return pack_act_any(UNIT_I8, n, c, h, w, x, xp, bytes, stream);
+}
+
+int unit_pack_act_f16(int32_t n, int32_t c, int32_t h, int32_t w, const uint16_t *x,
+                      void *xp, size_t bytes, void *stream)
+{
+    return pack_act_any(UNIT_F16, n, c, h, w, x, xp, bytes, stream);
+}
+
+static int pack_w_any(int dtype, const unit_conv2d_desc *d, const void *w, void *wp, size_t bytes, void *stream)
+{
+    size_t need = unit_packed_weights_bytes(d, dtype);
+    if (!need || !w || !wp) return UNIT_EINVAL;
+    if (bytes < need) return UNIT_EWORKSPACE;
+    if (!aligned16(wp)) return UNIT_EINVAL;
+    UNIT_HIP(launch_pack_weights(dtype, d->k, d->c, d->r, d->s, w, wp, static_cast<hipStream_t>(stream)));
+    return UNIT_OK;
+}
+
+int unit_pack_weights_i8(const unit_conv2d_desc *d, const int8_t *w, void *wp, size_t bytes, void *stream)
+{
+    return pack_w_any(UNIT_I8, d, w, wp, bytes, stream);
+}
+
+int unit_pack_weights_f16(const unit_conv2d_desc *d, const uint16_t *w, void *wp, size_t bytes, void *stream)
+{
+    return pack_w_any(UNIT_F16, d, w, wp, bytes, stream);
+}
+
+int unit_unpack_act_i8(int32_t n, int32_t c, int32_t h, int32_t w, const void *xp, int8_t *x, void *stream)
+{
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || !xp || !x) return UNIT_EINVAL;
+    UNIT_HIP(launch_unpack_act_i8(n, c, h, w, xp, x, static_cast<hipStream_t>(stream)));
+    return UNIT_OK;
+}
+
+int unit_conv2d_packed_i8(const unit_conv2d_desc *d, const void *xp, const void *wp,
+                          int32_t *y_i32, const unit_requant *rq, int8_t *y_i8, void *y_packed,
+                          void *ws, size_t ws_bytes, void *stream)
+{
+    return conv_packed(d, UNIT_I8, xp, wp, y_i32, rq, y_i8, y_packed, ws, ws_bytes, stream);
+}
+
+int unit_conv2d_packed_f16(const unit_conv2d_desc *d, const void *xp, const void *wp,
+                           float *y, void *ws, size_t ws_bytes, void *stream)
+{
+    return conv_packed(d, UNIT_F16, xp, wp, y, nullptr, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+int unit_maxpool_packed_i8(int32_t n, int32_t c, int32_t h, int32_t w,
+                           int32_t window, int32_t stride, int32_t pad,
+                           const void *xp, void *yp, void *stream)
+{
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || window <= 0 || stride <= 0 || pad < 0 || !xp || !yp)
+        return UNIT_EINVAL;
+    if (pad >= window || h + 2 * pad < window || w + 2 * pad < window) return UNIT_EINVAL;
+    if (!aligned16(xp) || !aligned16(yp)) return UNIT_EINVAL;
+    int p = (h + 2 * pad - window) / stride + 1, q = (w + 2 * pad - window) / stride + 1;
+    UNIT_HIP(launch_maxpool_packed_i8(n, pad_channels(c, UNIT_I8), h, w, window, stride, pad, p, q,
+                                      xp, yp, static_cast<hipStream_t>(stream)));
+    return UNIT_OK;
+}
+
+int unit_global_avgpool_packed_i8(int32_t n, int32_t c, int32_t h, int32_t w,
+                                  const void *xp, const float *scale, int8_t *y, void *stream)
+{
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || !xp || !scale || !y) return UNIT_EINVAL;
+    if ((long)h * w > 16777216L) return UNIT_EOVERFLOW;
+    UNIT_HIP(launch_avgpool_packed_i8(n, c, pad_channels(c, UNIT_I8), h * w, xp, scale, y,
+                                      static_cast<hipStream_t>(stream)));
+    return UNIT_OK;
+}
+
+int unit_widen_residual_i8(int32_t n, int32_t c, int32_t h, int32_t w,
+                           const void *xp, int32_t mult, int32_t *residual, void *stream)
+{
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || !xp || !residual) return UNIT_EINVAL;
+    UNIT_HIP(launch_widen_residual_i8(n, c, pad_channels(c, UNIT_I8), h * w, xp, mult, residual,
+                                      static_cast<hipStream_t>(stream)));
+    return UNIT_OK;
+}
+
+}  // extern "C"

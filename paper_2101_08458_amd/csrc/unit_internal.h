@@ -1,0 +1,59 @@
+// Internal host-side declarations shared by the API translation unit and the kernel
+// translation units.  Nothing here is visible at the C boundary.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "igemm.hpp"
+
+namespace unit {
+
+// Tile shapes compiled into the library.  Each exists for int8 and fp16, with and
+// without the conv gather.
+struct TileCfg {
+    int bm, bn, bkb;          // workgroup tile rows / cols / reduction bytes per step
+    int wgm, wgn, wgk;        // wave grid
+    int mf;                   // MFMA edge
+};
+enum { NUM_TILES = 6 };
+extern const TileCfg g_tiles[NUM_TILES];
+
+struct TileChoice {
+    int tile;                 // index into g_tiles
+    int split_k;              // grid.z
+    int ksteps_per_split;
+    int workgroups;
+};
+
+// selector.cpp (pure host arithmetic)
+TileChoice select_tile(int rows, int cols, int kchunks, int dtype, bool conv, bool allow_split = true);
+
+// launchers (kernels_*.hip).  All return hipError_t from the launch.
+hipError_t launch_igemm(int dtype, bool conv, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
+
+hipError_t launch_pack_act(int dtype, int n, int c, int h, int w, const void *x, void *xp, hipStream_t st);
+hipError_t launch_pack_weights(int dtype, int k, int c, int r, int s, const void *w, void *wp, hipStream_t st);
+hipError_t launch_unpack_act_i8(int n, int c, int h, int w, const void *xp, int8_t *x, hipStream_t st);
+hipError_t launch_pad_rows(const void *src, long ld_bytes, int rows, int row_bytes,
+                           void *dst, int dst_row_bytes, hipStream_t st);
+
+struct ReduceArgs {
+    const void *partials;  int nsplit;  long split_stride;      // elements
+    int dtype;
+    long total;                                                  // n*k*pq output elements
+    int K, PQ;                                                   // channel = (idx / PQ) % K
+    void *out;                                                   // int32 / float or NULL
+    int epi;  const float *scale;  const int32_t *bias;  const int32_t *residual;  int relu;
+    int8_t *out_i8;  int8_t *out_packed;  int packed_ld;
+};
+hipError_t launch_splitk_reduce(const ReduceArgs &a, hipStream_t st);
+
+hipError_t launch_maxpool_packed_i8(int n, int cp, int h, int w, int window, int stride, int pad,
+                                    int p, int q, const void *x, void *y, hipStream_t st);
+hipError_t launch_avgpool_packed_i8(int n, int c, int cp, int hw, const void *x, const float *scale,
+                                    int8_t *y, hipStream_t st);
+hipError_t launch_widen_residual_i8(int n, int c, int cp, int hw, const void *x, int mult,
+                                    int32_t *res, hipStream_t st);
+
+}  // namespace unit

@@ -1,0 +1,73 @@
+"""Helpers shared by the GPU parity tests: device upload, case announcement, selector
+overrides, and the fp16 error metric."""
+import contextlib
+import os
+import sys
+
+import numpy as np
+
+
+def announce(*what):
+    """Name the case before the GPU step so a fault can be attributed."""
+    print("[gpu-case]", *what, flush=True)
+    sys.stdout.flush()
+
+
+def dev(a):
+    import torch
+    if a.dtype == np.uint16:
+        a = a.view(np.int16)
+    return torch.from_numpy(np.ascontiguousarray(a)).to("cuda:0")
+
+
+def host(t):
+    return t.cpu().numpy()
+
+
+@contextlib.contextmanager
+def forced(tile=None, split=None):
+    """Override the selector through its environment knobs for the duration of a block."""
+    old = {k: os.environ.get(k) for k in ("UNIT_TILE", "UNIT_SPLITK")}
+    try:
+        for k, v in (("UNIT_TILE", tile), ("UNIT_SPLITK", split)):
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = str(v)
+        yield
+    finally:
+        for k, v in old.items():
+            if v is None:
+                os.environ.pop(k, None)
+            else:
+                os.environ[k] = v
+
+
+def f16_rel_err(got, ref, kred):
+    """max |got-ref| / max(|ref|, tau).
+
+    Two fp32 summation orders of the same kred exact products differ by a random-walk
+    rounding error of about sqrt(kred) * 2^-24 * rms(ref), whatever the implementation, so a
+    relative error is only meaningful for |ref| well above that.  tau puts the floor at
+    rms(ref) * max(1e-3, 4000 * sqrt(kred) * 2^-24): below tau the check becomes the
+    absolute bound 1e-3 * tau = 4 * sqrt(kred) * 2^-24 * rms(ref).
+    """
+    ref64 = ref.astype(np.float64)
+    rms = float(np.sqrt(np.mean(ref64 ** 2)))
+    tau = rms * max(1e-3, 4000.0 * np.sqrt(kred) * 2.0 ** -24) + 1e-30
+    return float(np.max(np.abs(got.astype(np.float64) - ref64) / np.maximum(np.abs(ref64), tau)))
+
+
+def same(got, exp, what=""):
+    """Exact equality with a short mismatch report (never dumps the arrays)."""
+    got, exp = np.asarray(got), np.asarray(exp)
+    if got.shape != exp.shape:
+        print(f"[mismatch] {what}: shape {got.shape} vs {exp.shape}", flush=True)
+        return False
+    bad = np.flatnonzero(got.reshape(-1) != exp.reshape(-1))
+    if bad.size:
+        i = bad[:5]
+        print(f"[mismatch] {what}: {bad.size}/{got.size} differ; first at {i.tolist()} "
+              f"got {got.reshape(-1)[i].tolist()} exp {exp.reshape(-1)[i].tolist()}", flush=True)
+        return False
+    return True

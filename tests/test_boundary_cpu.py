@@ -1,0 +1,89 @@
+"""Host-side checks of the C boundary that need no GPU: the library loads, exports every
+declared symbol, answers the size / selector queries, and rejects bad arguments before
+any HIP call (all error paths return ahead of the first launch)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2101_08458_amd import unit, workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(unit.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return unit.load()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "unit.h")).read()
+    declared = set(re.findall(r"\b(unit_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(unit.EXPORTS)
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert unit.unit_version() >= 100
+    assert unit.unit_status_str(unit.UNIT_EOVERFLOW).startswith("int8 reduction")
+
+
+def test_out_dims_and_sizes(lib):
+    for sh in wl.resnet50_convs() + wl.TABLE1:
+        d = unit.conv_desc(1, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
+        assert unit.unit_conv2d_out_dims(d) == wl.out_hw(sh)
+    assert unit.unit_packed_act_bytes(1, 3, 224, 224, unit.UNIT_I8) == 224 * 224 * 16
+    assert unit.unit_packed_act_bytes(2, 24, 5, 5, unit.UNIT_F16) == (2 * 25 * 24 * 2 + 255) // 256 * 256
+    d = unit.conv_desc(1, 64, 56, 56, 64, 3, 3, 1, 1)
+    assert unit.unit_packed_weights_bytes(d, unit.UNIT_I8) == 64 * 9 * 64
+    assert unit.unit_conv2d_workspace(d, unit.UNIT_I8) >= 56 * 56 * 64 + 64 * 9 * 64
+    assert unit.unit_packed_act_bytes(0, 3, 4, 4, unit.UNIT_I8) == 0
+
+
+def test_selector_answers(lib):
+    info = unit.unit_select_matmul(4096, 4096, 4096, unit.UNIT_I8)
+    assert info.block_m * info.block_n >= 128 * 128 and info.split_k == 1
+    assert info.workgroups == (4096 // info.block_m) * (4096 // info.block_n)
+    # a deep, small layer must be split across workgroups (7x7 output, reduction 4608)
+    d = unit.conv_desc(1, 512, 7, 7, 512, 3, 3, 1, 1)
+    info = unit.unit_select_conv2d(d, unit.UNIT_I8)
+    assert info.split_k > 1 and info.workgroups >= 128
+    assert unit.unit_conv2d_packed_workspace(d, unit.UNIT_I8) >= info.split_k * 512 * 49 * 4
+
+
+def test_error_paths_return_before_launch(lib):
+    d = unit.conv_desc(1, 8, 8, 8, 8, 3, 3, 1, 1)
+    null = None
+    fake = 0x1000  # never dereferenced: every call below must fail validation first
+    st = 0
+    f = lib.unit_conv2d_i8
+    assert f(None, fake, fake, fake, None, null, fake, 1 << 20, st) == unit.UNIT_EINVAL
+    assert f(ctypes.byref(d), null, fake, fake, None, null, fake, 1 << 20, st) == unit.UNIT_EINVAL
+    assert f(ctypes.byref(d), fake, fake, null, None, null, fake, 1 << 20, st) == unit.UNIT_EINVAL
+    assert f(ctypes.byref(d), fake, fake, fake, None, null, null, 0, st) == unit.UNIT_EWORKSPACE
+    assert f(ctypes.byref(d), fake, fake, fake, None, null, fake, 16, st) == unit.UNIT_EWORKSPACE
+    # requant without an int8 output / without scale
+    rq = unit.unit_requant(None, None, None, 0)
+    assert f(ctypes.byref(d), fake, fake, fake, ctypes.byref(rq), fake, fake, 1 << 20, st) == unit.UNIT_EINVAL
+    bad = unit.conv_desc(1, 8, 2, 2, 8, 3, 3, 1, 0)          # window larger than the image
+    assert f(ctypes.byref(bad), fake, fake, fake, None, null, fake, 1 << 20, st) == unit.UNIT_EINVAL
+    neg = unit.conv_desc(1, 8, 8, 8, 8, 3, 3, 0, 1)          # stride 0
+    assert f(ctypes.byref(neg), fake, fake, fake, None, null, fake, 1 << 20, st) == unit.UNIT_EINVAL
+    deep = unit.conv_desc(1, 14564, 8, 8, 8, 3, 3, 1, 1)     # 14564*9 = 131076 > 131071
+    assert f(ctypes.byref(deep), fake, fake, fake, None, null, fake, 1 << 30, st) == unit.UNIT_EOVERFLOW
+    ok_deep = unit.conv_desc(1, 14563, 8, 8, 8, 3, 3, 1, 1)  # 131067: allowed for int8 ...
+    assert unit.unit_conv2d_workspace(ok_deep, unit.UNIT_I8) > 0
+    assert unit.unit_conv2d_workspace(deep, unit.UNIT_F16) > 0   # ... and fp16 has no such bound
+
+    g = lib.unit_matmul_i8
+    assert g(0, 4, 4, fake, 4, fake, 4, fake, 4, null, 0, st) == unit.UNIT_EINVAL
+    assert g(4, 4, 16, fake, 8, fake, 16, fake, 4, null, 0, st) == unit.UNIT_EINVAL      # lda < k
+    assert g(4, 4, 16, fake, 16, fake, 16, fake, 2, null, 0, st) == unit.UNIT_EINVAL     # ldc < n
+    assert g(4, 4, 131072, fake, 131072, fake, 131072, fake, 4, null, 0, st) == unit.UNIT_EOVERFLOW
+    assert g(4, 4, 10, fake, 10, fake, 10, fake, 4, null, 0, st) == unit.UNIT_EWORKSPACE  # needs padding space
+    assert g(4, 4, 16, fake + 1, 16, fake, 16, fake, 4, null, 0, st) == unit.UNIT_EINVAL  # misaligned A
+    assert lib.unit_matmul_f16(4, 4, 131072, null, 131072, fake, 131072, fake, 4, null, 0, st) == unit.UNIT_EINVAL
+    assert lib.unit_pack_act_i8(1, 3, 4, 4, fake, fake, 16, st) == unit.UNIT_EWORKSPACE
+    assert lib.unit_maxpool_packed_i8(1, 16, 8, 8, 3, 2, 3, fake, fake, st) == unit.UNIT_EINVAL

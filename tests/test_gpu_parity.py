@@ -1,0 +1,419 @@
+"""GPU parity: libunit (through its C ABI) against the CPU oracle on identical seeded inputs.
+
+int8 paths must be bit-exact; fp16 paths must have max relative error <= 1e-3 (relative to
+max(|ref|, 1e-3*rms(ref))) and stay inside the fp32 summation bound 2*K*2^-24*sum|x||w|.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2101_08458_amd import unit, workloads as wl
+from gpu_util import announce, dev, host, forced, f16_rel_err, same
+
+pytestmark = pytest.mark.gpu
+
+ALL_TILES = [0, 1, 2, 3, 4, 5]
+
+
+def ws_bytes(nbytes):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda:0")
+
+
+# ------------------------------------------------------------------ matmul
+
+def run_matmul_i8(A, B, lda=None, ldb=None, ldc=None):
+    M, K = A.shape
+    N = B.shape[0]
+    lda, ldb, ldc = lda or K, ldb or K, ldc or N
+    Ap = np.zeros((M, lda), np.int8); Ap[:, :K] = A
+    Bp = np.zeros((N, ldb), np.int8); Bp[:, :K] = B
+    Ad, Bd = dev(Ap), dev(Bp)
+    C = torch.full((M, ldc), -7, dtype=torch.int32, device="cuda:0")
+    ws = ws_bytes(unit.unit_matmul_workspace(M, N, K, lda, ldb, unit.UNIT_I8))
+    unit.unit_matmul_i8(M, N, K, Ad, lda, Bd, ldb, C, ldc, ws)
+    torch.cuda.synchronize()
+    return host(C)[:, :N]
+
+
+def run_matmul_f16(A, B):
+    M, K = A.shape
+    N = B.shape[0]
+    Ad, Bd = dev(A), dev(B)
+    C = torch.empty((M, N), dtype=torch.float32, device="cuda:0")
+    ws = ws_bytes(unit.unit_matmul_workspace(M, N, K, K, K, unit.UNIT_F16))
+    unit.unit_matmul_f16(M, N, K, Ad, K, Bd, K, C, N, ws)
+    torch.cuda.synchronize()
+    return host(C)
+
+
+def test_mfma_fragment_layout_probe():
+    """Index-revealing operands: C[m,n] = 64*m + n needs the lane -> (row, col) mapping of
+    the accumulator fragments to be exactly as the epilogue assumes, for every tile shape."""
+    for M, N in [(32, 32), (64, 96), (16, 64)]:
+        K = 64
+        A = np.zeros((M, K), np.int8); A[:, 0] = np.arange(M) % 64; A[:, 1] = 1
+        B = np.zeros((N, K), np.int8); B[:, 0] = 64; B[:, 1] = np.arange(N)
+        # C[m,n] = 64*(m%64) + n
+        exp = 64 * (np.arange(M) % 64)[:, None] + np.arange(N)[None, :]
+        for tile in ALL_TILES:
+            announce("layout probe", M, N, "tile", tile)
+            with forced(tile=tile, split=1):
+                got = run_matmul_i8(A, B)
+            assert same(got, exp), f"tile {tile} M={M} N={N}"
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 16, 16), (64, 64, 64), (100, 100, 100), (257, 130, 384),
+                                   (1, 1000, 2048), (3, 7, 5), (300, 40, 1040)])
+def test_matmul_i8_parity(M, N, K):
+    A, B = wl.gemm_inputs_i8(M, N, K, 20, M + K)
+    ref = oracle.matmul_i8(A, B)
+    announce("matmul_i8", M, N, K, "auto")
+    assert same(run_matmul_i8(A, B), ref)
+    for tile in ALL_TILES:
+        for split in (1, 3):
+            announce("matmul_i8", M, N, K, "tile", tile, "split", split)
+            with forced(tile=tile, split=split):
+                assert same(run_matmul_i8(A, B), ref), (tile, split)
+
+
+def test_matmul_i8_leading_dimensions():
+    A, B = wl.gemm_inputs_i8(70, 50, 96, 21)
+    ref = oracle.matmul_i8(A, B)
+    announce("matmul_i8 ld aligned")
+    assert same(run_matmul_i8(A, B, lda=128, ldb=112, ldc=64), ref)
+    announce("matmul_i8 ld unaligned")
+    assert same(run_matmul_i8(A, B, lda=101, ldb=97, ldc=51), ref)
+
+
+def test_matmul_i8_extremes_and_identity():
+    K = 4096
+    A = np.full((33, K), -128, np.int8)
+    B = np.full((17, K), -128, np.int8)
+    announce("matmul_i8 extreme fill")
+    assert np.all(run_matmul_i8(A, B) == K * 16384)
+    g = wl.rng(22)
+    Bm = wl.int8_weights(g, (48, 64))
+    announce("matmul_i8 identity")
+    assert same(run_matmul_i8(np.eye(64, dtype=np.int8), Bm), Bm.T.astype(np.int32))
+
+
+@pytest.mark.parametrize("M,N,K", [(16, 16, 16), (100, 100, 100), (257, 130, 392), (2, 1000, 512)])
+def test_matmul_f16_parity(M, N, K):
+    A, B = wl.gemm_inputs_f16(M, N, K, 23, M + K)
+    ref = oracle.matmul_f16(A, B)
+    truth, mag = oracle.matmul_f16_f64(A, B)
+    for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 2)]:
+        announce("matmul_f16", M, N, K, "tile", tile, "split", split)
+        with forced(tile=tile, split=split):
+            got = run_matmul_f16(A, B)
+        assert f16_rel_err(got, ref, K) <= 1e-3, (tile, split)
+        assert np.all(np.abs(got - truth) <= 2 * K * 2.0 ** -24 * mag + 1e-30), (tile, split)
+
+
+def test_matmul_f16_exact_cases():
+    """Small integers: every partial sum is exact, so any summation order gives the same bits."""
+    g = wl.rng(24)
+    Ai = g.integers(-8, 9, size=(70, 200))
+    Bi = g.integers(-8, 9, size=(90, 200))
+    announce("matmul_f16 exact ints")
+    got = run_matmul_f16(wl.f16_bits(Ai), wl.f16_bits(Bi))
+    assert same(got.astype(np.int64), Ai @ Bi.T)
+    # subnormal inputs must not be flushed: 2^-24 * 1024 * K
+    A = np.full((16, 64), 0x0001, np.uint16)
+    B = wl.f16_bits(np.full((16, 64), 1024.0))
+    announce("matmul_f16 subnormal")
+    got = run_matmul_f16(A, B)
+    assert np.all(got == 64 * 1024.0 * 2.0 ** -24)
+
+
+def test_matmul_i8_full_size_sampled():
+    """4096^3 in the launch configuration the benchmark times; sampled rows and columns."""
+    M = N = K = 4096
+    A, B = wl.gemm_inputs_i8(M, N, K)
+    announce("matmul_i8 4096^3")
+    got = run_matmul_i8(A, B)
+    g = wl.rng(25)
+    rows = np.unique(np.concatenate([[0, 255, 256, 4095], g.integers(0, M, 12)]))
+    cols = np.unique(np.concatenate([[0, 255, 256, 4095], g.integers(0, N, 12)]))
+    assert same(got[rows], oracle.matmul_i8(np.ascontiguousarray(A[rows]), B))
+    assert same(got[:, cols], oracle.matmul_i8(A, np.ascontiguousarray(B[cols])))
+    # property that holds at any size: row sums of C equal A times the column-sum vector of B
+    colsum = B.astype(np.int64).sum(axis=0)
+    assert same(got.astype(np.int64).sum(axis=1), A.astype(np.int64) @ colsum)
+
+
+def test_matmul_f16_full_size_sampled():
+    M = N = K = 4096
+    A, B = wl.gemm_inputs_f16(M, N, K)
+    announce("matmul_f16 4096^3")
+    got = run_matmul_f16(A, B)
+    rows = np.array([0, 1, 255, 256, 2047, 4095])
+    ref = oracle.matmul_f16(np.ascontiguousarray(A[rows]), B)
+    truth, mag = oracle.matmul_f16_f64(np.ascontiguousarray(A[rows]), B)
+    assert f16_rel_err(got[rows], ref, K) <= 1e-3
+    assert np.all(np.abs(got[rows] - truth) <= 2 * K * 2.0 ** -24 * mag)
+
+
+# ------------------------------------------------------------------ conv2d
+
+def run_conv_i8(sh, n, x, w, rq=None):
+    d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
+    p, q = unit.unit_conv2d_out_dims(d)
+    ws = ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_I8))
+    xd, wd = dev(x), dev(w)
+    y32 = torch.full((n, sh.k, p, q), -7, dtype=torch.int32, device="cuda:0")
+    unit.unit_conv2d_i8(d, xd, wd, y32, None, None, ws)
+    torch.cuda.synchronize()
+    return host(y32)
+
+
+def run_conv_f16(sh, n, x, w):
+    d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
+    p, q = unit.unit_conv2d_out_dims(d)
+    ws = ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_F16))
+    y = torch.empty((n, sh.k, p, q), dtype=torch.float32, device="cuda:0")
+    unit.unit_conv2d_f16(d, dev(x), dev(w), y, ws)
+    torch.cuda.synchronize()
+    return host(y)
+
+
+SMALL_CONVS = [
+    (wl.ConvShape(2, 4, 4, 2, 3, 3, 1, 1), 1),
+    (wl.ConvShape(3, 9, 11, 5, 3, 3, 2, 1), 2),
+    (wl.ConvShape(20, 13, 9, 33, 1, 1, 1, 0), 3),
+    (wl.ConvShape(16, 14, 14, 8, 1, 1, 2, 0), 1),
+    (wl.ConvShape(3, 23, 23, 4, 7, 7, 2, 3), 1),
+    (wl.ConvShape(40, 10, 12, 70, 3, 3, 1, 1), 2),
+    (wl.ConvShape(70, 17, 17, 130, 3, 3, 2, 1), 1),
+]
+
+
+@pytest.mark.parametrize("sh,n", SMALL_CONVS)
+def test_conv_i8_small_all_tiles(sh, n):
+    x, w = wl.conv_inputs_i8(sh, n, 30, sh.c)
+    ref = oracle.conv2d_i8(x, w, (sh.stride,) * 2, (sh.pad,) * 2)
+    announce("conv_i8", sh, n, "auto")
+    assert same(run_conv_i8(sh, n, x, w), ref)
+    for tile in ALL_TILES:
+        for split in (1, 2):
+            announce("conv_i8", sh, n, "tile", tile, "split", split)
+            with forced(tile=tile, split=split):
+                assert same(run_conv_i8(sh, n, x, w), ref), (tile, split)
+
+
+def test_conv_i8_asymmetric_geometry():
+    """Different stride / pad / window per axis (the C ABI carries them separately)."""
+    g = wl.rng(31)
+    n, c, h, w_, k, r, s = 2, 12, 11, 9, 20, 3, 2
+    x = wl.int8_activations(g, (n, c, h, w_))
+    w = wl.int8_weights(g, (k, c, r, s))
+    ref = oracle.conv2d_i8(x, w, (2, 1), (1, 0))
+    d = unit.unit_conv2d_desc(n, c, h, w_, k, r, s, 2, 1, 1, 0)
+    p, q = unit.unit_conv2d_out_dims(d)
+    y = torch.empty((n, k, p, q), dtype=torch.int32, device="cuda:0")
+    announce("conv_i8 asymmetric")
+    unit.unit_conv2d_i8(d, dev(x), dev(w), y, None, None, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_I8)))
+    torch.cuda.synchronize()
+    assert same(host(y), ref)
+
+
+def test_conv_i8_config1_and_determinism():
+    sh = wl.CONFIG1
+    x, w = wl.conv_inputs_i8(sh, 1, 1)
+    ref = oracle.conv2d_i8(x, w, (1, 1), (1, 1))
+    announce("conv_i8 config 1")
+    first = run_conv_i8(sh, 1, x, w)
+    assert same(first, ref)
+    for rep in range(20):                      # an LDS double-buffer race would show as a mismatch
+        assert same(run_conv_i8(sh, 1, x, w), ref), rep
+    x2 = np.full_like(x, -128); w2 = np.full_like(w, -128)
+    got = run_conv_i8(sh, 1, x2, w2)
+    assert got[0, 0, 5, 5] == 64 * 9 * 16384 and got[0, 0, 0, 0] == 64 * 4 * 16384
+
+
+def test_conv_i8_resnet50_layers_batch1():
+    for idx, (sh, mult) in enumerate(wl.unique_shapes(wl.resnet50_convs())):
+        x, w = wl.conv_inputs_i8(sh, 1, 3, idx)
+        ref = oracle.conv2d_i8(x, w, (sh.stride,) * 2, (sh.pad,) * 2)
+        announce("conv_i8 resnet50", idx, sh)
+        assert same(run_conv_i8(sh, 1, x, w), ref), sh
+
+
+def test_conv_i8_table1_layers():
+    for idx, sh in enumerate(wl.TABLE1):
+        x, w = wl.conv_inputs_i8(sh, 1, 6, idx)
+        ref = oracle.conv2d_i8(x, w, (sh.stride,) * 2, (sh.pad,) * 2)
+        announce("conv_i8 table1", idx + 1, sh)
+        assert same(run_conv_i8(sh, 1, x, w), ref), sh
+
+
+@pytest.mark.parametrize("sh,n", SMALL_CONVS[:6])
+def test_conv_f16_small_all_tiles(sh, n):
+    x, w = wl.conv_inputs_f16(sh, n, 40, sh.c)
+    st, pd = (sh.stride,) * 2, (sh.pad,) * 2
+    ref = oracle.conv2d_f16(x, w, st, pd)
+    truth, mag = oracle.conv2d_f16_f64(x, w, st, pd)
+    kred = sh.c * sh.r * sh.s
+    for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 2)]:
+        announce("conv_f16", sh, n, "tile", tile, "split", split)
+        with forced(tile=tile, split=split):
+            got = run_conv_f16(sh, n, x, w)
+        assert f16_rel_err(got, ref, kred) <= 1e-3, (tile, split)
+        assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), (tile, split)
+
+
+def test_conv_f16_power_of_two_inputs_bit_exact():
+    g = wl.rng(41)
+    sh = wl.ConvShape(24, 9, 9, 40, 3, 3, 1, 1)
+    x = wl.f16_bits(g.choice([-1.0, 1.0], size=(1, 24, 9, 9)) * 2.0 ** g.integers(-3, 4, size=(1, 24, 9, 9)))
+    w = wl.f16_bits(g.choice([-1.0, 1.0], size=(40, 24, 3, 3)) * 2.0 ** g.integers(-3, 4, size=(40, 24, 3, 3)))
+    ref = oracle.conv2d_f16(x, w, (1, 1), (1, 1))
+    announce("conv_f16 power-of-two")
+    got = run_conv_f16(sh, 1, x, w)
+    assert same(got.view(np.uint32), ref.view(np.uint32))
+    announce("conv_f16 determinism")
+    x2, w2 = wl.conv_inputs_f16(sh, 1, 42)
+    a = run_conv_f16(sh, 1, x2, w2)
+    with forced(split=3):
+        b1 = run_conv_f16(sh, 1, x2, w2)
+        b2 = run_conv_f16(sh, 1, x2, w2)
+    assert same(a.view(np.uint32), run_conv_f16(sh, 1, x2, w2).view(np.uint32))
+    assert same(b1.view(np.uint32), b2.view(np.uint32))
+
+
+def sampled_conv_check_f16(sh, n, x, w, got, samples, g):
+    """Compare sampled outputs with the oracle run on the receptive field of each."""
+    P, Q = wl.out_hw(sh)
+    kred = sh.c * sh.r * sh.s
+    worst = 0.0
+    refs, gots = [], []
+    for _ in range(samples):
+        ni, k, p, q = int(g.integers(n)), int(g.integers(sh.k)), int(g.integers(P)), int(g.integers(Q))
+        patch = np.zeros((1, sh.c, sh.r, sh.s), np.uint16)
+        for r in range(sh.r):
+            for s in range(sh.s):
+                h, ww = p * sh.stride + r - sh.pad, q * sh.stride + s - sh.pad
+                if 0 <= h < sh.h and 0 <= ww < sh.w:
+                    patch[0, :, r, s] = x[ni, :, h, ww]
+        ref = oracle.conv2d_f16(patch, np.ascontiguousarray(w[k:k + 1]))[0, 0, 0, 0]
+        truth, mag = oracle.conv2d_f16_f64(patch, np.ascontiguousarray(w[k:k + 1]))
+        assert abs(got[ni, k, p, q] - truth[0, 0, 0, 0]) <= 2 * kred * 2.0 ** -24 * mag[0, 0, 0, 0] + 1e-30
+        refs.append(ref); gots.append(got[ni, k, p, q])
+    return f16_rel_err(np.array(gots), np.array(refs), kred)
+
+
+def test_conv_f16_resnet50_layers_batch16_sampled():
+    g = wl.rng(43)
+    for idx, (sh, mult) in enumerate(wl.unique_shapes(wl.resnet50_convs())):
+        if idx % 3 != 0 and sh.r == 1:
+            continue                                  # every 3x3 / 7x7 layer, a third of the 1x1 ones
+        x, w = wl.conv_inputs_f16(sh, 16, 4, idx)
+        announce("conv_f16 resnet50 b16", idx, sh)
+        got = run_conv_f16(sh, 16, x, w)
+        assert np.all(np.isfinite(got))
+        assert sampled_conv_check_f16(sh, 16, x, w, got, 48, g) <= 1e-3, sh
+
+
+# ------------------------------------------------------------------ fused epilogue / packed path
+
+def test_requant_epilogue_all_paths():
+    g = wl.rng(50)
+    for sh, n in [(wl.ConvShape(24, 12, 12, 40, 3, 3, 1, 1), 2), (wl.ConvShape(32, 9, 9, 19, 1, 1, 1, 0), 1)]:
+        x, w = wl.conv_inputs_i8(sh, n, 50, sh.c)
+        st, pd = (sh.stride,) * 2, (sh.pad,) * 2
+        acc = oracle.conv2d_i8(x, w, st, pd)
+        bias = g.integers(-5000, 5000, size=sh.k).astype(np.int32)
+        res = g.integers(-30000, 30000, size=acc.shape).astype(np.int32)
+        scale = (120.0 / np.abs(acc).max(axis=(0, 2, 3)).clip(1) * g.uniform(0.5, 1.0, sh.k)).astype(np.float32)
+        d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
+        p, q = unit.unit_conv2d_out_dims(d)
+        xp = ws_bytes(unit.unit_packed_act_bytes(n, sh.c, sh.h, sh.w, unit.UNIT_I8))
+        wp = ws_bytes(unit.unit_packed_weights_bytes(d, unit.UNIT_I8))
+        unit.unit_pack_act_i8(n, sh.c, sh.h, sh.w, dev(x), xp)
+        unit.unit_pack_weights_i8(d, dev(w), wp)
+        sd, bd, rd = dev(scale), dev(bias), dev(res)
+        kp = (sh.k + 15) // 16 * 16
+        for use_bias, use_res, relu in [(0, 0, 0), (1, 0, 1), (0, 1, 1), (1, 1, 0), (1, 1, 1)]:
+            exp = oracle.requant(acc, scale, bias if use_bias else None, res if use_res else None, relu)
+            rq = unit.make_requant(sd, bd if use_bias else None, rd if use_res else None, relu)
+            for tile, split in [(None, None), (2, 1), (2, 2), (3, 1), (4, 3), (5, 1), (1, 1)]:
+                announce("requant", sh, "bias", use_bias, "res", use_res, "relu", relu, "tile", tile, "split", split)
+                y8 = torch.full((n, sh.k, p, q), 99, dtype=torch.int8, device="cuda:0")
+                y32 = torch.full((n, sh.k, p, q), -7, dtype=torch.int32, device="cuda:0")
+                ypk = torch.full((n, p, q, kp), 99, dtype=torch.int8, device="cuda:0")
+                with forced(tile=tile, split=split):
+                    ws = ws_bytes(unit.unit_conv2d_packed_workspace(d, unit.UNIT_I8))
+                    unit.unit_conv2d_packed_i8(d, xp, wp, y32, rq, y8, ypk, ws)
+                torch.cuda.synchronize()
+                assert same(host(y8), exp)
+                assert same(host(y32), acc)
+                pk = host(ypk)
+                assert same(pk[..., :sh.k].transpose(0, 3, 1, 2), exp)
+                assert np.all(pk[..., sh.k:] == 0)
+                # the packed output unpacks to the same NCHW tensor
+                back = torch.empty((n, sh.k, p, q), dtype=torch.int8, device="cuda:0")
+                unit.unit_unpack_act_i8(n, sh.k, p, q, ypk, back)
+                torch.cuda.synchronize()
+                assert same(host(back), exp)
+
+
+def test_requant_epilogue_extreme_accumulators():
+    """|acc| up to 4608*2^14 ~ 7.5e7 > 2^24: the int32 -> fp32 conversion rounds, on both sides alike."""
+    sh = wl.ConvShape(512, 5, 5, 16, 3, 3, 1, 1)
+    g = wl.rng(51)
+    x = g.choice(np.array([-128, 127], np.int8), size=(1, 512, 5, 5))
+    w = g.choice(np.array([-128, 127], np.int8), size=(16, 512, 3, 3))
+    w[0] = -128; x[0, :, 1:4, 1:4] = -128           # one output reaches 4608 * 16384 exactly
+    acc = oracle.conv2d_i8(x, w, (1, 1), (1, 1))
+    assert acc.max() == 4608 * 16384
+    scale = np.full(16, 127.0 / 7.5e7, np.float32)
+    scale[1] = 3.3e-6
+    exp = oracle.requant(acc, scale)
+    d = unit.conv_desc(1, 512, 5, 5, 16, 3, 3, 1, 1)
+    y8 = torch.empty((1, 16, 5, 5), dtype=torch.int8, device="cuda:0")
+    sd, xd, wd = dev(scale), dev(x), dev(w)          # keep the device tensors alive across the call
+    rq = unit.make_requant(sd)
+    announce("requant extreme")
+    unit.unit_conv2d_i8(d, xd, wd, None, rq, y8, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_I8)))
+    torch.cuda.synchronize()
+    assert same(host(y8), exp)
+
+
+def test_pack_roundtrip_and_glue_ops():
+    g = wl.rng(52)
+    n, c, h, w_ = 2, 37, 13, 11
+    x = wl.int8_weights(g, (n, c, h, w_))
+    xp = ws_bytes(unit.unit_packed_act_bytes(n, c, h, w_, unit.UNIT_I8))
+    announce("pack/unpack")
+    unit.unit_pack_act_i8(n, c, h, w_, dev(x), xp)
+    back = torch.empty((n, c, h, w_), dtype=torch.int8, device="cuda:0")
+    unit.unit_unpack_act_i8(n, c, h, w_, xp, back)
+    torch.cuda.synchronize()
+    assert same(host(back), x)
+    cp = 48
+    raw = host(xp)[: n * h * w_ * cp].reshape(n, h, w_, cp)
+    assert same(raw[..., :c].view(np.int8).transpose(0, 3, 1, 2), x) and np.all(raw[..., c:] == 0)
+
+    announce("maxpool")
+    p, q = oracle.out_dim(h, 3, 2, 1), oracle.out_dim(w_, 3, 2, 1)
+    yp = ws_bytes(unit.unit_packed_act_bytes(n, c, p, q, unit.UNIT_I8))
+    unit.unit_maxpool_packed_i8(n, c, h, w_, 3, 2, 1, xp, yp)
+    mp = torch.empty((n, c, p, q), dtype=torch.int8, device="cuda:0")
+    unit.unit_unpack_act_i8(n, c, p, q, yp, mp)
+    torch.cuda.synchronize()
+    assert same(host(mp), oracle.maxpool_i8(x))
+
+    announce("avgpool")
+    scale = g.uniform(0.002, 0.02, c).astype(np.float32)
+    ya = torch.full((n, cp), 99, dtype=torch.int8, device="cuda:0")
+    unit.unit_global_avgpool_packed_i8(n, c, h, w_, xp, dev(scale), ya)
+    torch.cuda.synchronize()
+    assert same(host(ya)[:, :c], oracle.global_sumpool_requant_i8(x, scale))
+    assert np.all(host(ya)[:, c:] == 0)
+
+    announce("widen residual")
+    res = torch.empty((n, c, h, w_), dtype=torch.int32, device="cuda:0")
+    unit.unit_widen_residual_i8(n, c, h, w_, xp, 64, res)
+    torch.cuda.synchronize()
+    assert same(host(res), oracle.widen_scale_i8(x, 64))
