@@ -1,0 +1,292 @@
+#!/usr/bin/env python3
+"""Benchmark of libunit on one MI355X.
+
+Default workload (the one the headline metric is quoted on): the 53 conv layers of a
+ResNet-50-shaped network at batch 1, int8 x int8 -> int32, each layer run through the whole
+hot path (pack_act NCHW -> blocked NHWC, tile selection, implicit-GEMM MFMA kernel, split
+reduce where selected, NCHW int32 epilogue).  One "step" is one pass over all 53 layers;
+`value` is 2*MACs / time in TOPS and `ms_per_step` is the ResNet-50-shape batch-1 time.
+
+The same JSON line carries `roofline` (dominant kernel, HIP-event timed), `cpu_baseline`
+(the CPU oracle on a bounded sample) and `others` (the compute-bound configurations:
+GEMM 4096^3 and the large conv, int8 and fp16, each with its own MFMA roofline fraction).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"i8": 5000.0, "f16": 2500.0}        # dense MFMA TOPS / TFLOPS (published MI355X)
+HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet50_i8_b1",
+                    choices=["resnet50_i8_b1", "gemm_i8_4096", "large_conv_i8", "gemm_f16_4096",
+                             "large_conv_f16", "resnet50_f16_b16"])
+    ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    return ap.parse_args()
+
+
+class ConvCase:
+    """Device-resident buffers and launch closures for one conv layer."""
+
+    def __init__(self, torch, unit, wl, sh, n, dtype, config_id, layer_id):
+        self.sh, self.n, self.dtype = sh, n, dtype
+        self.unit = unit
+        dev = "cuda:0"
+        i8 = dtype == "i8"
+        self.ut = unit.UNIT_I8 if i8 else unit.UNIT_F16
+        x, w = (wl.conv_inputs_i8 if i8 else wl.conv_inputs_f16)(sh, n, config_id, layer_id)
+        tdt = torch.int8 if i8 else torch.int16
+        self.x = torch.from_numpy(x.view(np.int8 if i8 else np.int16)).to(dev)
+        wd = torch.from_numpy(w.view(np.int8 if i8 else np.int16)).to(dev)
+        self.d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
+        p, q = unit.unit_conv2d_out_dims(self.d)
+        self.p, self.q = p, q
+        self.xp = torch.empty(unit.unit_packed_act_bytes(n, sh.c, sh.h, sh.w, self.ut), dtype=torch.uint8, device=dev)
+        self.wp = torch.empty(unit.unit_packed_weights_bytes(self.d, self.ut), dtype=torch.uint8, device=dev)
+        (unit.unit_pack_weights_i8 if i8 else unit.unit_pack_weights_f16)(self.d, wd, self.wp)
+        self.y = torch.empty((n, sh.k, p, q), dtype=torch.int32 if i8 else torch.float32, device=dev)
+        self.ws = torch.empty(max(unit.unit_conv2d_packed_workspace(self.d, self.ut), 256), dtype=torch.uint8, device=dev)
+        es = 1 if i8 else 2
+        self.macs = wl.macs(sh, n)
+        self.bytes = (x.size + w.size) * es + self.y.numel() * 4      # each operand once, output once
+        self.info = unit.unit_select_conv2d(self.d, self.ut)
+        self.pack()
+        torch.cuda.synchronize()
+
+    def pack(self):
+        u, sh = self.unit, self.sh
+        (u.unit_pack_act_i8 if self.dtype == "i8" else u.unit_pack_act_f16)(self.n, sh.c, sh.h, sh.w, self.x, self.xp)
+
+    def conv(self):
+        u = self.unit
+        if self.dtype == "i8":
+            u.unit_conv2d_packed_i8(self.d, self.xp, self.wp, self.y, None, None, None, self.ws)
+        else:
+            u.unit_conv2d_packed_f16(self.d, self.xp, self.wp, self.y, self.ws)
+
+    def api(self):
+        self.pack()
+        self.conv()
+
+
+class GemmCase:
+    def __init__(self, torch, unit, wl, m, n, k, dtype):
+        dev = "cuda:0"
+        i8 = dtype == "i8"
+        self.unit, self.dtype, self.m, self.n, self.k = unit, dtype, m, n, k
+        A, B = (wl.gemm_inputs_i8 if i8 else wl.gemm_inputs_f16)(m, n, k)
+        self.A = torch.from_numpy(A.view(np.int8 if i8 else np.int16)).to(dev)
+        self.B = torch.from_numpy(B.view(np.int8 if i8 else np.int16)).to(dev)
+        self.C = torch.empty((m, n), dtype=torch.int32 if i8 else torch.float32, device=dev)
+        ut = unit.UNIT_I8 if i8 else unit.UNIT_F16
+        self.ws = torch.empty(max(unit.unit_matmul_workspace(m, n, k, k, k, ut), 256), dtype=torch.uint8, device=dev)
+        self.macs = m * n * k
+        self.bytes = (m * k + n * k) * (1 if i8 else 2) + m * n * 4
+        self.info = unit.unit_select_matmul(m, n, k, ut)
+        torch.cuda.synchronize()
+
+    def run(self):
+        u = self.unit
+        f = u.unit_matmul_i8 if self.dtype == "i8" else u.unit_matmul_f16
+        f(self.m, self.n, self.k, self.A, self.k, self.B, self.k, self.C, self.n, self.ws)
+
+
+def event_ms(torch, fn, reps, warm=3):
+    """Average duration of fn() launches on torch's current stream (the stream the library
+    launches on), from one HIP event pair around `reps` back-to-back calls."""
+    for _ in range(warm):
+        fn()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        fn()
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
+def wall_ms(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def tile_str(info):
+    return (f"{info.block_m}x{info.block_n}x{info.block_k_bytes}B waves {info.waves_m}x{info.waves_n}x{info.waves_k} "
+            f"mfma{info.mfma} split{info.split_k} wg{info.workgroups}")
+
+
+def mfma_roofline(dtype, macs, ms, traffic=None):
+    tops = 2.0 * macs / (ms * 1e-3) / 1e12
+    return {"bound": "mfma", "achieved": round(tops, 2), "peak": PEAK[dtype],
+            "unit": "TOP/s" if dtype == "i8" else "TFLOP/s", "frac": round(tops / PEAK[dtype], 4), "traffic": traffic}
+
+
+def cpu_baseline(wl, budget_s=12.0):
+    """The CPU oracle, as it stands, on the first layers of the same ResNet-50-shaped set
+    until about `budget_s` seconds of host time are used."""
+    import oracle
+    oracle.build()
+    macs, secs, used = 0, 0.0, 0
+    for idx, sh in enumerate(wl.resnet50_convs()):
+        x, w = wl.conv_inputs_i8(sh, 1, 3, idx)
+        t0 = time.perf_counter()
+        oracle.conv2d_i8(x, w, (sh.stride,) * 2, (sh.pad,) * 2)
+        secs += time.perf_counter() - t0
+        macs += wl.macs(sh)
+        used += 1
+        if secs > budget_s:
+            break
+    return {"value": round(2.0 * macs / secs / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
+            "kind": "oracle", "sample": f"first {used} of the 53 ResNet-50-shaped int8 conv layers at batch 1, "
+                                        f"{macs / 1e9:.2f} GMAC in {secs:.2f} s, OpenMP direct loops"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2101_08458_amd import unit, workloads as wl
+    unit.load()
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+
+    out = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
+    others = []
+
+    def conv_set(dtype, n, config_id):
+        layers = wl.resnet50_convs()
+        uniq = {}
+        for sh in layers:
+            if sh not in uniq:
+                uniq[sh] = ConvCase(torch, unit, wl, sh, n, dtype, config_id, len(uniq))
+        return layers, uniq
+
+    def run_conv_set(dtype, n, config_id, steps, warmup):
+        layers, uniq = conv_set(dtype, n, config_id)
+        seq = [uniq[sh] for sh in layers]
+
+        def step():
+            for c in seq:
+                c.api()
+        ms = wall_ms(torch, step, steps, warmup)
+        macs = sum(c.macs for c in seq)
+        # per-layer kernel-only and pack durations from HIP events (same launch configuration)
+        t_conv = t_pack = 0.0
+        byts = 0
+        per_layer = []
+        for sh, c in uniq.items():
+            mult = sum(1 for s in layers if s == sh)
+            tc = event_ms(torch, c.conv, 50)
+            tp = event_ms(torch, c.pack, 50)
+            t_conv += mult * tc
+            t_pack += mult * tp
+            byts += mult * c.bytes
+            per_layer.append({"shape": list(sh), "x": mult, "conv_us": round(tc * 1e3, 2), "pack_us": round(tp * 1e3, 2),
+                              "tile": tile_str(c.info)})
+        return ms, macs, t_conv, t_pack, byts, per_layer
+
+    wlname = args.workload
+    if wlname in ("resnet50_i8_b1", "resnet50_f16_b16"):
+        dtype, n, cid = ("i8", 1, 3) if wlname == "resnet50_i8_b1" else ("f16", 16, 4)
+        ms, macs, t_conv, t_pack, byts, per_layer = run_conv_set(dtype, n, cid, args.steps, args.warmup)
+        tops = 2.0 * macs / (ms * 1e-3) / 1e12
+        out.update({
+            "metric": "int8 conv2d TOPS" if dtype == "i8" else "fp16 conv2d TFLOPS",
+            "value": round(tops, 3), "unit": "TOPS" if dtype == "i8" else "TFLOPS",
+            "ms_per_step": round(ms, 4), "dtype": dtype,
+            "pct_of_mfma_peak": round(100.0 * tops / PEAK[dtype], 3),
+            "config": {"workload": f"53 conv layers of a ResNet-50-shaped network, batch {n}, "
+                                   f"{'int8->int32' if dtype == 'i8' else 'fp16->fp32'}, NCHW in -> NCHW out per layer "
+                                   "(pack_act + implicit-GEMM conv [+ split reduce]), weights pre-packed",
+                       "layers": 53, "batch": n, "gmacs_per_step": round(macs / 1e9, 3)},
+            "kernel_only_ms_per_step": round(t_conv, 4), "pack_act_ms_per_step": round(t_pack, 4),
+        })
+        gbs = byts / (t_conv * 1e-3) / 1e9
+        out["roofline"] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_GBS, "unit": "GB/s",
+                           "frac": round(gbs / HBM_GBS, 4), "traffic": None,
+                           "kernel": "igemm_kernel (conv, all 53 launches; split-reduce time included where selected)",
+                           "note": "sum of algorithmic bytes (x + w + y once) / sum of HIP-event kernel durations"}
+        out["per_layer"] = per_layer
+    else:
+        dtype = "i8" if "_i8" in wlname else "f16"
+        if wlname.startswith("gemm"):
+            c = GemmCase(torch, unit, wl, 4096, 4096, 4096, dtype)
+            fn, desc = c.run, f"GEMM 4096^3 {dtype}"
+        else:
+            c = ConvCase(torch, unit, wl, wl.LARGE_CONV, 32, dtype, 9, 0)
+            fn, desc = c.api, f"conv N=32 C=K=256 56x56 3x3 {dtype} (pack_act + conv)"
+        ms = wall_ms(torch, fn, args.steps, args.warmup)
+        tops = 2.0 * c.macs / (ms * 1e-3) / 1e12
+        kms = event_ms(torch, c.run if wlname.startswith("gemm") else c.conv, 50)
+        out.update({"metric": f"{'int8' if dtype == 'i8' else 'fp16'} {'matmul' if wlname.startswith('gemm') else 'conv2d'} "
+                              f"{'TOPS' if dtype == 'i8' else 'TFLOPS'}",
+                    "value": round(tops, 2), "unit": "TOPS" if dtype == "i8" else "TFLOPS",
+                    "ms_per_step": round(ms, 4), "dtype": dtype, "config": {"workload": desc, "tile": tile_str(c.info)},
+                    "roofline": mfma_roofline(dtype, c.macs, kms)})
+
+    if not args.no_others:
+        def add(name, dtype, macs, byts, ms, info, extra=None):
+            tops = 2.0 * macs / (ms * 1e-3) / 1e12
+            e = {"workload": name, "dtype": dtype, "us": round(ms * 1e3, 2), "value": round(tops, 2),
+                 "unit": "TOPS" if dtype == "i8" else "TFLOPS",
+                 "frac_mfma_peak": round(tops / PEAK[dtype], 4),
+                 "GBps": round(byts / (ms * 1e-3) / 1e9, 1), "tile": tile_str(info)}
+            if extra:
+                e.update(extra)
+            others.append(e)
+
+        for dtype in ("i8", "f16"):
+            g = GemmCase(torch, unit, wl, 4096, 4096, 4096, dtype)
+            add("gemm 4096^3", dtype, g.macs, g.bytes, event_ms(torch, g.run, 30), g.info)
+            del g
+            c = ConvCase(torch, unit, wl, wl.LARGE_CONV, 32, dtype, 9, 0)
+            add("large conv N=32 C=K=256 56x56 3x3, kernel only", dtype, c.macs, c.bytes, event_ms(torch, c.conv, 20), c.info)
+            add("large conv N=32 C=K=256 56x56 3x3, pack_act + conv", dtype, c.macs, c.bytes, event_ms(torch, c.api, 20), c.info)
+            del c
+            torch.cuda.empty_cache()
+        c = ConvCase(torch, unit, wl, wl.CONFIG1, 1, "i8", 1, 0)
+        add("config 1: conv 1x64x56x56 * 64x64x3x3, kernel only", "i8", c.macs, c.bytes, event_ms(torch, c.conv, 200), c.info)
+        add("config 1, pack_act + conv", "i8", c.macs, c.bytes, event_ms(torch, c.api, 200), c.info)
+        g = GemmCase(torch, unit, wl, 1, 1000, 2048, "i8")
+        add("gemm FC 1x1000x2048", "i8", g.macs, g.bytes, event_ms(torch, g.run, 200), g.info)
+        if wlname != "resnet50_f16_b16":
+            ms, macs, t_conv, t_pack, byts, _ = run_conv_set("f16", 16, 4, 5, 2)
+            others.append({"workload": "53 ResNet-50-shaped conv layers, batch 16, fp16->fp32, pack_act + conv",
+                           "dtype": "f16", "ms": round(ms, 3), "value": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
+                           "unit": "TFLOPS", "kernel_only_ms": round(t_conv, 3), "pack_act_ms": round(t_pack, 3),
+                           "kernel_GBps": round(byts / (t_conv * 1e-3) / 1e9, 1)})
+        out["others"] = others
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -40,6 +40,7 @@ struct IgemmArgs {
     //   out[n*img_stride + row*row_stride + col % cols_per_img]   (4-byte elements)
     void *out;  long row_stride;  long img_stride;  int cols_per_img;
     long split_stride;                              // elements between grid.z partials
+    long b_bytes;                                   // conv: bytes of the packed activation tensor (< 2 GiB)
     // fused epilogue (EPI_REQUANT): int8 results
     int epi;
     const float *scale;  const int32_t *bias;  const int32_t *residual;  int relu;
@@ -97,6 +98,23 @@ template <int NCH> __device__ __forceinline__ int swz(int row)
     return (row / SWD) % NCH;
 }
 
+// Raw buffer descriptors: loads and stores that fall outside [0, num_records) return zero /
+// are dropped by the hardware, so tile edges, the reduction tail and conv padding need no
+// branches -- an invalid lane just gets an offset beyond the range.
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
+#define UNIT_OOB 0x80000000u      /* every buffer is kept below 2 GiB by the host checks */
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, unsigned bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ unsigned to_bits(int v)   { return (unsigned)v; }
+__device__ __forceinline__ unsigned to_bits(float v) { return __float_as_uint(v); }
+__device__ __forceinline__ v4i buf_load16(__amdgpu_buffer_rsrc_t r, unsigned off)
+{
+    return __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
+}
+
 template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, bool CONV>
 struct IgemmCfg {
     enum {
@@ -118,7 +136,7 @@ struct IgemmCfg {
     static_assert(BKB % KSUBB == 0, "step must be whole MFMAs");
 };
 
-template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, bool CONV>
+template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, bool CONV, int EPI>
 __global__ void __launch_bounds__(WGM * WGN * WGK * 64)
 igemm_kernel(const IgemmArgs g)
 {
@@ -127,6 +145,7 @@ igemm_kernel(const IgemmArgs g)
     typedef typename M::acc_t acc_t;
     typedef typename M::elem_t elem_t;
     constexpr int NT = C::NT, NCH = C::NCH, TM = C::TM, TN = C::TN, LA = C::LA, LB = C::LB;
+    constexpr bool FULL_A = (BM * NCH) % NT == 0, FULL_B = (BN * NCH) % NT == 0;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -159,83 +178,96 @@ igemm_kernel(const IgemmArgs g)
     int ks_end = ks_begin + g.ksteps_per_split;
     if (ks_end > ksteps_total) ks_end = ksteps_total;
 
-    // ---- per-thread global-load bookkeeping: chunk slot id = tid + i*NT -> (row r, chunk c)
-    const uint8_t *pa[LA];  bool va[LA];  int la_off[LA];
+    // ---- per-thread global-load bookkeeping: chunk slot id = tid + i*NT -> (row r, chunk cB).
+    // NT is a multiple of NCH, so every slot of a thread has the same chunk column cB.
+    const int cB = tid % NCH;
+    const int rows_here = (g.rows - row0 < BM) ? g.rows - row0 : BM;
+    const __amdgpu_buffer_rsrc_t rsA =
+        make_rsrc(g.A + (long)row0 * g.lda, (unsigned)((long)(rows_here - 1) * g.lda + (long)g.kchunks * 16));
+    unsigned offA[LA];  int ldsA[LA];
 #pragma unroll
     for (int i = 0; i < LA; ++i) {
         int id = tid + i * NT;
-        int r = id / NCH, c = id % NCH;
-        bool in_tile = (BM * NCH % NT == 0) || (id < BM * NCH);
-        int grow = row0 + r;
-        va[i] = in_tile && grow < g.rows;
-        pa[i] = g.A + (long)(va[i] ? grow : 0) * g.lda + c * 16;
-        la_off[i] = in_tile ? r * BKB + ((c ^ swz<NCH>(r)) << 4) : -1;
+        int r = id / NCH;
+        bool in_tile = FULL_A || (id < BM * NCH);
+        offA[i] = (in_tile && r < rows_here) ? (unsigned)(r * (int)g.lda + cB * 16) : UNIT_OOB;
+        ldsA[i] = in_tile ? r * BKB + ((cB ^ swz<NCH>(r)) << 4) : -1;
     }
-    const uint8_t *pb[LB];  bool vb[LB];  int lb_off[LB];
+    const int cols_here = (g.cols - col0 < BN) ? g.cols - col0 : BN;
+    const __amdgpu_buffer_rsrc_t rsB = CONV
+        ? make_rsrc(g.B, (unsigned)g.b_bytes)
+        : make_rsrc(g.B + (long)col0 * g.ldb, (unsigned)((long)(cols_here - 1) * g.ldb + (long)g.kchunks * 16));
+    unsigned offB[LB];  int ldsB[LB];
     int bh0[LB], bw0[LB];
-    const int cB = tid % NCH;                       // chunk column of this thread (NT % NCH == 0)
 #pragma unroll
     for (int i = 0; i < LB; ++i) {
         int id = tid + i * NT;
-        int r = id / NCH, c = id % NCH;
-        bool in_tile = (BN * NCH % NT == 0) || (id < BN * NCH);
-        int gcol = col0 + r;
-        vb[i] = in_tile && gcol < g.cols;
-        lb_off[i] = in_tile ? BM * BKB + r * BKB + ((c ^ swz<NCH>(r)) << 4) : -1;
+        int r = id / NCH;
+        bool in_tile = FULL_B || (id < BN * NCH);
+        bool valid = in_tile && r < cols_here;
+        ldsB[i] = in_tile ? BM * BKB + r * BKB + ((cB ^ swz<NCH>(r)) << 4) : -1;
         if (CONV) {
-            int cc = vb[i] ? gcol : 0;
+            int cc = valid ? col0 + r : 0;
             int n = cc / g.PQ, pq = cc - n * g.PQ;
             int p = pq / g.Q, q = pq - p * g.Q;
-            bh0[i] = p * g.sh - g.ph;
-            bw0[i] = q * g.sw - g.pw;
-            pb[i] = g.B + (long)n * g.H * g.W * g.CB * 16;
+            // an invalid column gets a row far outside the image: its bounds test always fails
+            const int bh = p * g.sh - g.ph, bw = q * g.sw - g.pw;
+            bh0[i] = valid ? bh : -0x100000;
+            bw0[i] = bw;
+            // byte offset of tap (0,0); modulo 2^32 (negative in the padding), exact once a tap is in range
+            offB[i] = (unsigned)((n * g.H + bh) * g.W + bw) * (unsigned)(g.CB * 16);
         } else {
-            pb[i] = g.B + (long)(vb[i] ? gcol : 0) * g.ldb + c * 16;
+            offB[i] = valid ? (unsigned)(r * (int)g.ldb + cB * 16) : UNIT_OOB;
             bh0[i] = bw0[i] = 0;
         }
     }
+    // conv: reduction chunk kc -> (r, s, channel chunk cb), advanced incrementally per step
+    int kc = ks_begin * NCH + cB;
+    int cr = 0, cs = 0, ccb = 0;
+    if (CONV) {
+        int rs = kc / g.CB;
+        ccb = kc - rs * g.CB;
+        cr = rs / g.S;
+        cs = rs - cr * g.S;
+    }
 
     v4i ra[LA], rb[LB];
-    const v4i zero4 = {0, 0, 0, 0};
 
-    auto load_global = [&](int ks) {
+    // loads the tile of the step whose first chunk (for this thread) is kc, then advances kc
+    auto load_global = [&]() {
+        const bool kok = kc < g.kchunks;
+        const unsigned kbyte = (unsigned)(kc - cB) * 16u;          // = step * BKB
 #pragma unroll
-        for (int i = 0; i < LA; ++i) {
-            int c = (tid + i * NT) % NCH;
-            bool ok = va[i] && (ks * NCH + c < g.kchunks);
-            ra[i] = ok ? *reinterpret_cast<const v4i *>(pa[i] + (long)ks * BKB) : zero4;
-        }
+        for (int i = 0; i < LA; ++i)
+            ra[i] = buf_load16(rsA, kok ? offA[i] + kbyte : UNIT_OOB);
         if (CONV) {
-            // reduction chunk kc -> (r, s, channel chunk); identical for all of this
-            // thread's columns because its chunk column cB is fixed
-            int kc = ks * NCH + cB;
-            int rs = kc / g.CB, cb = kc - rs * g.CB;
-            int r = rs / g.S, s = rs - r * g.S;
-            bool kok = kc < g.kchunks;
+            const unsigned tap = (unsigned)((cr * g.W + cs) * g.CB + ccb) * 16u;
 #pragma unroll
             for (int i = 0; i < LB; ++i) {
-                int h = bh0[i] + r, w = bw0[i] + s;
-                bool ok = vb[i] && kok && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-                long off = ((long)(h * g.W + w) * g.CB + cb) * 16;
-                rb[i] = ok ? *reinterpret_cast<const v4i *>(pb[i] + off) : zero4;
+                int h = bh0[i] + cr, w = bw0[i] + cs;
+                bool ok = kok && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                rb[i] = buf_load16(rsB, ok ? offB[i] + tap : UNIT_OOB);
+            }
+            ccb += NCH;
+            while (ccb >= g.CB) {
+                ccb -= g.CB;
+                if (++cs == g.S) { cs = 0; ++cr; }
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < LB; ++i) {
-                int c = (tid + i * NT) % NCH;
-                bool ok = vb[i] && (ks * NCH + c < g.kchunks);
-                rb[i] = ok ? *reinterpret_cast<const v4i *>(pb[i] + (long)ks * BKB) : zero4;
-            }
+            for (int i = 0; i < LB; ++i)
+                rb[i] = buf_load16(rsB, kok ? offB[i] + kbyte : UNIT_OOB);
         }
+        kc += NCH;
     };
     auto store_lds = [&](int buf) {
         uint8_t *base = smem + buf * C::STAGE_BYTES;
 #pragma unroll
         for (int i = 0; i < LA; ++i)
-            if (la_off[i] >= 0) *reinterpret_cast<v4i *>(base + la_off[i]) = ra[i];
+            if (FULL_A || ldsA[i] >= 0) *reinterpret_cast<v4i *>(base + ldsA[i]) = ra[i];
 #pragma unroll
         for (int i = 0; i < LB; ++i)
-            if (lb_off[i] >= 0) *reinterpret_cast<v4i *>(base + lb_off[i]) = rb[i];
+            if (FULL_B || ldsB[i] >= 0) *reinterpret_cast<v4i *>(base + ldsB[i]) = rb[i];
     };
 
     // ---- fragment addressing (lane -> row inside an MFMA tile, 16-byte chunk along k)
@@ -255,13 +287,13 @@ igemm_kernel(const IgemmArgs g)
             for (int e = 0; e < M::NACC; ++e) acc[i][j][e] = 0;
 
     if (ks_begin < ks_end) {
-        load_global(ks_begin);
+        load_global();
         store_lds(0);
         __syncthreads();
         for (int ks = ks_begin; ks < ks_end; ++ks) {
             const int buf = (ks - ks_begin) & 1;
             const bool more = ks + 1 < ks_end;
-            if (more) load_global(ks + 1);
+            if (more) load_global();
             const uint8_t *sA = smem + buf * C::STAGE_BYTES;
             const uint8_t *sB = sA + BM * BKB;
 #pragma unroll
@@ -313,31 +345,59 @@ igemm_kernel(const IgemmArgs g)
     }
 
     // ---- epilogue
-    elem_t *out = reinterpret_cast<elem_t *>(g.out) + (long)blockIdx.z * g.split_stride;
+    if (EPI == EPI_RAW) {
+        // 4-byte stores through a buffer descriptor anchored at the tile's first row;
+        // out-of-tile lanes get an out-of-range offset and are dropped by the hardware.
+        const elem_t *tile_base = reinterpret_cast<const elem_t *>(g.out) + (long)blockIdx.z * g.split_stride +
+                                  (long)row0 * g.row_stride;
+        const __amdgpu_buffer_rsrc_t rsO = make_rsrc(tile_base, UNIT_OOB);   // lanes are masked explicitly
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-        const int col = col0 + wn * C::WTN + j * MF + lrow;
-        if (col >= g.cols) continue;
-        long cbase;
-        if (CONV) {
-            int n = col / g.cols_per_img;
-            cbase = (long)n * g.img_stride + (col - n * g.cols_per_img);
-        } else {
-            cbase = col;
-        }
+        for (int j = 0; j < TN; ++j) {
+            const int col = col0 + wn * C::WTN + j * MF + lrow;
+            unsigned cbase;
+            if (CONV) {
+                int n = col / g.cols_per_img;
+                cbase = (unsigned)((long)n * g.img_stride + (col - n * g.cols_per_img));
+            } else {
+                cbase = (unsigned)col;
+            }
+            const bool col_ok = col < g.cols;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
+            for (int i = 0; i < TM; ++i) {
 #pragma unroll
-            for (int e = 0; e < M::NACC; ++e) {
-                const int row = row0 + wm * C::WTM + i * MF + acc_row<MF>(e, lane);
-                if (row >= g.rows) {
-                    // padding channels of a packed int8 output are defined to be zero
-                    if (DT == DT_I8 && g.epi == EPI_REQUANT && g.out_packed && row < g.packed_ld)
-                        g.out_packed[(long)col * g.packed_ld + row] = 0;
-                    continue;
+                for (int e = 0; e < M::NACC; ++e) {
+                    const int lr = wm * C::WTM + i * MF + acc_row<MF>(e, lane);
+                    const bool ok = col_ok && lr < rows_here;
+                    const unsigned off = ok ? (cbase + (unsigned)lr * (unsigned)g.row_stride) * 4u : UNIT_OOB;
+                    const elem_t val = acc[i][j][e];
+                    __builtin_amdgcn_raw_buffer_store_b32(to_bits(val), rsO, off, 0, 0);
                 }
-                const long addr = cbase + (long)row * g.row_stride;
-                if (DT == DT_I8 && g.epi == EPI_REQUANT) {
+            }
+        }
+    } else {
+        elem_t *out = reinterpret_cast<elem_t *>(g.out);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = col0 + wn * C::WTN + j * MF + lrow;
+            if (col >= g.cols) continue;
+            long cbase;
+            if (CONV) {
+                int n = col / g.cols_per_img;
+                cbase = (long)n * g.img_stride + (col - n * g.cols_per_img);
+            } else {
+                cbase = col;
+            }
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int e = 0; e < M::NACC; ++e) {
+                    const int row = row0 + wm * C::WTM + i * MF + acc_row<MF>(e, lane);
+                    if (row >= g.rows) {
+                        // padding channels of a packed int8 output are defined to be zero
+                        if (g.out_packed && row < g.packed_ld) g.out_packed[(long)col * g.packed_ld + row] = 0;
+                        continue;
+                    }
+                    const long addr = cbase + (long)row * g.row_stride;
                     int t = (int)acc[i][j][e];
                     if (g.store_raw) out[addr] = acc[i][j][e];
                     if (g.bias) t += g.bias[row];
@@ -345,8 +405,6 @@ igemm_kernel(const IgemmArgs g)
                     int v = requant_elem(t, g.scale[row], g.relu);
                     if (g.out_i8) g.out_i8[addr] = (int8_t)v;
                     if (g.out_packed) g.out_packed[(long)col * g.packed_ld + row] = (int8_t)v;
-                } else {
-                    out[addr] = acc[i][j][e];
                 }
             }
         }

@@ -68,7 +68,9 @@ int conv_geom(const unit_conv2d_desc *d, int dtype, ConvGeom *g)
     g->out_elems = g->cols * d->k;
     // index arithmetic in the kernels is 32-bit for rows/cols/chunks
     if (g->cols > 0x7fffffffL || kbytes > 0x7fffffffL || g->out_elems > (1L << 40)) return UNIT_ENOTSUP;
-    if ((long)d->h * d->w * g->cp * elem_size(dtype) > 0x7fffffffL) return UNIT_ENOTSUP;
+    // buffer descriptors address at most 2 GiB per tensor
+    if ((long)d->n * d->h * d->w * g->cp * elem_size(dtype) >= 0x7fffffffL) return UNIT_ENOTSUP;
+    if (g->out_elems * 4 >= 0x7fffffffL || kbytes * 256 >= 0x7fffffffL) return UNIT_ENOTSUP;
     return UNIT_OK;
 }
 
@@ -136,6 +138,7 @@ int conv_packed(const unit_conv2d_desc *d, int dtype, const void *xp, const void
     a.B = static_cast<const uint8_t *>(xp);  a.ldb = 0;                      a.cols = (int)g.cols;
     a.kchunks = g.kchunks;
     a.H = d->h;  a.W = d->w;  a.CB = g.cp * es / 16;  a.P = g.p;  a.Q = g.q;  a.PQ = g.p * g.q;
+    a.b_bytes = (long)d->n * d->h * d->w * g.cp * es;
     a.R = d->r;  a.S = d->s;  a.sh = d->stride_h;  a.sw = d->stride_w;  a.ph = d->pad_h;  a.pw = d->pad_w;
     a.out = y_raw;  a.row_stride = a.PQ;  a.img_stride = (long)d->k * a.PQ;  a.cols_per_img = a.PQ;
     if (rq) {
@@ -195,7 +198,8 @@ int matmul_geom(int m, int n, int k, long lda, long ldb, int dtype, MatmulGeom *
     if (m <= 0 || n <= 0 || k <= 0 || lda < k || ldb < k) return UNIT_EINVAL;
     if (dtype == UNIT_I8 && k > UNIT_MAX_REDUCTION_I8) return UNIT_EOVERFLOW;
     const int es = elem_size(dtype);
-    if ((long)k * es > 0x7fffff00L) return UNIT_ENOTSUP;
+    // a 256-row tile of either operand and of C must stay below 2 GiB (buffer descriptors)
+    if (lda * es * 256 >= 0x7fffffffL || ldb * es * 256 >= 0x7fffffffL) return UNIT_ENOTSUP;
     g->kpad_bytes = (int)(((long)k * es + 15) / 16 * 16);
     g->kchunks = g->kpad_bytes / 16;
     bool ktail = ((long)k * es) % 16 != 0;
@@ -215,6 +219,7 @@ int matmul_any(int dtype, int m, int n, int k, const void *A, long lda, const vo
     int rc = matmul_geom(m, n, k, lda, ldb, dtype, &g);
     if (rc != UNIT_OK) return rc;
     if (!A || !B || !C || ldc < n) return UNIT_EINVAL;
+    if (ldc * 4 * 256 >= 0x7fffffffL) return UNIT_ENOTSUP;
     const int es = elem_size(dtype);
     if ((!g.pad_a && !aligned16(A)) || (!g.pad_b && !aligned16(B))) return UNIT_EINVAL;
     if (reinterpret_cast<uintptr_t>(C) & 3) return UNIT_EINVAL;
