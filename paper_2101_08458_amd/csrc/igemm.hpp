@@ -115,37 +115,56 @@ __device__ __forceinline__ v4i buf_load16(__amdgpu_buffer_rsrc_t r, unsigned off
     return __builtin_bit_cast(v4i, __builtin_amdgcn_raw_buffer_load_b128(r, off, 0, 0));
 }
 
-template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, bool CONV>
+// Global -> LDS without passing through registers: one wave-level instruction moves
+// 64 lanes x 16 bytes into 1 KiB of contiguous LDS starting at the (wave-uniform) address
+// `lds`; lane L fetches from byte offset `off` of the buffer and lands at lds + 16*L.
+// Out-of-range lanes write zeros.  Completion is tracked by vmcnt.
+__device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t r, uint8_t *lds, unsigned off)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void *)lds, 16, off, 0, 0, 0);
+}
+// s_waitcnt vmcnt(N) lgkmcnt(0)  (expcnt left alone); N <= 63
+#define UNIT_WAIT_VM_LGKM0(N) __builtin_amdgcn_s_waitcnt((((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4)))
+// workgroup barrier that the compiler may not move LDS traffic across
+#define UNIT_BARRIER() do { asm volatile("" ::: "memory"); __builtin_amdgcn_s_barrier(); asm volatile("" ::: "memory"); } while (0)
+
+template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, int NST>
 struct IgemmCfg {
     enum {
-        NT    = WGM * WGN * WGK * 64,
-        NCH   = BKB / 16,
+        NW    = WGM * WGN * WGK,                   // waves per workgroup
+        NT    = NW * 64,
+        NCH   = BKB / 16,                          // 16-byte chunks per row per step
         WTM   = BM / WGM,  WTN = BN / WGN,
         TM    = WTM / MF,  TN  = WTN / MF,
         KSUBB = (MF == 32) ? 32 : 64,              // reduction bytes per MFMA
         NKSUB = BKB / KSUBB,
         CPL   = KSUBB / 16,                        // 16-byte chunks per MFMA along k
-        LA    = (BM * NCH + NT - 1) / NT,
-        LB    = (BN * NCH + NT - 1) / NT,
+        RPI   = 1024 / BKB,                        // tile rows filled by one wave-level DMA
+        IA    = BM / RPI / NW,                     // DMA instructions per wave per step, A tile
+        IB    = BN / RPI / NW,
+        LPT   = IA + IB,
         STAGE_BYTES  = (BM + BN) * BKB,
         REDUCE_BYTES = (WGK - 1) * BM * BN * 4,
-        SMEM_BYTES   = (2 * STAGE_BYTES > REDUCE_BYTES) ? 2 * STAGE_BYTES : REDUCE_BYTES,
+        SMEM_BYTES   = (NST * STAGE_BYTES > REDUCE_BYTES) ? NST * STAGE_BYTES : REDUCE_BYTES,
     };
     static_assert(BM % (WGM * MF) == 0 && BN % (WGN * MF) == 0, "wave tiles must be whole MFMA tiles");
     static_assert(NKSUB % WGK == 0 && NKSUB >= WGK, "in-group split must divide the sub-steps");
-    static_assert(BKB % KSUBB == 0, "step must be whole MFMAs");
+    static_assert(BKB % KSUBB == 0 && 1024 % BKB == 0, "step must be whole MFMAs and divide a DMA block");
+    static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tiles must split evenly into per-wave DMA blocks");
+    static_assert((NW * RPI) % 16 == 0, "the row swizzle must not depend on the DMA instruction index");
+    static_assert(NST >= 2 && (NST - 1) * LPT <= 63, "stage count limited by the vmcnt range");
+    static_assert(SMEM_BYTES <= 160 * 1024, "LDS capacity");
 };
 
-template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, bool CONV, int EPI>
+template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, int NST, bool CONV, int EPI>
 __global__ void __launch_bounds__(WGM * WGN * WGK * 64)
 igemm_kernel(const IgemmArgs g)
 {
-    typedef IgemmCfg<DT, BM, BN, BKB, WGM, WGN, WGK, MF, CONV> C;
+    typedef IgemmCfg<DT, BM, BN, BKB, WGM, WGN, WGK, MF, NST> C;
     typedef Mma<DT, MF> M;
     typedef typename M::acc_t acc_t;
     typedef typename M::elem_t elem_t;
-    constexpr int NT = C::NT, NCH = C::NCH, TM = C::TM, TN = C::TN, LA = C::LA, LB = C::LB;
-    constexpr bool FULL_A = (BM * NCH) % NT == 0, FULL_B = (BN * NCH) % NT == 0;
+    constexpr int NW = C::NW, NCH = C::NCH, TM = C::TM, TN = C::TN, IA = C::IA, IB = C::IB, RPI = C::RPI;
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -177,52 +196,51 @@ igemm_kernel(const IgemmArgs g)
     const int ks_begin = blockIdx.z * g.ksteps_per_split;
     int ks_end = ks_begin + g.ksteps_per_split;
     if (ks_end > ksteps_total) ks_end = ksteps_total;
+    // first reduction chunk this workgroup must not load: later tiles come back as zeros
+    const int kend = (ks_end * NCH < g.kchunks) ? ks_end * NCH : g.kchunks;
 
-    // ---- per-thread global-load bookkeeping: chunk slot id = tid + i*NT -> (row r, chunk cB).
-    // NT is a multiple of NCH, so every slot of a thread has the same chunk column cB.
-    const int cB = tid % NCH;
+    // ---- global -> LDS bookkeeping.  DMA instruction j of wave w fills tile rows
+    // (j*NW + w)*RPI .. +RPI; lane L lands in row L/NCH, physical chunk L%NCH of that
+    // block and therefore fetches the logical chunk cT = (L%NCH) ^ swz(row).  NW*RPI is a
+    // multiple of the swizzle period, so cT is the same for every j.
+    const int lr_blk = lane / NCH;                                  // row inside a DMA block
+    const int cT = (lane % NCH) ^ swz<NCH>(wave * RPI + lr_blk);    // logical chunk this thread fetches
     const int rows_here = (g.rows - row0 < BM) ? g.rows - row0 : BM;
     const __amdgpu_buffer_rsrc_t rsA =
         make_rsrc(g.A + (long)row0 * g.lda, (unsigned)((long)(rows_here - 1) * g.lda + (long)g.kchunks * 16));
-    unsigned offA[LA];  int ldsA[LA];
+    unsigned offA[IA];
 #pragma unroll
-    for (int i = 0; i < LA; ++i) {
-        int id = tid + i * NT;
-        int r = id / NCH;
-        bool in_tile = FULL_A || (id < BM * NCH);
-        offA[i] = (in_tile && r < rows_here) ? (unsigned)(r * (int)g.lda + cB * 16) : UNIT_OOB;
-        ldsA[i] = in_tile ? r * BKB + ((cB ^ swz<NCH>(r)) << 4) : -1;
+    for (int j = 0; j < IA; ++j) {
+        int r = (j * NW + wave) * RPI + lr_blk;
+        offA[j] = (r < rows_here) ? (unsigned)(r * (int)g.lda + cT * 16) : UNIT_OOB;
     }
     const int cols_here = (g.cols - col0 < BN) ? g.cols - col0 : BN;
     const __amdgpu_buffer_rsrc_t rsB = CONV
         ? make_rsrc(g.B, (unsigned)g.b_bytes)
         : make_rsrc(g.B + (long)col0 * g.ldb, (unsigned)((long)(cols_here - 1) * g.ldb + (long)g.kchunks * 16));
-    unsigned offB[LB];  int ldsB[LB];
-    int bh0[LB], bw0[LB];
+    unsigned offB[IB];
+    int bh0[IB], bw0[IB];
 #pragma unroll
-    for (int i = 0; i < LB; ++i) {
-        int id = tid + i * NT;
-        int r = id / NCH;
-        bool in_tile = FULL_B || (id < BN * NCH);
-        bool valid = in_tile && r < cols_here;
-        ldsB[i] = in_tile ? BM * BKB + r * BKB + ((cB ^ swz<NCH>(r)) << 4) : -1;
+    for (int j = 0; j < IB; ++j) {
+        int r = (j * NW + wave) * RPI + lr_blk;
+        bool valid = r < cols_here;
         if (CONV) {
             int cc = valid ? col0 + r : 0;
             int n = cc / g.PQ, pq = cc - n * g.PQ;
             int p = pq / g.Q, q = pq - p * g.Q;
             // an invalid column gets a row far outside the image: its bounds test always fails
             const int bh = p * g.sh - g.ph, bw = q * g.sw - g.pw;
-            bh0[i] = valid ? bh : -0x100000;
-            bw0[i] = bw;
+            bh0[j] = valid ? bh : -0x100000;
+            bw0[j] = bw;
             // byte offset of tap (0,0); modulo 2^32 (negative in the padding), exact once a tap is in range
-            offB[i] = (unsigned)((n * g.H + bh) * g.W + bw) * (unsigned)(g.CB * 16);
+            offB[j] = (unsigned)((n * g.H + bh) * g.W + bw) * (unsigned)(g.CB * 16);
         } else {
-            offB[i] = valid ? (unsigned)(r * (int)g.ldb + cB * 16) : UNIT_OOB;
-            bh0[i] = bw0[i] = 0;
+            offB[j] = valid ? (unsigned)(r * (int)g.ldb + cT * 16) : UNIT_OOB;
+            bh0[j] = bw0[j] = 0;
         }
     }
     // conv: reduction chunk kc -> (r, s, channel chunk cb), advanced incrementally per step
-    int kc = ks_begin * NCH + cB;
+    int kc = ks_begin * NCH + cT;
     int cr = 0, cs = 0, ccb = 0;
     if (CONV) {
         int rs = kc / g.CB;
@@ -231,22 +249,22 @@ igemm_kernel(const IgemmArgs g)
         cs = rs - cr * g.S;
     }
 
-    v4i ra[LA], rb[LB];
-
-    // loads the tile of the step whose first chunk (for this thread) is kc, then advances kc
-    auto load_global = [&]() {
-        const bool kok = kc < g.kchunks;
-        const unsigned kbyte = (unsigned)(kc - cB) * 16u;          // = step * BKB
+    // issues the DMA of the next tile (the one whose chunk for this thread is kc) into `stage`
+    auto issue_tile = [&](int stage) {
+        const bool kok = kc < kend;
+        const unsigned kbyte = (unsigned)(kc - cT) * 16u;          // = step * BKB
+        uint8_t *dst = smem + stage * C::STAGE_BYTES + wave * 1024;
 #pragma unroll
-        for (int i = 0; i < LA; ++i)
-            ra[i] = buf_load16(rsA, kok ? offA[i] + kbyte : UNIT_OOB);
+        for (int j = 0; j < IA; ++j)
+            dma16(rsA, dst + j * NW * 1024, kok ? offA[j] + kbyte : UNIT_OOB);
+        dst += BM * BKB;
         if (CONV) {
             const unsigned tap = (unsigned)((cr * g.W + cs) * g.CB + ccb) * 16u;
 #pragma unroll
-            for (int i = 0; i < LB; ++i) {
-                int h = bh0[i] + cr, w = bw0[i] + cs;
+            for (int j = 0; j < IB; ++j) {
+                int h = bh0[j] + cr, w = bw0[j] + cs;
                 bool ok = kok && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
-                rb[i] = buf_load16(rsB, ok ? offB[i] + tap : UNIT_OOB);
+                dma16(rsB, dst + j * NW * 1024, ok ? offB[j] + tap : UNIT_OOB);
             }
             ccb += NCH;
             while (ccb >= g.CB) {
@@ -255,19 +273,10 @@ igemm_kernel(const IgemmArgs g)
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < LB; ++i)
-                rb[i] = buf_load16(rsB, kok ? offB[i] + kbyte : UNIT_OOB);
+            for (int j = 0; j < IB; ++j)
+                dma16(rsB, dst + j * NW * 1024, kok ? offB[j] + kbyte : UNIT_OOB);
         }
         kc += NCH;
-    };
-    auto store_lds = [&](int buf) {
-        uint8_t *base = smem + buf * C::STAGE_BYTES;
-#pragma unroll
-        for (int i = 0; i < LA; ++i)
-            if (FULL_A || ldsA[i] >= 0) *reinterpret_cast<v4i *>(base + ldsA[i]) = ra[i];
-#pragma unroll
-        for (int i = 0; i < LB; ++i)
-            if (FULL_B || ldsB[i] >= 0) *reinterpret_cast<v4i *>(base + ldsB[i]) = rb[i];
     };
 
     // ---- fragment addressing (lane -> row inside an MFMA tile, 16-byte chunk along k)
@@ -286,36 +295,89 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
             for (int e = 0; e < M::NACC; ++e) acc[i][j][e] = 0;
 
+    // ---- main loop.  NST LDS stages hold the tile being multiplied and the NST-1 tiles
+    // after it, which stream in by DMA while the MFMAs run.  Per step a wave runs NS
+    // sub-steps; sub-step s issues the fragment reads of sub-step s+1 into the other half
+    // of the fragment double buffer, then its own MFMAs.  The step's single barrier sits in
+    // front of the LAST sub-step's MFMAs: after it the freed stage is re-armed with the
+    // tile NST steps ahead and the first fragments of the next tile are read, so those
+    // MFMAs cover barrier skew and LDS latency.
+    constexpr int NS = C::NKSUB / WGK;              // sub-steps per wave per step
+    v4i fa[2][TM], fb[2][TN];
+    auto read_frags = [&](int stage, int sub, int slot) {
+        const uint8_t *sA = smem + stage * C::STAGE_BYTES;
+        const uint8_t *sB = sA + BM * BKB;
+        const int ch = (sub * WGK + wk) * C::CPL + lchunk;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[slot][i] = *reinterpret_cast<const v4i *>(sA + (a_row + i * MF) * BKB + ((ch ^ a_swz) << 4));
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb[slot][j] = *reinterpret_cast<const v4i *>(sB + (b_row + j * MF) * BKB + ((ch ^ b_swz) << 4));
+    };
+
     if (ks_begin < ks_end) {
-        load_global();
-        store_lds(0);
-        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < NST; ++t) issue_tile(t);            // tiles 0..NST-1 (zeros past the slice end)
+        UNIT_WAIT_VM_LGKM0((NST - 1) * C::LPT);                 // own part of tile 0 has landed
+        UNIT_BARRIER();
+        read_frags(0, 0, 0);
+        int stage = 0;
         for (int ks = ks_begin; ks < ks_end; ++ks) {
-            const int buf = (ks - ks_begin) & 1;
-            const bool more = ks + 1 < ks_end;
-            if (more) load_global();
-            const uint8_t *sA = smem + buf * C::STAGE_BYTES;
-            const uint8_t *sB = sA + BM * BKB;
+            const int next_stage = (stage + 1 == NST) ? 0 : stage + 1;
 #pragma unroll
-            for (int kk = 0; kk < C::NKSUB / WGK; ++kk) {
-                const int ksub = kk * WGK + wk;
-                const int ch = ksub * C::CPL + lchunk;
-                v4i af[TM], bf[TN];
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-                    af[i] = *reinterpret_cast<const v4i *>(sA + (a_row + i * MF) * BKB + ((ch ^ a_swz) << 4));
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    bf[j] = *reinterpret_cast<const v4i *>(sB + (b_row + j * MF) * BKB + ((ch ^ b_swz) << 4));
+            for (int s2 = 0; s2 < NS; ++s2) {
+                const int slot = s2 & 1;
+                const bool last = (s2 + 1 == NS);
+                if (last) {
+                    UNIT_WAIT_VM_LGKM0((NST - 2) * C::LPT);     // next tile landed, my reads of this one done
+                    UNIT_BARRIER();
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                // One scheduling region: the MFMAs of this sub-step plus the memory
+                // instructions that must be in flight before the next one -- the fragment
+                // reads of the next sub-step and, after the barrier, the DMA that re-arms the
+                // freed stage.  The group barriers below spread those between the MFMAs so
+                // the matrix pipe never waits behind a burst of memory instructions.
+                if (!last) {
+                    read_frags(stage, s2 + 1, slot ^ 1);
+                } else {
+                    read_frags(next_stage, 0, slot ^ 1);
+                    issue_tile(stage);                           // tile ks+NST into the stage just freed
+                }
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        M::run(acc[i][j], af[i], bf[j]);
+                        M::run(acc[i][j], fa[slot][i], fb[slot][j]);
+                {
+                    constexpr int NMEM = TM + TN + C::LPT;       // upper bound: reads + DMAs
+                    constexpr int PER  = (TM * TN / NMEM) > 0 ? (TM * TN / NMEM) : 1;
+#pragma unroll
+                    for (int r = 0; r < TM + TN; ++r) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);   // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // LDS read
+                    }
+                    if (last) {
+#pragma unroll
+                        for (int r = 0; r < C::LPT; ++r) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);   // MFMA
+                            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);     // global -> LDS DMA
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (more) store_lds(buf ^ 1);
-            __syncthreads();
+            if (NS & 1) {                            // odd sub-step count: next tile's first fragments sit in slot 1
+#pragma unroll
+                for (int i = 0; i < TM; ++i) fa[0][i] = fa[1][i];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) fb[0][j] = fb[1][j];
+            }
+            stage = next_stage;
         }
+        UNIT_WAIT_VM_LGKM0(0);                       // drain the (zero-fill) DMAs of the tiles past the end
+        UNIT_BARRIER();
     }
 
     // ---- in-group split reduction: waves with wk > 0 park their accumulators in LDS

@@ -9,8 +9,8 @@
 
 namespace unit {
 
-#define UNIT_TILE_CASE(ID, BM, BN, BKB, WGM, WGN, WGK, MF) \
-    {BM, BN, BKB, WGM, WGN, WGK, MF},
+#define UNIT_TILE_CASE(ID, BM, BN, BKB, WGM, WGN, WGK, MF, NST) \
+    {BM, BN, BKB, WGM, WGN, WGK, MF, NST},
 const TileCfg g_tiles[NUM_TILES] = {
 #include "tiles.def"
 };

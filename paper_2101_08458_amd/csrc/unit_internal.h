@@ -15,6 +15,7 @@ struct TileCfg {
     int bm, bn, bkb;          // workgroup tile rows / cols / reduction bytes per step
     int wgm, wgn, wgk;        // wave grid
     int mf;                   // MFMA edge
+    int nst;                  // LDS stages
 };
 enum { NUM_TILES = 6 };
 extern const TileCfg g_tiles[NUM_TILES];
