@@ -37,6 +37,8 @@ def parse():
                              "large_conv_f16", "resnet50_f16_b16"])
     ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-calibration-mib", type=int, default=0,
+                    help="also run one plain device copy of this many MiB (counter calibration for profiles)")
     return ap.parse_args()
 
 
@@ -106,28 +108,44 @@ class GemmCase:
         f(self.m, self.n, self.k, self.A, self.k, self.B, self.k, self.C, self.n, self.ws)
 
 
-def event_ms(torch, fn, reps, warm=3):
-    """Average duration of fn() launches on torch's current stream (the stream the library
-    launches on), from one HIP event pair around `reps` back-to-back calls."""
+def event_ms(torch, fn, reps, warm=2):
+    """Average device time of one fn() from a HIP event pair around a graph of `reps`
+    back-to-back calls on torch's current stream (the stream the library launches on)."""
+    g = capture(torch, fn, reps)
     for _ in range(warm):
-        fn()
+        g.replay()
     a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     a.record()
-    for _ in range(reps):
-        fn()
+    g.replay()
     b.record()
     torch.cuda.synchronize()
     return a.elapsed_time(b) / reps
 
 
-def wall_ms(torch, fn, steps, warmup):
+def capture(torch, fn, reps=1):
+    """Record `reps` calls of fn() into a HIP graph (the library launches on torch's current
+    stream, which is the capturing stream inside the context).  Replaying it runs exactly the
+    same kernels without the per-launch host cost of the Python binding."""
+    fn()                                   # first call outside capture: one-time function attributes
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for _ in range(reps):
+            fn()
+    return g
+
+
+def wall_ms(torch, fn, steps, warmup, use_graph=True):
+    """Wall-clock time per call: `warmup` untimed calls, then exactly `steps` timed ones between
+    two device synchronisations."""
+    run = capture(torch, fn).replay if use_graph else fn
     for _ in range(warmup):
-        fn()
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        fn()
+        run()
     torch.cuda.synchronize()
     return (time.perf_counter() - t0) * 1e3 / steps
 
@@ -175,6 +193,13 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
 
+    if args.copy_calibration_mib:
+        src = torch.ones(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     out = {"n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "data": "synthetic"}
     others = []
@@ -195,6 +220,7 @@ def main():
             for c in seq:
                 c.api()
         ms = wall_ms(torch, step, steps, warmup)
+        ms_eager = wall_ms(torch, step, max(steps // 10, 3), 2, use_graph=False)
         macs = sum(c.macs for c in seq)
         # per-layer kernel-only and pack durations from HIP events (same launch configuration)
         t_conv = t_pack = 0.0
@@ -209,12 +235,12 @@ def main():
             byts += mult * c.bytes
             per_layer.append({"shape": list(sh), "x": mult, "conv_us": round(tc * 1e3, 2), "pack_us": round(tp * 1e3, 2),
                               "tile": tile_str(c.info)})
-        return ms, macs, t_conv, t_pack, byts, per_layer
+        return ms, ms_eager, macs, t_conv, t_pack, byts, per_layer
 
     wlname = args.workload
     if wlname in ("resnet50_i8_b1", "resnet50_f16_b16"):
         dtype, n, cid = ("i8", 1, 3) if wlname == "resnet50_i8_b1" else ("f16", 16, 4)
-        ms, macs, t_conv, t_pack, byts, per_layer = run_conv_set(dtype, n, cid, args.steps, args.warmup)
+        ms, ms_eager, macs, t_conv, t_pack, byts, per_layer = run_conv_set(dtype, n, cid, args.steps, args.warmup)
         tops = 2.0 * macs / (ms * 1e-3) / 1e12
         out.update({
             "metric": "int8 conv2d TOPS" if dtype == "i8" else "fp16 conv2d TFLOPS",
@@ -225,6 +251,8 @@ def main():
                                    f"{'int8->int32' if dtype == 'i8' else 'fp16->fp32'}, NCHW in -> NCHW out per layer "
                                    "(pack_act + implicit-GEMM conv [+ split reduce]), weights pre-packed",
                        "layers": 53, "batch": n, "gmacs_per_step": round(macs / 1e9, 3)},
+            "launch": "one HIP graph per step (all kernels of the 53 layers), replayed",
+            "eager_ms_per_step": round(ms_eager, 4),
             "kernel_only_ms_per_step": round(t_conv, 4), "pack_act_ms_per_step": round(t_pack, 4),
         })
         gbs = byts / (t_conv * 1e-3) / 1e9
@@ -276,7 +304,7 @@ def main():
         g = GemmCase(torch, unit, wl, 1, 1000, 2048, "i8")
         add("gemm FC 1x1000x2048", "i8", g.macs, g.bytes, event_ms(torch, g.run, 200), g.info)
         if wlname != "resnet50_f16_b16":
-            ms, macs, t_conv, t_pack, byts, _ = run_conv_set("f16", 16, 4, 5, 2)
+            ms, _, macs, t_conv, t_pack, byts, _ = run_conv_set("f16", 16, 4, 20, 3)
             others.append({"workload": "53 ResNet-50-shaped conv layers, batch 16, fp16->fp32, pack_act + conv",
                            "dtype": "f16", "ms": round(ms, 3), "value": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
                            "unit": "TFLOPS", "kernel_only_ms": round(t_conv, 3), "pack_act_ms": round(t_pack, 3),

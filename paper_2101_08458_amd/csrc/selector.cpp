@@ -49,9 +49,11 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, bool conv, bo
     const int nch = c.bkb / 16;
     const int ksteps = cdiv(kchunks, nch);
     const long nt = (long)cdiv(rows, c.bm) * cdiv(cols, c.bn);
+    // Split the reduction across workgroups only when the tiles alone leave more than half
+    // of the compute units idle (the extra reduce launch costs about as much as a small conv).
     int split = 1;
-    if (nt < CUS) {
-        split = cdiv(2 * CUS, nt);                 // aim at two workgroups per compute unit
+    if (nt <= CUS / 2) {
+        split = (int)((3 * CUS / 2 + nt / 2) / nt);   // aim at about 1.5 workgroups per compute unit
         int max_split = ksteps / 2;                // keep at least two steps per slice
         if (split > max_split) split = max_split;
         if (split < 1) split = 1;
