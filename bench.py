@@ -309,6 +309,15 @@ def main():
                            "dtype": "f16", "ms": round(ms, 3), "value": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
                            "unit": "TFLOPS", "kernel_only_ms": round(t_conv, 3), "pack_act_ms": round(t_pack, 3),
                            "kernel_GBps": round(byts / (t_conv * 1e-3) / 1e9, 1)})
+        from paper_2101_08458_amd.resnet18_int8 import ResNet18Int8, random_params
+        for batch in (1, 8):
+            net = ResNet18Int8(batch, random_params(wl.rng(5, batch)))
+            xin = torch.from_numpy(wl.int8_activations(wl.rng(5, 100 + batch), (batch, 3, 224, 224))).to("cuda:0")
+            ms = wall_ms(torch, lambda: net.forward(xin), 50, 5)
+            others.append({"workload": f"ResNet-18-shaped chained int8 inference, batch {batch} (HIP graph replay)",
+                           "dtype": "i8", "ms": round(ms, 4), "images_per_s": round(batch / ms * 1e3, 1),
+                           "value": round(2.0 * 1.8136e9 * batch / (ms * 1e-3) / 1e12, 2), "unit": "TOPS"})
+            del net
         out["others"] = others
 
     if not args.no_cpu:
