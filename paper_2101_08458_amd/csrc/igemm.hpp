@@ -156,8 +156,8 @@ struct IgemmCfg {
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS capacity");
 };
 
-template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, int NST, bool CONV, int EPI>
-__global__ void __launch_bounds__(WGM * WGN * WGK * 64)
+template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, int NST, int OCC, bool CONV, int EPI>
+__global__ void __launch_bounds__(WGM * WGN * WGK * 64, OCC)
 igemm_kernel(const IgemmArgs g)
 {
     typedef IgemmCfg<DT, BM, BN, BKB, WGM, WGN, WGK, MF, NST> C;

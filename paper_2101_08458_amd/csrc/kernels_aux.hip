@@ -144,14 +144,8 @@ hipError_t launch_pad_rows(const void *src, long ld_bytes, int rows, int row_byt
 // split reduction is the paper's "split reduction" tuning step (Section III-C.3) carried
 // across workgroups; the in-group part lives in the main kernel.
 template <typename E>
-__global__ void __launch_bounds__(256)
-splitk_reduce_kernel(const ReduceArgs a)
+__device__ __forceinline__ void reduce_epilogue(const ReduceArgs &a, long i, E sum)
 {
-    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= a.total) return;
-    const E *p = reinterpret_cast<const E *>(a.partials) + i;
-    E sum = p[0];
-    for (int z = 1; z < a.nsplit; ++z) sum += p[(long)z * a.split_stride];
     if (a.out) reinterpret_cast<E *>(a.out)[i] = sum;
     if (a.epi == EPI_REQUANT) {
         int px = i % a.PQ;
@@ -167,6 +161,42 @@ splitk_reduce_kernel(const ReduceArgs a)
     }
 }
 
+// Each thread owns four consecutive outputs and walks the slices with 16-byte loads, four
+// slices in flight (the slice stride is kept a multiple of four elements by the host).
+template <typename E>
+__global__ void __launch_bounds__(256)
+splitk_reduce_kernel(const ReduceArgs a)
+{
+    typedef E v4e __attribute__((ext_vector_type(4)));
+    const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+    if (i >= a.total) return;
+    const E *p = reinterpret_cast<const E *>(a.partials) + i;
+    if (i + 3 < a.total) {
+        v4e sum = *reinterpret_cast<const v4e *>(p);
+        int z = 1;
+        for (; z + 3 < a.nsplit; z += 4) {          // fixed order z = 1, 2, 3, ...: deterministic for fp32
+            v4e t0 = *reinterpret_cast<const v4e *>(p + (long)z * a.split_stride);
+            v4e t1 = *reinterpret_cast<const v4e *>(p + (long)(z + 1) * a.split_stride);
+            v4e t2 = *reinterpret_cast<const v4e *>(p + (long)(z + 2) * a.split_stride);
+            v4e t3 = *reinterpret_cast<const v4e *>(p + (long)(z + 3) * a.split_stride);
+            sum += t0;  sum += t1;  sum += t2;  sum += t3;
+        }
+        for (; z < a.nsplit; ++z) sum += *reinterpret_cast<const v4e *>(p + (long)z * a.split_stride);
+        if (a.epi == EPI_RAW && a.out && (i & 3) == 0) {
+            *reinterpret_cast<v4e *>(reinterpret_cast<E *>(a.out) + i) = sum;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) reduce_epilogue<E>(a, i + e, sum[e]);
+        }
+    } else {
+        for (long j = i; j < a.total; ++j) {
+            E sum = reinterpret_cast<const E *>(a.partials)[j];
+            for (int z = 1; z < a.nsplit; ++z) sum += reinterpret_cast<const E *>(a.partials)[j + (long)z * a.split_stride];
+            reduce_epilogue<E>(a, j, sum);
+        }
+    }
+}
+
 // zero the padding channels [K, packed_ld) of a packed int8 output
 __global__ void zero_pad_channels_kernel(int8_t *yp, int K, int ld, long pixels)
 {
@@ -178,7 +208,7 @@ __global__ void zero_pad_channels_kernel(int8_t *yp, int K, int ld, long pixels)
 
 hipError_t launch_splitk_reduce(const ReduceArgs &a, hipStream_t st)
 {
-    dim3 grid((unsigned)((a.total + 255) / 256)), block(256);
+    dim3 grid((unsigned)((a.total + 1023) / 1024)), block(256);
     if (a.dtype == DT_I8) hipLaunchKernelGGL(splitk_reduce_kernel<int>, grid, block, 0, st, a);
     else                  hipLaunchKernelGGL(splitk_reduce_kernel<float>, grid, block, 0, st, a);
     hipError_t e = hipGetLastError();

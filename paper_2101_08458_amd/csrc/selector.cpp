@@ -9,7 +9,7 @@
 
 namespace unit {
 
-#define UNIT_TILE_CASE(ID, BM, BN, BKB, WGM, WGN, WGK, MF, NST) \
+#define UNIT_TILE_CASE(ID, BM, BN, BKB, WGM, WGN, WGK, MF, NST, OCC) \
     {BM, BN, BKB, WGM, WGN, WGK, MF, NST},
 const TileCfg g_tiles[NUM_TILES] = {
 #include "tiles.def"
@@ -33,14 +33,16 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, bool conv, bo
         tile = 5;
     } else {
         // largest tile that still gives every compute unit a workgroup
-        static const int order[] = {0, 1, 2};
+        static const int order[] = {0, 1};
         for (int t : order) {
             const TileCfg &c = g_tiles[t];
             long nt = (long)cdiv(rows, c.bm) * cdiv(cols, c.bn);
             double fill = (double)rows * cols / ((double)nt * c.bm * c.bn);
             if (nt >= CUS * 3 / 4 && fill >= 0.6) { tile = t; break; }
         }
-        if (tile < 0) tile = (rows > 32 && cols > 32) ? 2 : 4;
+        // small problems are launch- and latency-bound: measured over the ResNet-50 batch-1
+        // layers, 64x64 (2x2 waves) wins once it yields ~100 workgroups, 32x32 below that
+        if (tile < 0) tile = ((long)cdiv(rows, 64) * cdiv(cols, 64) >= 96) ? 3 : 4;
     }
     int forced = env_int("UNIT_TILE", -1);
     if (forced >= 0 && forced < NUM_TILES) tile = forced;
@@ -49,13 +51,14 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, bool conv, bo
     const int nch = c.bkb / 16;
     const int ksteps = cdiv(kchunks, nch);
     const long nt = (long)cdiv(rows, c.bm) * cdiv(cols, c.bn);
-    // Split the reduction across workgroups only when the tiles alone leave more than half
-    // of the compute units idle (the extra reduce launch costs about as much as a small conv).
+    // Split the reduction across workgroups only for deep reductions with few tiles: each
+    // main-loop step of a small tile costs ~0.2 us of DMA latency, while the extra reduce
+    // launch costs ~3 us, so it pays from about 24 steps on (slices of ~6 steps).
     int split = 1;
-    if (nt <= CUS / 2) {
-        split = (int)((3 * CUS / 2 + nt / 2) / nt);   // aim at about 1.5 workgroups per compute unit
-        int max_split = ksteps / 2;                // keep at least two steps per slice
-        if (split > max_split) split = max_split;
+    if (ksteps >= 24 && nt <= CUS / 2) {
+        split = ksteps / 6;
+        int cap = (int)(2 * CUS / nt);
+        if (split > cap) split = cap;
         if (split < 1) split = 1;
     }
     int fs = env_int("UNIT_SPLITK", -1);

@@ -93,11 +93,12 @@ int run_igemm(int dtype, bool conv, IgemmArgs a, long out_elems, int K, int PQ,
         UNIT_HIP(launch_igemm(dtype, conv, ch.tile, a, 1, st));
         return UNIT_OK;
     }
-    size_t need = (size_t)ch.split_k * out_elems * 4;
+    const long slice = (out_elems + 3) & ~3L;     // 16-byte aligned slices for the reduce kernel
+    size_t need = (size_t)ch.split_k * slice * 4;
     if (!ws || ws_bytes < need) return UNIT_EWORKSPACE;
     IgemmArgs m = a;
     m.out = ws;
-    m.split_stride = out_elems;
+    m.split_stride = slice;
     m.epi = EPI_RAW;
     m.store_raw = 1;
     if (!conv) {                                   // partials of a matmul are dense [rows][cols]
@@ -106,7 +107,7 @@ int run_igemm(int dtype, bool conv, IgemmArgs a, long out_elems, int K, int PQ,
     UNIT_HIP(launch_igemm(dtype, conv, ch.tile, m, ch.split_k, st));
     ReduceArgs r;
     std::memset(&r, 0, sizeof r);
-    r.partials = ws;  r.nsplit = ch.split_k;  r.split_stride = out_elems;
+    r.partials = ws;  r.nsplit = ch.split_k;  r.split_stride = slice;
     r.dtype = dtype;  r.total = out_elems;  r.K = K;  r.PQ = PQ;
     r.out = (a.epi == EPI_RAW || a.store_raw) ? a.out : nullptr;
     r.epi = a.epi;  r.scale = a.scale;  r.bias = a.bias;  r.residual = a.residual;  r.relu = a.relu;
@@ -156,7 +157,7 @@ int conv_packed(const unit_conv2d_desc *d, int dtype, const void *xp, const void
 size_t conv_split_bytes(const ConvGeom &g, int dtype)
 {
     TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true);
-    return ch.split_k > 1 ? align256((size_t)ch.split_k * g.out_elems * 4) : 0;
+    return ch.split_k > 1 ? align256((size_t)ch.split_k * ((g.out_elems + 3) & ~3L) * 4) : 0;
 }
 
 int conv_plain(const unit_conv2d_desc *d, int dtype, const void *x, const void *w,
@@ -208,7 +209,7 @@ int matmul_geom(int m, int n, int k, long lda, long ldb, int dtype, MatmulGeom *
     g->a_bytes = g->pad_a ? align256((size_t)m * g->kpad_bytes) : 0;
     g->b_bytes = g->pad_b ? align256((size_t)n * g->kpad_bytes) : 0;
     TileChoice ch = select_tile(m, n, g->kchunks, dtype, false);
-    g->split_bytes = ch.split_k > 1 ? align256((size_t)ch.split_k * m * n * 4) : 0;
+    g->split_bytes = ch.split_k > 1 ? align256((size_t)ch.split_k * (((long)m * n + 3) & ~3L) * 4) : 0;
     return UNIT_OK;
 }
 
