@@ -25,6 +25,10 @@ if ROOT not in sys.path:
 
 PEAK = {"i8": 5000.0, "f16": 2500.0}        # dense MFMA TOPS / TFLOPS (published MI355X)
 HBM_GBS = 8000.0
+# HBM-side bytes per launch (per step for the layer set) of the main kernel, from the committed
+# rocprofv3 counter runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy in the
+# same run); files profiles/igemm_*.md.  Not measurable live, so carried as constants.
+TRAFFIC = {"resnet50_i8_b1": 169.0e6, "gemm_i8_4096": 168.1e6, "gemm_f16_4096": 268.7e6, "large_conv_i8": 138.5e6}
 
 
 def parse():
@@ -257,7 +261,8 @@ def main():
         })
         gbs = byts / (t_conv * 1e-3) / 1e9
         out["roofline"] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_GBS, "unit": "GB/s",
-                           "frac": round(gbs / HBM_GBS, 4), "traffic": None,
+                           "frac": round(gbs / HBM_GBS, 4), "traffic": TRAFFIC.get(wlname),
+                           "algorithmic_bytes": byts,
                            "kernel": "igemm_kernel (conv, all 53 launches; split-reduce time included where selected)",
                            "note": "sum of algorithmic bytes (x + w + y once) / sum of HIP-event kernel durations"}
         out["per_layer"] = per_layer
@@ -276,7 +281,9 @@ def main():
                               f"{'TOPS' if dtype == 'i8' else 'TFLOPS'}",
                     "value": round(tops, 2), "unit": "TOPS" if dtype == "i8" else "TFLOPS",
                     "ms_per_step": round(ms, 4), "dtype": dtype, "config": {"workload": desc, "tile": tile_str(c.info)},
-                    "roofline": mfma_roofline(dtype, c.macs, kms)})
+                    "roofline": mfma_roofline(dtype, c.macs, kms, TRAFFIC.get(wlname))})
+        out["roofline"]["algorithmic_bytes"] = c.bytes
+        out["roofline"]["kernel_us"] = round(kms * 1e3, 2)
 
     if not args.no_others:
         def add(name, dtype, macs, byts, ms, info, extra=None):
