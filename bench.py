@@ -66,7 +66,7 @@ class ConvCase:
         self.wp = torch.empty(unit.unit_packed_weights_bytes(self.d, self.ut), dtype=torch.uint8, device=dev)
         (unit.unit_pack_weights_i8 if i8 else unit.unit_pack_weights_f16)(self.d, wd, self.wp)
         self.y = torch.empty((n, sh.k, p, q), dtype=torch.int32 if i8 else torch.float32, device=dev)
-        self.ws = torch.empty(max(unit.unit_conv2d_packed_workspace(self.d, self.ut), 256), dtype=torch.uint8, device=dev)
+        self.ws = torch.empty(max(unit.unit_conv2d_wpacked_workspace(self.d, self.ut), 256), dtype=torch.uint8, device=dev)
         es = 1 if i8 else 2
         self.macs = wl.macs(sh, n)
         self.bytes = (x.size + w.size) * es + self.y.numel() * 4      # each operand once, output once
@@ -86,8 +86,13 @@ class ConvCase:
             u.unit_conv2d_packed_f16(self.d, self.xp, self.wp, self.y, self.ws)
 
     def api(self):
-        self.pack()
-        self.conv()
+        """NCHW activations in, NCHW accumulators out, weights pre-packed: one library call
+        (pack_act + conv, or the fused NCHW-direct kernel where the shape allows it)."""
+        u = self.unit
+        if self.dtype == "i8":
+            u.unit_conv2d_wpacked_i8(self.d, self.x, self.wp, self.y, None, None, self.ws)
+        else:
+            u.unit_conv2d_wpacked_f16(self.d, self.x, self.wp, self.y, self.ws)
 
 
 class GemmCase:
@@ -227,24 +232,27 @@ def main():
         ms_eager = wall_ms(torch, step, max(steps // 10, 3), 2, use_graph=False)
         macs = sum(c.macs for c in seq)
         # per-layer kernel-only and pack durations from HIP events (same launch configuration)
-        t_conv = t_pack = 0.0
+        t_conv = t_pack = t_api = 0.0
         byts = 0
         per_layer = []
         for sh, c in uniq.items():
             mult = sum(1 for s in layers if s == sh)
             tc = event_ms(torch, c.conv, 50)
             tp = event_ms(torch, c.pack, 50)
+            ta = event_ms(torch, c.api, 50)
             t_conv += mult * tc
             t_pack += mult * tp
             byts += mult * c.bytes
-            per_layer.append({"shape": list(sh), "x": mult, "conv_us": round(tc * 1e3, 2), "pack_us": round(tp * 1e3, 2),
+            t_api += mult * ta
+            per_layer.append({"shape": list(sh), "x": mult, "api_us": round(ta * 1e3, 2),
+                              "conv_us": round(tc * 1e3, 2), "pack_us": round(tp * 1e3, 2),
                               "tile": tile_str(c.info)})
-        return ms, ms_eager, macs, t_conv, t_pack, byts, per_layer
+        return ms, ms_eager, macs, t_conv, t_pack, byts, per_layer, t_api
 
     wlname = args.workload
     if wlname in ("resnet50_i8_b1", "resnet50_f16_b16"):
         dtype, n, cid = ("i8", 1, 3) if wlname == "resnet50_i8_b1" else ("f16", 16, 4)
-        ms, ms_eager, macs, t_conv, t_pack, byts, per_layer = run_conv_set(dtype, n, cid, args.steps, args.warmup)
+        ms, ms_eager, macs, t_conv, t_pack, byts, per_layer, t_api = run_conv_set(dtype, n, cid, args.steps, args.warmup)
         tops = 2.0 * macs / (ms * 1e-3) / 1e12
         out.update({
             "metric": "int8 conv2d TOPS" if dtype == "i8" else "fp16 conv2d TFLOPS",
@@ -253,10 +261,12 @@ def main():
             "pct_of_mfma_peak": round(100.0 * tops / PEAK[dtype], 3),
             "config": {"workload": f"53 conv layers of a ResNet-50-shaped network, batch {n}, "
                                    f"{'int8->int32' if dtype == 'i8' else 'fp16->fp32'}, NCHW in -> NCHW out per layer "
-                                   "(pack_act + implicit-GEMM conv [+ split reduce]), weights pre-packed",
+                                   "(one unit_conv2d_wpacked call: pack_act + implicit-GEMM conv [+ split reduce], or the "
+                                   "fused NCHW-direct kernel for 1x1/stride-1 layers at batch 1), weights pre-packed",
                        "layers": 53, "batch": n, "gmacs_per_step": round(macs / 1e9, 3)},
             "launch": "one HIP graph per step (all kernels of the 53 layers), replayed",
             "eager_ms_per_step": round(ms_eager, 4),
+            "api_call_ms_per_step": round(t_api, 4),
             "kernel_only_ms_per_step": round(t_conv, 4), "pack_act_ms_per_step": round(t_pack, 4),
         })
         gbs = byts / (t_conv * 1e-3) / 1e9
@@ -311,7 +321,7 @@ def main():
         g = GemmCase(torch, unit, wl, 1, 1000, 2048, "i8")
         add("gemm FC 1x1000x2048", "i8", g.macs, g.bytes, event_ms(torch, g.run, 200), g.info)
         if wlname != "resnet50_f16_b16":
-            ms, _, macs, t_conv, t_pack, byts, _ = run_conv_set("f16", 16, 4, 20, 3)
+            ms, _, macs, t_conv, t_pack, byts, _, _ = run_conv_set("f16", 16, 4, 20, 3)
             others.append({"workload": "53 ResNet-50-shaped conv layers, batch 16, fp16->fp32, pack_act + conv",
                            "dtype": "f16", "ms": round(ms, 3), "value": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
                            "unit": "TFLOPS", "kernel_only_ms": round(t_conv, 3), "pack_act_ms": round(t_pack, 3),

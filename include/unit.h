@@ -169,6 +169,20 @@ int unit_conv2d_packed_i8(const unit_conv2d_desc *d, const void *x_packed, const
 int unit_conv2d_packed_f16(const unit_conv2d_desc *d, const void *x_packed, const void *w_packed,
                            float *y, void *ws, size_t ws_bytes, void *stream);
 
+/*
+ * conv2d on plain NCHW activations with pre-packed weights: the per-layer call of an
+ * inference loop whose weights were packed once.  Activations are packed into the workspace
+ * first, except for 1x1 / stride-1 / unpadded convs of a single image (n == 1, h*w*elem a
+ * multiple of 4 bytes, 16-byte aligned x, no requantise), which read NCHW directly inside
+ * the main kernel.  Outputs as in unit_conv2d_i8 / unit_conv2d_f16.
+ */
+size_t unit_conv2d_wpacked_workspace(const unit_conv2d_desc *d, int dtype);
+int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const void *w_packed,
+                           int32_t *y_i32, const unit_requant *rq, int8_t *y_i8,
+                           void *ws, size_t ws_bytes, void *stream);
+int unit_conv2d_wpacked_f16(const unit_conv2d_desc *d, const uint16_t *x, const void *w_packed,
+                            float *y, void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------ int8 network glue
  * Operators the chained int8 inference needs around the convolutions.  They work on the
  * packed int8 layout [n][h][w][cp].                                                        */

@@ -27,6 +27,10 @@ typedef _Float16 v8h  __attribute__((ext_vector_type(8)));
 
 enum { DT_I8 = 0, DT_F16 = 1 };
 enum { EPI_RAW = 0, EPI_REQUANT = 1 };
+// where the B operand (columns) comes from: a plain matrix, the packed-NHWC conv gather, or
+// an NCHW tensor read directly (1x1 stride-1 convs of one image: channel rows of pixels,
+// transposed on the way from LDS into the fragments)
+enum { BSRC_PLAIN = 0, BSRC_GATHER = 1, BSRC_NCHW = 2 };
 
 struct IgemmArgs {
     // operands (byte pointers; every row starts 16-byte aligned, reduction zero padded to 16 B)
@@ -36,6 +40,7 @@ struct IgemmArgs {
     int ksteps_per_split;                           // main-loop steps per grid.z slice
     // conv gather of B (CONV kernels only): packed activations [n][H][W][CB*16 bytes]
     int H, W, CB, P, Q, PQ, R, S, sh, sw, ph, pw;
+    int Cin;                                        // NCHW-direct kernels: real channel count
     // output: element (row, col) of image n = col / cols_per_img lives at
     //   out[n*img_stride + row*row_stride + col % cols_per_img]   (4-byte elements)
     void *out;  long row_stride;  long img_stride;  int cols_per_img;
@@ -156,7 +161,7 @@ struct IgemmCfg {
     static_assert(SMEM_BYTES <= 160 * 1024, "LDS capacity");
 };
 
-template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, int NST, int OCC, bool CONV, int EPI>
+template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, int NST, int OCC, int BSRC, int EPI>
 __global__ void __launch_bounds__(WGM * WGN * WGK * 64, OCC)
 igemm_kernel(const IgemmArgs g)
 {
@@ -165,6 +170,11 @@ igemm_kernel(const IgemmArgs g)
     typedef typename M::acc_t acc_t;
     typedef typename M::elem_t elem_t;
     constexpr int NW = C::NW, NCH = C::NCH, TM = C::TM, TN = C::TN, IA = C::IA, IB = C::IB, RPI = C::RPI;
+    constexpr bool CONV = (BSRC != BSRC_PLAIN);     // conv-style output indexing
+    constexpr int ES = (DT == DT_I8) ? 1 : 2;       // operand element bytes
+    constexpr int EPC = 16 / ES;                    // elements per 16-byte chunk
+    constexpr int CPR = BN * ES / 16;               // NCHW mode: 16-byte chunks per channel row of the B tile
+    constexpr int CRPI = 64 / CPR;                  // NCHW mode: channel rows per DMA instruction
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -215,7 +225,7 @@ igemm_kernel(const IgemmArgs g)
         offA[j] = (r < rows_here) ? (unsigned)(r * (int)g.lda + cT * 16) : UNIT_OOB;
     }
     const int cols_here = (g.cols - col0 < BN) ? g.cols - col0 : BN;
-    const __amdgpu_buffer_rsrc_t rsB = CONV
+    const __amdgpu_buffer_rsrc_t rsB = (BSRC != BSRC_PLAIN)
         ? make_rsrc(g.B, (unsigned)g.b_bytes)
         : make_rsrc(g.B + (long)col0 * g.ldb, (unsigned)((long)(cols_here - 1) * g.ldb + (long)g.kchunks * 16));
     unsigned offB[IB];
@@ -224,7 +234,13 @@ igemm_kernel(const IgemmArgs g)
     for (int j = 0; j < IB; ++j) {
         int r = (j * NW + wave) * RPI + lr_blk;
         bool valid = r < cols_here;
-        if (CONV) {
+        if (BSRC == BSRC_NCHW) {
+            // lane -> (channel row inside the DMA block, 16-byte chunk of pixels)
+            const int crow = (j * NW + wave) * CRPI + lane / CPR;
+            offB[j] = (unsigned)((crow * g.PQ + col0 + (lane % CPR) * EPC) * ES);
+            bh0[j] = crow;                          // channel row of this lane inside a step
+            bw0[j] = 0;
+        } else if (BSRC == BSRC_GATHER) {
             int cc = valid ? col0 + r : 0;
             int n = cc / g.PQ, pq = cc - n * g.PQ;
             int p = pq / g.Q, q = pq - p * g.Q;
@@ -242,7 +258,7 @@ igemm_kernel(const IgemmArgs g)
     // conv: reduction chunk kc -> (r, s, channel chunk cb), advanced incrementally per step
     int kc = ks_begin * NCH + cT;
     int cr = 0, cs = 0, ccb = 0;
-    if (CONV) {
+    if (BSRC == BSRC_GATHER) {
         int rs = kc / g.CB;
         ccb = kc - rs * g.CB;
         cr = rs / g.S;
@@ -258,7 +274,17 @@ igemm_kernel(const IgemmArgs g)
         for (int j = 0; j < IA; ++j)
             dma16(rsA, dst + j * NW * 1024, kok ? offA[j] + kbyte : UNIT_OOB);
         dst += BM * BKB;
-        if (CONV) {
+        if (BSRC == BSRC_NCHW) {
+            // channel rows of this step: chan0 .. chan0 + BKB/ES; rows past the real channel
+            // count or past the slice end come back as zeros
+            const int chan0 = (kc - cT) * EPC;
+            const int chan_end = (kend * EPC < g.Cin) ? kend * EPC : g.Cin;
+#pragma unroll
+            for (int j = 0; j < IB; ++j) {
+                bool ok = chan0 + bh0[j] < chan_end;
+                dma16(rsB, dst + j * NW * 1024, ok ? offB[j] + (unsigned)(chan0 * g.PQ * ES) : UNIT_OOB);
+            }
+        } else if (BSRC == BSRC_GATHER) {
             const unsigned tap = (unsigned)((cr * g.W + cs) * g.CB + ccb) * 16u;
 #pragma unroll
             for (int j = 0; j < IB; ++j) {
@@ -311,9 +337,33 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             fa[slot][i] = *reinterpret_cast<const v4i *>(sA + (a_row + i * MF) * BKB + ((ch ^ a_swz) << 4));
+        if (BSRC == BSRC_NCHW) {
+            // B tile is [channel][pixel]: gather this lane's 16 bytes of consecutive channels
+            // for its pixel column, one element per LDS read
+            const int k0 = ch * EPC;                 // first channel row of this lane's chunk
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-            fb[slot][j] = *reinterpret_cast<const v4i *>(sB + (b_row + j * MF) * BKB + ((ch ^ b_swz) << 4));
+            for (int j = 0; j < TN; ++j) {
+                const uint8_t *src = sB + k0 * (BN * ES) + (b_row + j * MF) * ES;
+                unsigned w[4];
+#pragma unroll
+                for (int d = 0; d < 4; ++d) {
+                    if (ES == 1) {
+                        unsigned b0 = src[(4 * d + 0) * BN], b1 = src[(4 * d + 1) * BN];
+                        unsigned b2 = src[(4 * d + 2) * BN], b3 = src[(4 * d + 3) * BN];
+                        w[d] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+                    } else {
+                        unsigned h0 = *reinterpret_cast<const uint16_t *>(src + (2 * d + 0) * BN * 2);
+                        unsigned h1 = *reinterpret_cast<const uint16_t *>(src + (2 * d + 1) * BN * 2);
+                        w[d] = h0 | (h1 << 16);
+                    }
+                }
+                fb[slot][j] = v4i{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+                fb[slot][j] = *reinterpret_cast<const v4i *>(sB + (b_row + j * MF) * BKB + ((ch ^ b_swz) << 4));
+        }
     };
 
     if (ks_begin < ks_end) {

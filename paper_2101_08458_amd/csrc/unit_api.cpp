@@ -7,13 +7,13 @@
 #include "unit_internal.h"
 
 namespace unit {
-hipError_t launch_igemm_i8(bool conv, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
-hipError_t launch_igemm_f16(bool conv, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
+hipError_t launch_igemm_i8(int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
+hipError_t launch_igemm_f16(int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
 
-hipError_t launch_igemm(int dtype, bool conv, int tile, const IgemmArgs &a, int split_k, hipStream_t st)
+hipError_t launch_igemm(int dtype, int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st)
 {
-    return dtype == DT_I8 ? launch_igemm_i8(conv, tile, a, split_k, st)
-                          : launch_igemm_f16(conv, tile, a, split_k, st);
+    return dtype == DT_I8 ? launch_igemm_i8(bsrc, tile, a, split_k, st)
+                          : launch_igemm_f16(bsrc, tile, a, split_k, st);
 }
 }  // namespace unit
 
@@ -83,14 +83,15 @@ void fill_tile_info(const TileChoice &ch, unit_tile_info *out)
 }
 
 // Runs the main kernel (+ the split reduce when the selector splits across workgroups).
-int run_igemm(int dtype, bool conv, IgemmArgs a, long out_elems, int K, int PQ,
+int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
               void *ws, size_t ws_bytes, hipStream_t st, bool allow_split = true)
 {
+    const bool conv = bsrc != BSRC_PLAIN;
     TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, conv, allow_split);
     a.ksteps_per_split = ch.ksteps_per_split;
     if (ch.split_k == 1) {
         a.split_stride = 0;
-        UNIT_HIP(launch_igemm(dtype, conv, ch.tile, a, 1, st));
+        UNIT_HIP(launch_igemm(dtype, bsrc, ch.tile, a, 1, st));
         return UNIT_OK;
     }
     const long slice = (out_elems + 3) & ~3L;     // 16-byte aligned slices for the reduce kernel
@@ -104,7 +105,7 @@ int run_igemm(int dtype, bool conv, IgemmArgs a, long out_elems, int K, int PQ,
     if (!conv) {                                   // partials of a matmul are dense [rows][cols]
         m.row_stride = a.cols;
     }
-    UNIT_HIP(launch_igemm(dtype, conv, ch.tile, m, ch.split_k, st));
+    UNIT_HIP(launch_igemm(dtype, bsrc, ch.tile, m, ch.split_k, st));
     ReduceArgs r;
     std::memset(&r, 0, sizeof r);
     r.partials = ws;  r.nsplit = ch.split_k;  r.split_stride = slice;
@@ -116,9 +117,20 @@ int run_igemm(int dtype, bool conv, IgemmArgs a, long out_elems, int K, int PQ,
     return UNIT_OK;
 }
 
+// A 1x1, stride-1, unpadded conv of one image can read its NCHW input directly: the
+// channel rows are DMAed as they are and transposed between LDS and the fragments, which
+// saves the separate pack_act launch.  Needs 4-byte aligned channel rows.
+bool nchw_direct_ok(const unit_conv2d_desc *d, int dtype, const void *x, const unit_requant *rq)
+{
+    return d->n == 1 && d->r == 1 && d->s == 1 && d->stride_h == 1 && d->stride_w == 1 &&
+           d->pad_h == 0 && d->pad_w == 0 && rq == nullptr &&
+           ((long)d->h * d->w * elem_size(dtype)) % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+}
+
+// `xp` is the packed activation tensor, or (nchw_direct) the caller's NCHW tensor itself.
 int conv_packed(const unit_conv2d_desc *d, int dtype, const void *xp, const void *wp,
                 void *y_raw, const unit_requant *rq, int8_t *y_i8, void *y_packed,
-                void *ws, size_t ws_bytes, void *stream)
+                void *ws, size_t ws_bytes, void *stream, bool nchw_direct = false)
 {
     ConvGeom g;
     int rc = conv_geom(d, dtype, &g);
@@ -139,7 +151,8 @@ int conv_packed(const unit_conv2d_desc *d, int dtype, const void *xp, const void
     a.B = static_cast<const uint8_t *>(xp);  a.ldb = 0;                      a.cols = (int)g.cols;
     a.kchunks = g.kchunks;
     a.H = d->h;  a.W = d->w;  a.CB = g.cp * es / 16;  a.P = g.p;  a.Q = g.q;  a.PQ = g.p * g.q;
-    a.b_bytes = (long)d->n * d->h * d->w * g.cp * es;
+    a.b_bytes = nchw_direct ? (long)d->c * d->h * d->w * es : (long)d->n * d->h * d->w * g.cp * es;
+    a.Cin = d->c;
     a.R = d->r;  a.S = d->s;  a.sh = d->stride_h;  a.sw = d->stride_w;  a.ph = d->pad_h;  a.pw = d->pad_w;
     a.out = y_raw;  a.row_stride = a.PQ;  a.img_stride = (long)d->k * a.PQ;  a.cols_per_img = a.PQ;
     if (rq) {
@@ -151,13 +164,27 @@ int conv_packed(const unit_conv2d_desc *d, int dtype, const void *xp, const void
     } else {
         a.epi = EPI_RAW;  a.store_raw = 1;
     }
-    return run_igemm(dtype, true, a, g.out_elems, d->k, a.PQ, ws, ws_bytes, static_cast<hipStream_t>(stream));
+    return run_igemm(dtype, nchw_direct ? BSRC_NCHW : BSRC_GATHER, a, g.out_elems, d->k, a.PQ, ws, ws_bytes,
+                     static_cast<hipStream_t>(stream));
 }
 
 size_t conv_split_bytes(const ConvGeom &g, int dtype)
 {
     TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true);
     return ch.split_k > 1 ? align256((size_t)ch.split_k * ((g.out_elems + 3) & ~3L) * 4) : 0;
+}
+
+int conv_wpacked(const unit_conv2d_desc *d, int dtype, const void *x, const void *wp,
+                 void *y_raw, const unit_requant *rq, int8_t *y_i8,
+                 void *ws, size_t ws_bytes, void *stream);
+bool nchw_direct_ok(const unit_conv2d_desc *d, int dtype, const void *x, const unit_requant *rq);
+
+// workspace conv_wpacked needs for this call (after the packed weights, if any)
+size_t wpacked_need(const unit_conv2d_desc *d, int dtype, const ConvGeom &g, const void *x, const unit_requant *rq)
+{
+    size_t split_b = conv_split_bytes(g, dtype);
+    return nchw_direct_ok(d, dtype, x, rq) ? split_b
+                                           : unit_packed_act_bytes(d->n, d->c, d->h, d->w, dtype) + split_b;
 }
 
 int conv_plain(const unit_conv2d_desc *d, int dtype, const void *x, const void *w,
@@ -173,18 +200,36 @@ int conv_plain(const unit_conv2d_desc *d, int dtype, const void *x, const void *
     } else if (!y_raw || y_i8) {
         return UNIT_EINVAL;
     }
-    size_t act_b = unit_packed_act_bytes(d->n, d->c, d->h, d->w, dtype);
     size_t wt_b = unit_packed_weights_bytes(d, dtype);
-    size_t split_b = conv_split_bytes(g, dtype);
-    if (!ws || ws_bytes < act_b + wt_b + split_b) return UNIT_EWORKSPACE;
+    if (!ws || ws_bytes < wt_b + wpacked_need(d, dtype, g, x, rq)) return UNIT_EWORKSPACE;
     if (!aligned256(ws)) return UNIT_EINVAL;
+    uint8_t *wp = static_cast<uint8_t *>(ws);
+    UNIT_HIP(launch_pack_weights(dtype, d->k, d->c, d->r, d->s, w, wp, static_cast<hipStream_t>(stream)));
+    return conv_wpacked(d, dtype, x, wp, y_raw, rq, y_i8, wp + wt_b, ws_bytes - wt_b, stream);
+}
+
+// NCHW activations + packed weights: fused direct read when possible, else pack_act into the
+// workspace followed by the packed kernel.
+int conv_wpacked(const unit_conv2d_desc *d, int dtype, const void *x, const void *wp,
+                 void *y_raw, const unit_requant *rq, int8_t *y_i8,
+                 void *ws, size_t ws_bytes, void *stream)
+{
+    ConvGeom g;
+    int rc = conv_geom(d, dtype, &g);
+    if (rc != UNIT_OK) return rc;
+    if (!x || !wp) return UNIT_EINVAL;
+    if (ws && !aligned256(ws)) return UNIT_EINVAL;
+    size_t split_b = conv_split_bytes(g, dtype);
+    if (!aligned16(wp)) return UNIT_EINVAL;
+    if (nchw_direct_ok(d, dtype, x, rq)) {
+        if (split_b && (!ws || ws_bytes < split_b)) return UNIT_EWORKSPACE;
+        return conv_packed(d, dtype, x, wp, y_raw, rq, y_i8, nullptr, ws, ws_bytes, stream, true);
+    }
+    size_t act_b = unit_packed_act_bytes(d->n, d->c, d->h, d->w, dtype);
+    if (!ws || ws_bytes < act_b + split_b) return UNIT_EWORKSPACE;
     uint8_t *xp = static_cast<uint8_t *>(ws);
-    uint8_t *wp = xp + act_b;
-    uint8_t *part = wp + wt_b;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    UNIT_HIP(launch_pack_act(dtype, d->n, d->c, d->h, d->w, x, xp, st));
-    UNIT_HIP(launch_pack_weights(dtype, d->k, d->c, d->r, d->s, w, wp, st));
-    return conv_packed(d, dtype, xp, wp, y_raw, rq, y_i8, nullptr, split_b ? part : nullptr, split_b, stream);
+    UNIT_HIP(launch_pack_act(dtype, d->n, d->c, d->h, d->w, x, xp, static_cast<hipStream_t>(stream)));
+    return conv_packed(d, dtype, xp, wp, y_raw, rq, y_i8, nullptr, split_b ? xp + act_b : nullptr, split_b, stream);
 }
 
 struct MatmulGeom {
@@ -248,7 +293,7 @@ int matmul_any(int dtype, int m, int n, int k, const void *A, long lda, const vo
     a.out = C;  a.row_stride = ldc;  a.img_stride = 0;  a.cols_per_img = n;
     a.epi = EPI_RAW;  a.store_raw = 1;
     // the split reduce writes a dense [m][n] result: only usable when ldc == n
-    return run_igemm(dtype, false, a, (long)m * n, 1, n, g.split_bytes ? wsp : nullptr, g.split_bytes, st,
+    return run_igemm(dtype, BSRC_PLAIN, a, (long)m * n, 1, n, g.split_bytes ? wsp : nullptr, g.split_bytes, st,
                      ldc == n);
 }
 
@@ -417,6 +462,28 @@ int unit_conv2d_packed_i8(const unit_conv2d_desc *d, const void *xp, const void 
                           void *ws, size_t ws_bytes, void *stream)
 {
     return conv_packed(d, UNIT_I8, xp, wp, y_i32, rq, y_i8, y_packed, ws, ws_bytes, stream);
+}
+
+size_t unit_conv2d_wpacked_workspace(const unit_conv2d_desc *d, int dtype)
+{
+    ConvGeom g;
+    if (conv_geom(d, dtype, &g) != UNIT_OK) return 0;
+    return unit_packed_act_bytes(d->n, d->c, d->h, d->w, dtype) + conv_split_bytes(g, dtype);
+}
+
+int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const void *wp,
+                           int32_t *y_i32, const unit_requant *rq, int8_t *y_i8,
+                           void *ws, size_t ws_bytes, void *stream)
+{
+    if (rq ? (!rq->scale || !y_i8) : (!y_i32 || y_i8)) return UNIT_EINVAL;
+    return conv_wpacked(d, UNIT_I8, x, wp, y_i32, rq, y_i8, ws, ws_bytes, stream);
+}
+
+int unit_conv2d_wpacked_f16(const unit_conv2d_desc *d, const uint16_t *x, const void *wp,
+                            float *y, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!y) return UNIT_EINVAL;
+    return conv_wpacked(d, UNIT_F16, x, wp, y, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 int unit_conv2d_packed_f16(const unit_conv2d_desc *d, const void *xp, const void *wp,

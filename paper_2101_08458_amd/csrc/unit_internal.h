@@ -31,7 +31,7 @@ struct TileChoice {
 TileChoice select_tile(int rows, int cols, int kchunks, int dtype, bool conv, bool allow_split = true);
 
 // launchers (kernels_*.hip).  All return hipError_t from the launch.
-hipError_t launch_igemm(int dtype, bool conv, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
+hipError_t launch_igemm(int dtype, int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
 
 hipError_t launch_pack_act(int dtype, int n, int c, int h, int w, const void *x, void *xp, hipStream_t st);
 hipError_t launch_pack_weights(int dtype, int k, int c, int r, int s, const void *w, void *wp, hipStream_t st);

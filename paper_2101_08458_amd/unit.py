@@ -52,6 +52,7 @@ EXPORTS = [
     "unit_pack_act_i8", "unit_pack_act_f16", "unit_pack_weights_i8", "unit_pack_weights_f16",
     "unit_unpack_act_i8", "unit_conv2d_packed_i8", "unit_conv2d_packed_f16",
     "unit_maxpool_packed_i8", "unit_global_avgpool_packed_i8", "unit_widen_residual_i8",
+    "unit_conv2d_wpacked_workspace", "unit_conv2d_wpacked_i8", "unit_conv2d_wpacked_f16",
 ]
 
 
@@ -92,6 +93,9 @@ def load():
         "unit_unpack_act_i8": (ctypes.c_int, [i32, i32, i32, i32, vp, vp, vp]),
         "unit_conv2d_packed_i8": (ctypes.c_int, [dp, vp, vp, vp, rp, vp, vp, vp, sz, vp]),
         "unit_conv2d_packed_f16": (ctypes.c_int, [dp, vp, vp, vp, vp, sz, vp]),
+        "unit_conv2d_wpacked_workspace": (sz, [dp, ctypes.c_int]),
+        "unit_conv2d_wpacked_i8": (ctypes.c_int, [dp, vp, vp, vp, rp, vp, vp, sz, vp]),
+        "unit_conv2d_wpacked_f16": (ctypes.c_int, [dp, vp, vp, vp, vp, sz, vp]),
         "unit_maxpool_packed_i8": (ctypes.c_int, [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]),
         "unit_global_avgpool_packed_i8": (ctypes.c_int, [i32, i32, i32, i32, vp, vp, vp, vp]),
         "unit_widen_residual_i8": (ctypes.c_int, [i32, i32, i32, i32, vp, i32, vp, vp]),
@@ -253,6 +257,23 @@ def unit_conv2d_packed_f16(d, xp, wp, y, ws=None, stream=None):
     wsp, wsb = _ws(ws)
     _check(load().unit_conv2d_packed_f16(ctypes.byref(d), _p(xp), _p(wp), _p(y), wsp, wsb, _stream(stream)),
            "unit_conv2d_packed_f16")
+
+
+def unit_conv2d_wpacked_workspace(d, dtype):
+    return load().unit_conv2d_wpacked_workspace(ctypes.byref(d), dtype)
+
+
+def unit_conv2d_wpacked_i8(d, x, wp, y_i32, rq, y_i8, ws=None, stream=None):
+    wsp, wsb = _ws(ws)
+    _check(load().unit_conv2d_wpacked_i8(ctypes.byref(d), _p(x), _p(wp), _p(y_i32),
+                                         ctypes.byref(rq) if rq is not None else None, _p(y_i8),
+                                         wsp, wsb, _stream(stream)), "unit_conv2d_wpacked_i8")
+
+
+def unit_conv2d_wpacked_f16(d, x, wp, y, ws=None, stream=None):
+    wsp, wsb = _ws(ws)
+    _check(load().unit_conv2d_wpacked_f16(ctypes.byref(d), _p(x), _p(wp), _p(y), wsp, wsb, _stream(stream)),
+           "unit_conv2d_wpacked_f16")
 
 
 def unit_maxpool_packed_i8(n, c, h, w, window, stride, pad, xp, yp, stream=None):

@@ -202,6 +202,42 @@ def test_conv_i8_small_all_tiles(sh, n):
                 assert same(run_conv_i8(sh, n, x, w), ref), (tile, split)
 
 
+NCHW_DIRECT = [   # 1x1 / stride 1 / one image: read straight from NCHW when h*w*elem % 4 == 0
+    wl.ConvShape(20, 14, 14, 33, 1, 1, 1, 0), wl.ConvShape(64, 56, 56, 64, 1, 1, 1, 0),
+    wl.ConvShape(70, 10, 10, 130, 1, 1, 1, 0), wl.ConvShape(256, 6, 6, 40, 1, 1, 1, 0),
+    wl.ConvShape(3, 18, 18, 5, 1, 1, 1, 0), wl.ConvShape(130, 7, 7, 64, 1, 1, 1, 0),   # 7x7: falls back to pack + gather
+]
+
+
+@pytest.mark.parametrize("sh", NCHW_DIRECT)
+def test_conv_wpacked_nchw_direct(sh):
+    """Pre-packed weights + NCHW activations, the per-layer call the benchmark times."""
+    st, pd = (1, 1), (0, 0)
+    d = unit.conv_desc(1, sh.c, sh.h, sh.w, sh.k, 1, 1, 1, 0)
+    x, w = wl.conv_inputs_i8(sh, 1, 32, sh.c)
+    ref = oracle.conv2d_i8(x, w, st, pd)
+    xh, wh = wl.conv_inputs_f16(sh, 1, 33, sh.c)
+    refh = oracle.conv2d_f16(xh, wh, st, pd)
+    truth, mag = oracle.conv2d_f16_f64(xh, wh, st, pd)
+    xd, xhd = dev(x), dev(xh)
+    wp = ws_bytes(unit.unit_packed_weights_bytes(d, unit.UNIT_I8))
+    wph = ws_bytes(unit.unit_packed_weights_bytes(d, unit.UNIT_F16))
+    unit.unit_pack_weights_i8(d, dev(w), wp)
+    unit.unit_pack_weights_f16(d, dev(wh), wph)
+    for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 2)]:
+        announce("wpacked", sh, "tile", tile, "split", split)
+        with forced(tile=tile, split=split):
+            y = torch.full((1, sh.k, sh.h, sh.w), -7, dtype=torch.int32, device="cuda:0")
+            unit.unit_conv2d_wpacked_i8(d, xd, wp, y, None, None, ws_bytes(unit.unit_conv2d_wpacked_workspace(d, unit.UNIT_I8)))
+            yh = torch.empty((1, sh.k, sh.h, sh.w), dtype=torch.float32, device="cuda:0")
+            unit.unit_conv2d_wpacked_f16(d, xhd, wph, yh, ws_bytes(unit.unit_conv2d_wpacked_workspace(d, unit.UNIT_F16)))
+            torch.cuda.synchronize()
+        assert same(host(y), ref, f"i8 tile {tile} split {split}")
+        got = host(yh)
+        assert f16_rel_err(got, refh, sh.c) <= 1e-3, (tile, split)
+        assert np.all(np.abs(got - truth) <= 2 * sh.c * 2.0 ** -24 * mag + 1e-30), (tile, split)
+
+
 def test_conv_i8_asymmetric_geometry():
     """Different stride / pad / window per axis (the C ABI carries them separately)."""
     g = wl.rng(31)
