@@ -87,3 +87,23 @@ def test_error_paths_return_before_launch(lib):
     assert lib.unit_matmul_f16(4, 4, 131072, null, 131072, fake, 131072, fake, 4, null, 0, st) == unit.UNIT_EINVAL
     assert lib.unit_pack_act_i8(1, 3, 4, 4, fake, fake, 16, st) == unit.UNIT_EWORKSPACE
     assert lib.unit_maxpool_packed_i8(1, 16, 8, 8, 3, 2, 3, fake, fake, st) == unit.UNIT_EINVAL
+
+
+def test_size_limits_and_wpacked_errors(lib):
+    fake, st = 0x1000, 0
+    # every tensor addressed through a buffer descriptor must stay below 2 GiB
+    big_act = unit.conv_desc(64, 512, 256, 256, 8, 1, 1, 1, 0)           # 2 GiB of int8 activations
+    assert lib.unit_conv2d_packed_i8(ctypes.byref(big_act), fake, fake, fake, None, None, None, None, 0, st) == unit.UNIT_ENOTSUP
+    big_out = unit.conv_desc(32, 16, 512, 512, 64, 1, 1, 1, 0)           # 2 GiB of int32 outputs
+    assert lib.unit_conv2d_packed_i8(ctypes.byref(big_out), fake, fake, fake, None, None, None, None, 0, st) == unit.UNIT_ENOTSUP
+    assert unit.unit_conv2d_workspace(big_act, unit.UNIT_I8) == 0
+    assert lib.unit_matmul_i8(4, 4, 16, fake, 1 << 24, fake, 16, fake, 4, None, 0, st) == unit.UNIT_ENOTSUP
+    d = unit.conv_desc(1, 64, 8, 8, 32, 1, 1, 1, 0)
+    f = lib.unit_conv2d_wpacked_i8
+    assert f(ctypes.byref(d), None, fake, fake, None, None, None, 0, st) == unit.UNIT_EINVAL
+    assert f(ctypes.byref(d), fake, fake, None, None, None, None, 0, st) == unit.UNIT_EINVAL
+    assert f(ctypes.byref(d), fake, fake + 4, fake, None, None, None, 0, st) == unit.UNIT_EINVAL       # misaligned packed weights
+    d3 = unit.conv_desc(1, 64, 8, 8, 32, 3, 3, 1, 1)                      # 3x3 needs the pack workspace
+    assert f(ctypes.byref(d3), fake, fake, fake, None, None, None, 0, st) == unit.UNIT_EWORKSPACE
+    assert unit.unit_conv2d_wpacked_workspace(d3, unit.UNIT_I8) >= 64 * 64
+    assert lib.unit_conv2d_wpacked_f16(ctypes.byref(d), fake, fake, None, None, 0, st) == unit.UNIT_EINVAL

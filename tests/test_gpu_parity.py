@@ -453,3 +453,39 @@ def test_pack_roundtrip_and_glue_ops():
     unit.unit_widen_residual_i8(n, c, h, w_, xp, 64, res)
     torch.cuda.synchronize()
     assert same(host(res), oracle.widen_scale_i8(x, 64))
+
+
+# ------------------------------------------------------------------ edge and degenerate cases
+
+def test_degenerate_shapes():
+    cases = [
+        (wl.ConvShape(1, 1, 1, 1, 1, 1, 1, 0), 1),            # one MAC
+        (wl.ConvShape(1, 5, 7, 1, 3, 3, 1, 2), 2),            # pad = window - 1: first outputs see one tap
+        (wl.ConvShape(5, 9, 9, 3, 1, 1, 3, 0), 1),            # stride larger than the window
+        (wl.ConvShape(17, 3, 3, 9, 3, 3, 1, 0), 3),           # output 1x1: a pure dot product per channel
+        (wl.ConvShape(33, 6, 5, 65, 3, 3, 1, 1), 5),          # tiles straddle image boundaries (n*p*q = 150)
+        (wl.ConvShape(8, 12, 12, 8, 5, 5, 2, 2), 1),
+    ]
+    for sh, n in cases:
+        x, w = wl.conv_inputs_i8(sh, n, 60, sh.c)
+        ref = oracle.conv2d_i8(x, w, (sh.stride,) * 2, (sh.pad,) * 2)
+        announce("degenerate i8", sh, n)
+        assert same(run_conv_i8(sh, n, x, w), ref, str(sh))
+        xh, wh = wl.conv_inputs_f16(sh, n, 61, sh.c)
+        refh = oracle.conv2d_f16(xh, wh, (sh.stride,) * 2, (sh.pad,) * 2)
+        announce("degenerate f16", sh, n)
+        assert f16_rel_err(run_conv_f16(sh, n, xh, wh), refh, sh.c * sh.r * sh.s) <= 1e-3, sh
+    announce("matmul 1x1x1")
+    assert same(run_matmul_i8(np.array([[-128]], np.int8), np.array([[-128]], np.int8)), np.array([[16384]]))
+
+
+def test_matmul_i8_longest_exact_reduction():
+    """k = 131071 with every product at its extreme: the int32 sum is 2147467264 < 2^31."""
+    K = unit.UNIT_MAX_REDUCTION_I8
+    A = np.full((3, K), -128, np.int8)
+    B = np.full((5, K), -128, np.int8)
+    B[1] = 127; B[2, ::2] = 127
+    announce("matmul_i8 k=131071")
+    got = run_matmul_i8(A, B)
+    assert same(got, A.astype(np.int64) @ B.astype(np.int64).T, "longest reduction")
+    assert got[0, 0] == K * 16384 and got.max() < 2 ** 31
