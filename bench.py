@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet50_i8_b1",
                     choices=["resnet50_i8_b1", "gemm_i8_4096", "large_conv_i8", "gemm_f16_4096",
-                             "large_conv_f16", "resnet50_f16_b16"])
+                             "large_conv_f16", "resnet50_f16_b16", "table1_ablation"])
     ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -190,6 +190,56 @@ def cpu_baseline(wl, budget_s=12.0):
                                         f"{macs / 1e9:.2f} GMAC in {secs:.2f} s, OpenMP direct loops"}
 
 
+def table1_ablation(torch, unit, wl, out):
+    """The paper's per-kernel experiment (Table I layers; its GPU ablation Generic -> +SplitK
+    -> +Tune, Section VI-B) on this hardware: batch 1, kernel only (packed operands).
+    Generic = one fixed tile (64x64, 2x2 waves) without a reduction split; +SplitK = the same
+    tile with the best grid split; +Tune = best tile and split of the sweep; selector = what
+    the library's rule picks.  Fused H*W (the paper's FuseDim) is inherent in the implicit
+    GEMM and cannot be switched off."""
+    os.environ.pop("UNIT_TILE", None)
+    os.environ.pop("UNIT_SPLITK", None)
+    splits = [1, 2, 3, 4, 6, 8, 12]
+    rows = []
+    for dtype in ("f16", "i8"):
+        for idx, sh in enumerate(wl.TABLE1):
+            c = ConvCase(torch, unit, wl, sh, 1, dtype, 6, idx)
+
+            def timed(tile, split):
+                os.environ["UNIT_TILE"], os.environ["UNIT_SPLITK"] = str(tile), str(split)
+                try:
+                    if unit.unit_select_conv2d(c.d, c.ut).split_k != split:
+                        return None
+                    need = unit.unit_conv2d_packed_workspace(c.d, c.ut)
+                    if need > c.ws.numel():
+                        c.ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+                    return event_ms(torch, c.conv, 20) * 1e3
+                finally:
+                    os.environ.pop("UNIT_TILE", None)
+                    os.environ.pop("UNIT_SPLITK", None)
+
+            generic = timed(3, 1)
+            splitk = min(t for t in (timed(3, s) for s in splits) if t is not None)
+            tuned = min(t for t in (timed(tl, s) for tl in (1, 2, 3, 4) for s in splits) if t is not None)
+            need = unit.unit_conv2d_packed_workspace(c.d, c.ut)
+            if need > c.ws.numel():
+                c.ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
+            auto = event_ms(torch, c.conv, 20) * 1e3
+            rows.append({"dtype": dtype, "layer": idx + 1, "shape": list(sh), "generic_us": round(generic, 2),
+                         "splitk_us": round(splitk, 2), "tuned_us": round(tuned, 2), "selector_us": round(auto, 2),
+                         "selector_tile": tile_str(unit.unit_select_conv2d(c.d, c.ut))})
+            del c
+    out.update({"metric": "Table I conv layers, batch 1, kernel-only us per layer", "unit": "us", "dtype": "f16+i8",
+                "config": {"workload": "16 conv layers of the paper's Table I, batch 1, packed operands"},
+                "value": round(sum(r["selector_us"] for r in rows if r["dtype"] == "f16"), 2),
+                "higher_is_better": False, "layers": rows})
+    for dt in ("f16", "i8"):
+        sel = [r for r in rows if r["dtype"] == dt]
+        gm = lambda key: float(np.exp(np.mean([np.log(r["generic_us"] / r[key]) for r in sel])))
+        out[f"geomean_speedup_over_generic_{dt}"] = {"splitk": round(gm("splitk_us"), 3), "tuned": round(gm("tuned_us"), 3),
+                                                      "selector": round(gm("selector_us"), 3)}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -250,6 +300,10 @@ def main():
         return ms, ms_eager, macs, t_conv, t_pack, byts, per_layer, t_api
 
     wlname = args.workload
+    if wlname == "table1_ablation":
+        table1_ablation(torch, unit, wl, out)
+        print(json.dumps(out))
+        return
     if wlname in ("resnet50_i8_b1", "resnet50_f16_b16"):
         dtype, n, cid = ("i8", 1, 3) if wlname == "resnet50_i8_b1" else ("f16", 16, 4)
         ms, ms_eager, macs, t_conv, t_pack, byts, per_layer, t_api = run_conv_set(dtype, n, cid, args.steps, args.warmup)

@@ -284,6 +284,19 @@ def test_conv_i8_table1_layers():
         assert same(run_conv_i8(sh, 1, x, w), ref), sh
 
 
+def test_conv_f16_table1_layers():
+    for idx, sh in enumerate(wl.TABLE1):
+        x, w = wl.conv_inputs_f16(sh, 1, 7, idx)
+        st, pd = (sh.stride,) * 2, (sh.pad,) * 2
+        ref = oracle.conv2d_f16(x, w, st, pd)
+        truth, mag = oracle.conv2d_f16_f64(x, w, st, pd)
+        kred = sh.c * sh.r * sh.s
+        announce("conv_f16 table1", idx + 1, sh)
+        got = run_conv_f16(sh, 1, x, w)
+        assert f16_rel_err(got, ref, kred) <= 1e-3, sh
+        assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), sh
+
+
 @pytest.mark.parametrize("sh,n", SMALL_CONVS[:6])
 def test_conv_f16_small_all_tiles(sh, n):
     x, w = wl.conv_inputs_f16(sh, n, 40, sh.c)
