@@ -52,6 +52,10 @@ def _load():
     L.oracle_conv2d_i8.argtypes = conv_args
     L.oracle_conv2d_f16.argtypes = conv_args
     L.oracle_conv2d_f16_f64.argtypes = conv_args + [p]
+    L.oracle_conv3d_i8.argtypes = [i] * 9 + [p, p, p, p, p]
+    L.oracle_conv3d_f16.argtypes = [i] * 9 + [p, p, p, p, p, p, p]
+    L.oracle_conv3d_i8.restype = None
+    L.oracle_conv3d_f16.restype = None
     mm_args = [i, i, i, p, l, p, l, p, l]
     L.oracle_matmul_i8.argtypes = mm_args
     L.oracle_matmul_f16.argtypes = mm_args
@@ -138,6 +142,40 @@ def conv2d_f16_f64(x, w, stride=(1, 1), pad=(0, 0)):
     ya = np.empty(oshape, np.float64)
     _load().oracle_conv2d_f16_f64(*dims, _ptr(x), _ptr(w), _ptr(y), _ptr(ya))
     return y, ya
+
+
+def _conv3_dims(x, w, stride, pad):
+    N, C, D, H, W = x.shape
+    K, C2, T, R, S = w.shape
+    if C2 != C:
+        raise ValueError("channel mismatch")
+    O, P, Q = (out_dim(D, T, stride[0], pad[0]), out_dim(H, R, stride[1], pad[1]),
+               out_dim(W, S, stride[2], pad[2]))
+    if min(O, P, Q) <= 0:
+        raise ValueError("empty output")
+    st = np.asarray(stride, np.int32)
+    pd = np.asarray(pad, np.int32)
+    return (N, C, D, H, W, K, T, R, S), st, pd, (N, K, O, P, Q)
+
+
+def conv3d_i8(x, w, stride=(1, 1, 1), pad=(0, 0, 0)):
+    """x int8 NCDHW, w int8 KCTRS -> int32 NKOPQ."""
+    _chk(x, np.int8), _chk(w, np.int8)
+    dims, st, pd, oshape = _conv3_dims(x, w, stride, pad)
+    y = np.empty(oshape, np.int32)
+    _load().oracle_conv3d_i8(*dims, _ptr(st), _ptr(pd), _ptr(x), _ptr(w), _ptr(y))
+    return y
+
+
+def conv3d_f16(x, w, stride=(1, 1, 1), pad=(0, 0, 0)):
+    """binary16 bit patterns -> (fp32 result, fp64-accumulated value, sum of |products|)."""
+    _chk(x, np.uint16), _chk(w, np.uint16)
+    dims, st, pd, oshape = _conv3_dims(x, w, stride, pad)
+    y = np.empty(oshape, np.float32)
+    y64 = np.empty(oshape, np.float64)
+    ya = np.empty(oshape, np.float64)
+    _load().oracle_conv3d_f16(*dims, _ptr(st), _ptr(pd), _ptr(x), _ptr(w), _ptr(y), _ptr(y64), _ptr(ya))
+    return y, y64, ya
 
 
 def _mm_dims(A, B):

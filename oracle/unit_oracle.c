@@ -28,6 +28,8 @@
  *
  * Pins (tests/test_oracle_*.py): brute force in pure Python on tiny shapes,
  * delta and identity kernels, the all-ones closed form, conv == im2col-matmul,
+ * conv3d against a float64 library conv3d, a scatter-form brute force and its depth-1
+ * reduction to conv2d,
  * float64 library conv/matmul on integer-valued tensors, the 16x4 VNNI lane
  * semantics, the 16x16x16 Tensor Core shape, Table I output sizes, the requant
  * tie/saturation table and an exhaustive 2^16 sweep against exact rational
@@ -187,6 +189,83 @@ void oracle_conv2d_f16_f64(int N, int C, int H, int W, int K, int R, int S,
                     y[o] = acc;
                     if (yabs) yabs[o] = aacc;
                 }
+}
+
+/* ------------------------------------------------------------------ conv3d */
+
+/*
+ * The paper's extensibility experiment (Section VI-C, "3D Convolution") feeds the same
+ * pipeline a conv3d: the 2-D definition with one more spatial axis.
+ * x: [N,C,D,H,W], w: [K,C,T,R,S], y: [N,K,O,P,Q];  zero padding, no dilation.
+ * stride = {sd,sh,sw}, pad = {pd,ph,pw}.
+ */
+void oracle_conv3d_i8(int N, int C, int D, int H, int W, int K, int T, int R, int S,
+                      const int *stride, const int *pad,
+                      const int8_t *x, const int8_t *w, int32_t *y)
+{
+    const int O = oracle_out_dim(D, T, stride[0], pad[0]);
+    const int P = oracle_out_dim(H, R, stride[1], pad[1]);
+    const int Q = oracle_out_dim(W, S, stride[2], pad[2]);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k)
+            for (int o = 0; o < O; ++o)
+                for (int p = 0; p < P; ++p)
+                    for (int q = 0; q < Q; ++q) {
+                        int32_t acc = 0;
+                        for (int c = 0; c < C; ++c)
+                            for (int t = 0; t < T; ++t)
+                                for (int r = 0; r < R; ++r)
+                                    for (int s = 0; s < S; ++s) {
+                                        int d  = o * stride[0] + t - pad[0];
+                                        int h  = p * stride[1] + r - pad[1];
+                                        int ww = q * stride[2] + s - pad[2];
+                                        if (d < 0 || d >= D || h < 0 || h >= H || ww < 0 || ww >= W) continue;
+                                        int32_t a = (int32_t)x[((((size_t)n * C + c) * D + d) * H + h) * W + ww];
+                                        int32_t b = (int32_t)w[((((size_t)k * C + c) * T + t) * R + r) * S + s];
+                                        acc += a * b;
+                                    }
+                        y[((((size_t)n * K + k) * O + o) * P + p) * Q + q] = acc;
+                    }
+}
+
+/* fp16 inputs, fp32 accumulation in c -> t -> r -> s order; y64/yabs (optional) receive the
+ * fp64-accumulated value and the sum of |products|. */
+void oracle_conv3d_f16(int N, int C, int D, int H, int W, int K, int T, int R, int S,
+                       const int *stride, const int *pad,
+                       const uint16_t *x, const uint16_t *w, float *y, double *y64, double *yabs)
+{
+    const int O = oracle_out_dim(D, T, stride[0], pad[0]);
+    const int P = oracle_out_dim(H, R, stride[1], pad[1]);
+    const int Q = oracle_out_dim(W, S, stride[2], pad[2]);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k)
+            for (int o = 0; o < O; ++o)
+                for (int p = 0; p < P; ++p)
+                    for (int q = 0; q < Q; ++q) {
+                        float acc = 0.0f;
+                        double acc64 = 0.0, aabs = 0.0;
+                        for (int c = 0; c < C; ++c)
+                            for (int t = 0; t < T; ++t)
+                                for (int r = 0; r < R; ++r)
+                                    for (int s = 0; s < S; ++s) {
+                                        int d  = o * stride[0] + t - pad[0];
+                                        int h  = p * stride[1] + r - pad[1];
+                                        int ww = q * stride[2] + s - pad[2];
+                                        if (d < 0 || d >= D || h < 0 || h >= H || ww < 0 || ww >= W) continue;
+                                        float a = oracle_half_to_float(x[((((size_t)n * C + c) * D + d) * H + h) * W + ww]);
+                                        float b = oracle_half_to_float(w[((((size_t)k * C + c) * T + t) * R + r) * S + s]);
+                                        float prod = a * b;
+                                        acc = acc + prod;
+                                        acc64 += (double)a * (double)b;
+                                        aabs += fabs((double)a * (double)b);
+                                    }
+                        size_t idx = ((((size_t)n * K + k) * O + o) * P + p) * Q + q;
+                        y[idx] = acc;
+                        if (y64) y64[idx] = acc64;
+                        if (yabs) yabs[idx] = aabs;
+                    }
 }
 
 /* ------------------------------------------------------------------ matmul */
