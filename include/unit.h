@@ -183,6 +183,24 @@ int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const voi
 int unit_conv2d_wpacked_f16(const unit_conv2d_desc *d, const uint16_t *x, const void *w_packed,
                             float *y, void *ws, size_t ws_bytes, void *stream);
 
+/* ------------------------------------------------------------------ conv3d
+ * The paper's extensibility experiment (Section VI-C, "3D Convolution"): the same path with one
+ * more spatial axis.  x: [n,c,d,h,w] (NCDHW), w: [k,c,t,r,s], y: [n,k,o,p,q];
+ * o = floor((d + 2*pad_d - t)/stride_d) + 1, p and q likewise; zero padding, dilation 1.
+ * Raw int32 / fp32 outputs only.  Errors as for the 2-D calls.                                  */
+typedef struct unit_conv3d_desc {
+    int32_t n, c, d, h, w;
+    int32_t k, t, r, s;
+    int32_t stride_d, stride_h, stride_w, pad_d, pad_h, pad_w;
+} unit_conv3d_desc;
+
+int    unit_conv3d_out_dims(const unit_conv3d_desc *d, int32_t *o, int32_t *p, int32_t *q);
+size_t unit_conv3d_workspace(const unit_conv3d_desc *d, int dtype);
+int unit_conv3d_i8 (const unit_conv3d_desc *d, const int8_t *x, const int8_t *w, int32_t *y,
+                    void *ws, size_t ws_bytes, void *stream);
+int unit_conv3d_f16(const unit_conv3d_desc *d, const uint16_t *x, const uint16_t *w, float *y,
+                    void *ws, size_t ws_bytes, void *stream);
+
 /* ------------------------------------------------------------------ int8 network glue
  * Operators the chained int8 inference needs around the convolutions.  They work on the
  * packed int8 layout [n][h][w][cp].                                                        */

@@ -39,7 +39,8 @@ struct IgemmArgs {
     int kchunks;                                    // reduction length in 16-byte chunks
     int ksteps_per_split;                           // main-loop steps per grid.z slice
     // conv gather of B (CONV kernels only): packed activations [n][H][W][CB*16 bytes]
-    int H, W, CB, P, Q, PQ, R, S, sh, sw, ph, pw;
+    // (D, T, sd, pd describe the depth axis; conv2d is D = T = 1)
+    int D, H, W, CB, P, Q, PQ, T, R, S, sd, sh, sw, pd, ph, pw;
     int Cin;                                        // NCHW-direct kernels: real channel count
     // output: element (row, col) of image n = col / cols_per_img lives at
     //   out[n*img_stride + row*row_stride + col % cols_per_img]   (4-byte elements)
@@ -229,7 +230,7 @@ igemm_kernel(const IgemmArgs g)
         ? make_rsrc(g.B, (unsigned)g.b_bytes)
         : make_rsrc(g.B + (long)col0 * g.ldb, (unsigned)((long)(cols_here - 1) * g.ldb + (long)g.kchunks * 16));
     unsigned offB[IB];
-    int bh0[IB], bw0[IB];
+    int bd0[IB], bh0[IB], bw0[IB];
 #pragma unroll
     for (int j = 0; j < IB; ++j) {
         int r = (j * NW + wave) * RPI + lr_blk;
@@ -239,28 +240,32 @@ igemm_kernel(const IgemmArgs g)
             const int crow = (j * NW + wave) * CRPI + lane / CPR;
             offB[j] = (unsigned)((crow * g.PQ + col0 + (lane % CPR) * EPC) * ES);
             bh0[j] = crow;                          // channel row of this lane inside a step
-            bw0[j] = 0;
+            bd0[j] = bw0[j] = 0;
         } else if (BSRC == BSRC_GATHER) {
             int cc = valid ? col0 + r : 0;
-            int n = cc / g.PQ, pq = cc - n * g.PQ;
+            int n = cc / g.PQ, opq = cc - n * g.PQ;
+            int o = opq / (g.P * g.Q), pq = opq - o * (g.P * g.Q);
             int p = pq / g.Q, q = pq - p * g.Q;
             // an invalid column gets a row far outside the image: its bounds test always fails
-            const int bh = p * g.sh - g.ph, bw = q * g.sw - g.pw;
+            const int bd = o * g.sd - g.pd, bh = p * g.sh - g.ph, bw = q * g.sw - g.pw;
+            bd0[j] = bd;
             bh0[j] = valid ? bh : -0x100000;
             bw0[j] = bw;
-            // byte offset of tap (0,0); modulo 2^32 (negative in the padding), exact once a tap is in range
-            offB[j] = (unsigned)((n * g.H + bh) * g.W + bw) * (unsigned)(g.CB * 16);
+            // byte offset of tap (0,0,0); modulo 2^32 (negative in the padding), exact once a tap is in range
+            offB[j] = (unsigned)(((n * g.D + bd) * g.H + bh) * g.W + bw) * (unsigned)(g.CB * 16);
         } else {
             offB[j] = valid ? (unsigned)(r * (int)g.ldb + cT * 16) : UNIT_OOB;
-            bh0[j] = bw0[j] = 0;
+            bd0[j] = bh0[j] = bw0[j] = 0;
         }
     }
     // conv: reduction chunk kc -> (r, s, channel chunk cb), advanced incrementally per step
     int kc = ks_begin * NCH + cT;
-    int cr = 0, cs = 0, ccb = 0;
+    int ct = 0, cr = 0, cs = 0, ccb = 0;
     if (BSRC == BSRC_GATHER) {
-        int rs = kc / g.CB;
-        ccb = kc - rs * g.CB;
+        int trs = kc / g.CB;
+        ccb = kc - trs * g.CB;
+        ct = trs / (g.R * g.S);
+        int rs = trs - ct * (g.R * g.S);
         cr = rs / g.S;
         cs = rs - cr * g.S;
     }
@@ -285,17 +290,20 @@ igemm_kernel(const IgemmArgs g)
                 dma16(rsB, dst + j * NW * 1024, ok ? offB[j] + (unsigned)(chan0 * g.PQ * ES) : UNIT_OOB);
             }
         } else if (BSRC == BSRC_GATHER) {
-            const unsigned tap = (unsigned)((cr * g.W + cs) * g.CB + ccb) * 16u;
+            const unsigned tap = (unsigned)(((ct * g.H + cr) * g.W + cs) * g.CB + ccb) * 16u;
 #pragma unroll
             for (int j = 0; j < IB; ++j) {
-                int h = bh0[j] + cr, w = bw0[j] + cs;
-                bool ok = kok && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                int dd = bd0[j] + ct, h = bh0[j] + cr, w = bw0[j] + cs;
+                bool ok = kok && (unsigned)dd < (unsigned)g.D && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
                 dma16(rsB, dst + j * NW * 1024, ok ? offB[j] + tap : UNIT_OOB);
             }
             ccb += NCH;
             while (ccb >= g.CB) {
                 ccb -= g.CB;
-                if (++cs == g.S) { cs = 0; ++cr; }
+                if (++cs == g.S) {
+                    cs = 0;
+                    if (++cr == g.R) { cr = 0; ++ct; }
+                }
             }
         } else {
 #pragma unroll

@@ -23,6 +23,27 @@ namespace {
 
 thread_local char g_hip_err[256] = "";
 
+// Internal problem description: conv2d is the depth-1 case of conv3d (the only thing that
+// changes between them is the address generator of the gather).
+struct ConvND {
+    int n, c, d, h, w;
+    int k, t, r, s;
+    int stride_d, stride_h, stride_w, pad_d, pad_h, pad_w;
+    ConvND() : n(0), c(0), d(0), h(0), w(0), k(0), t(0), r(0), s(0),
+               stride_d(0), stride_h(0), stride_w(0), pad_d(0), pad_h(0), pad_w(0) {}
+    explicit ConvND(const unit_conv2d_desc *p) : ConvND() {
+        if (!p) return;
+        n = p->n; c = p->c; d = 1; h = p->h; w = p->w; k = p->k; t = 1; r = p->r; s = p->s;
+        stride_d = 1; stride_h = p->stride_h; stride_w = p->stride_w; pad_d = 0; pad_h = p->pad_h; pad_w = p->pad_w;
+    }
+    explicit ConvND(const unit_conv3d_desc *p) : ConvND() {
+        if (!p) return;
+        n = p->n; c = p->c; d = p->d; h = p->h; w = p->w; k = p->k; t = p->t; r = p->r; s = p->s;
+        stride_d = p->stride_d; stride_h = p->stride_h; stride_w = p->stride_w;
+        pad_d = p->pad_d; pad_h = p->pad_h; pad_w = p->pad_w;
+    }
+};
+
 int hip_fail(hipError_t e)
 {
     std::snprintf(g_hip_err, sizeof g_hip_err, "%s", hipGetErrorString(e));
@@ -37,39 +58,45 @@ inline int pad_channels(int c, int dtype) { int ch = chunk_elems(dtype); return 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 inline bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255) == 0; }
 
-bool desc_ok(const unit_conv2d_desc *d)
+bool desc_ok(const ConvND *d)
 {
     if (!d) return false;
-    if (d->n <= 0 || d->c <= 0 || d->h <= 0 || d->w <= 0 || d->k <= 0 || d->r <= 0 || d->s <= 0) return false;
-    if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return false;
-    if (d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s) return false;
+    if (d->n <= 0 || d->c <= 0 || d->d <= 0 || d->h <= 0 || d->w <= 0) return false;
+    if (d->k <= 0 || d->t <= 0 || d->r <= 0 || d->s <= 0) return false;
+    if (d->stride_d <= 0 || d->stride_h <= 0 || d->stride_w <= 0) return false;
+    if (d->pad_d < 0 || d->pad_h < 0 || d->pad_w < 0) return false;
+    if (d->d + 2 * d->pad_d < d->t || d->h + 2 * d->pad_h < d->r || d->w + 2 * d->pad_w < d->s) return false;
     return true;
 }
 
+size_t packed_act_bytes_nd(const struct ConvND *d, int dtype);
+size_t packed_weights_bytes_nd(const struct ConvND *d, int dtype);
+
 struct ConvGeom {
-    int p, q, cp, kchunks, rows;
+    int o, p, q, cp, kchunks, rows;
     long cols;
     long out_elems;
 };
 
-int conv_geom(const unit_conv2d_desc *d, int dtype, ConvGeom *g)
+int conv_geom(const ConvND *d, int dtype, ConvGeom *g)
 {
     if (dtype != UNIT_I8 && dtype != UNIT_F16) return UNIT_EINVAL;
     if (!desc_ok(d)) return UNIT_EINVAL;
+    g->o = (d->d + 2 * d->pad_d - d->t) / d->stride_d + 1;
     g->p = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
     g->q = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
     g->cp = pad_channels(d->c, dtype);
-    long red = (long)d->c * d->r * d->s;
+    long red = (long)d->c * d->t * d->r * d->s;
     if (dtype == UNIT_I8 && red > UNIT_MAX_REDUCTION_I8) return UNIT_EOVERFLOW;
-    long kbytes = (long)d->r * d->s * g->cp * elem_size(dtype);
+    long kbytes = (long)d->t * d->r * d->s * g->cp * elem_size(dtype);
     g->kchunks = (int)(kbytes / 16);
     g->rows = d->k;
-    g->cols = (long)d->n * g->p * g->q;
+    g->cols = (long)d->n * g->o * g->p * g->q;
     g->out_elems = g->cols * d->k;
     // index arithmetic in the kernels is 32-bit for rows/cols/chunks
     if (g->cols > 0x7fffffffL || kbytes > 0x7fffffffL || g->out_elems > (1L << 40)) return UNIT_ENOTSUP;
     // buffer descriptors address at most 2 GiB per tensor
-    if ((long)d->n * d->h * d->w * g->cp * elem_size(dtype) >= 0x7fffffffL) return UNIT_ENOTSUP;
+    if ((long)d->n * d->d * d->h * d->w * g->cp * elem_size(dtype) >= 0x7fffffffL) return UNIT_ENOTSUP;
     if (g->out_elems * 4 >= 0x7fffffffL || kbytes * 256 >= 0x7fffffffL) return UNIT_ENOTSUP;
     return UNIT_OK;
 }
@@ -120,15 +147,16 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
 // A 1x1, stride-1, unpadded conv of one image can read its NCHW input directly: the
 // channel rows are DMAed as they are and transposed between LDS and the fragments, which
 // saves the separate pack_act launch.  Needs 4-byte aligned channel rows.
-bool nchw_direct_ok(const unit_conv2d_desc *d, int dtype, const void *x, const unit_requant *rq)
+bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requant *rq)
 {
-    return d->n == 1 && d->r == 1 && d->s == 1 && d->stride_h == 1 && d->stride_w == 1 &&
-           d->pad_h == 0 && d->pad_w == 0 && rq == nullptr &&
-           ((long)d->h * d->w * elem_size(dtype)) % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+    return d->n == 1 && d->t == 1 && d->r == 1 && d->s == 1 &&
+           d->stride_d == 1 && d->stride_h == 1 && d->stride_w == 1 &&
+           d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr &&
+           ((long)d->d * d->h * d->w * elem_size(dtype)) % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
 }
 
 // `xp` is the packed activation tensor, or (nchw_direct) the caller's NCHW tensor itself.
-int conv_packed(const unit_conv2d_desc *d, int dtype, const void *xp, const void *wp,
+int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
                 void *y_raw, const unit_requant *rq, int8_t *y_i8, void *y_packed,
                 void *ws, size_t ws_bytes, void *stream, bool nchw_direct = false)
 {
@@ -150,10 +178,12 @@ int conv_packed(const unit_conv2d_desc *d, int dtype, const void *xp, const void
     a.A = static_cast<const uint8_t *>(wp);  a.lda = (long)g.kchunks * 16;  a.rows = d->k;
     a.B = static_cast<const uint8_t *>(xp);  a.ldb = 0;                      a.cols = (int)g.cols;
     a.kchunks = g.kchunks;
-    a.H = d->h;  a.W = d->w;  a.CB = g.cp * es / 16;  a.P = g.p;  a.Q = g.q;  a.PQ = g.p * g.q;
-    a.b_bytes = nchw_direct ? (long)d->c * d->h * d->w * es : (long)d->n * d->h * d->w * g.cp * es;
+    a.D = d->d;  a.H = d->h;  a.W = d->w;  a.CB = g.cp * es / 16;
+    a.P = g.p;  a.Q = g.q;  a.PQ = g.o * g.p * g.q;
+    a.b_bytes = nchw_direct ? (long)d->c * d->d * d->h * d->w * es : (long)d->n * d->d * d->h * d->w * g.cp * es;
     a.Cin = d->c;
-    a.R = d->r;  a.S = d->s;  a.sh = d->stride_h;  a.sw = d->stride_w;  a.ph = d->pad_h;  a.pw = d->pad_w;
+    a.T = d->t;  a.R = d->r;  a.S = d->s;
+    a.sd = d->stride_d;  a.sh = d->stride_h;  a.sw = d->stride_w;  a.pd = d->pad_d;  a.ph = d->pad_h;  a.pw = d->pad_w;
     a.out = y_raw;  a.row_stride = a.PQ;  a.img_stride = (long)d->k * a.PQ;  a.cols_per_img = a.PQ;
     if (rq) {
         a.epi = EPI_REQUANT;  a.scale = rq->scale;  a.bias = rq->bias;  a.residual = rq->residual;
@@ -168,26 +198,35 @@ int conv_packed(const unit_conv2d_desc *d, int dtype, const void *xp, const void
                      static_cast<hipStream_t>(stream));
 }
 
+size_t packed_act_bytes_nd(const ConvND *d, int dtype)
+{
+    return align256((size_t)d->n * d->d * d->h * d->w * pad_channels(d->c, dtype) * elem_size(dtype));
+}
+size_t packed_weights_bytes_nd(const ConvND *d, int dtype)
+{
+    return align256((size_t)d->k * d->t * d->r * d->s * pad_channels(d->c, dtype) * elem_size(dtype));
+}
+
 size_t conv_split_bytes(const ConvGeom &g, int dtype)
 {
     TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true);
     return ch.split_k > 1 ? align256((size_t)ch.split_k * ((g.out_elems + 3) & ~3L) * 4) : 0;
 }
 
-int conv_wpacked(const unit_conv2d_desc *d, int dtype, const void *x, const void *wp,
+int conv_wpacked(const ConvND *d, int dtype, const void *x, const void *wp,
                  void *y_raw, const unit_requant *rq, int8_t *y_i8,
                  void *ws, size_t ws_bytes, void *stream);
-bool nchw_direct_ok(const unit_conv2d_desc *d, int dtype, const void *x, const unit_requant *rq);
+bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requant *rq);
 
 // workspace conv_wpacked needs for this call (after the packed weights, if any)
-size_t wpacked_need(const unit_conv2d_desc *d, int dtype, const ConvGeom &g, const void *x, const unit_requant *rq)
+size_t wpacked_need(const ConvND *d, int dtype, const ConvGeom &g, const void *x, const unit_requant *rq)
 {
     size_t split_b = conv_split_bytes(g, dtype);
     return nchw_direct_ok(d, dtype, x, rq) ? split_b
-                                           : unit_packed_act_bytes(d->n, d->c, d->h, d->w, dtype) + split_b;
+                                           : packed_act_bytes_nd(d, dtype) + split_b;
 }
 
-int conv_plain(const unit_conv2d_desc *d, int dtype, const void *x, const void *w,
+int conv_plain(const ConvND *d, int dtype, const void *x, const void *w,
                void *y_raw, const unit_requant *rq, int8_t *y_i8,
                void *ws, size_t ws_bytes, void *stream)
 {
@@ -200,17 +239,17 @@ int conv_plain(const unit_conv2d_desc *d, int dtype, const void *x, const void *
     } else if (!y_raw || y_i8) {
         return UNIT_EINVAL;
     }
-    size_t wt_b = unit_packed_weights_bytes(d, dtype);
+    size_t wt_b = packed_weights_bytes_nd(d, dtype);
     if (!ws || ws_bytes < wt_b + wpacked_need(d, dtype, g, x, rq)) return UNIT_EWORKSPACE;
     if (!aligned256(ws)) return UNIT_EINVAL;
     uint8_t *wp = static_cast<uint8_t *>(ws);
-    UNIT_HIP(launch_pack_weights(dtype, d->k, d->c, d->r, d->s, w, wp, static_cast<hipStream_t>(stream)));
+    UNIT_HIP(launch_pack_weights(dtype, d->k, d->c, d->t * d->r, d->s, w, wp, static_cast<hipStream_t>(stream)));
     return conv_wpacked(d, dtype, x, wp, y_raw, rq, y_i8, wp + wt_b, ws_bytes - wt_b, stream);
 }
 
 // NCHW activations + packed weights: fused direct read when possible, else pack_act into the
 // workspace followed by the packed kernel.
-int conv_wpacked(const unit_conv2d_desc *d, int dtype, const void *x, const void *wp,
+int conv_wpacked(const ConvND *d, int dtype, const void *x, const void *wp,
                  void *y_raw, const unit_requant *rq, int8_t *y_i8,
                  void *ws, size_t ws_bytes, void *stream)
 {
@@ -225,10 +264,10 @@ int conv_wpacked(const unit_conv2d_desc *d, int dtype, const void *x, const void
         if (split_b && (!ws || ws_bytes < split_b)) return UNIT_EWORKSPACE;
         return conv_packed(d, dtype, x, wp, y_raw, rq, y_i8, nullptr, ws, ws_bytes, stream, true);
     }
-    size_t act_b = unit_packed_act_bytes(d->n, d->c, d->h, d->w, dtype);
+    size_t act_b = packed_act_bytes_nd(d, dtype);
     if (!ws || ws_bytes < act_b + split_b) return UNIT_EWORKSPACE;
     uint8_t *xp = static_cast<uint8_t *>(ws);
-    UNIT_HIP(launch_pack_act(dtype, d->n, d->c, d->h, d->w, x, xp, static_cast<hipStream_t>(stream)));
+    UNIT_HIP(launch_pack_act(dtype, d->n, d->c, d->d * d->h, d->w, x, xp, static_cast<hipStream_t>(stream)));
     return conv_packed(d, dtype, xp, wp, y_raw, rq, y_i8, nullptr, split_b ? xp + act_b : nullptr, split_b, stream);
 }
 
@@ -320,7 +359,8 @@ const char *unit_last_hip_error(void) { return g_hip_err; }
 
 int unit_conv2d_out_dims(const unit_conv2d_desc *d, int32_t *p, int32_t *q)
 {
-    if (!desc_ok(d) || !p || !q) return UNIT_EINVAL;
+    ConvND nd(d);
+    if (!desc_ok(&nd) || !p || !q) return UNIT_EINVAL;
     *p = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
     *q = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
     return UNIT_OK;
@@ -334,23 +374,25 @@ size_t unit_packed_act_bytes(int32_t n, int32_t c, int32_t h, int32_t w, int dty
 
 size_t unit_packed_weights_bytes(const unit_conv2d_desc *d, int dtype)
 {
-    if (!desc_ok(d) || (dtype != UNIT_I8 && dtype != UNIT_F16)) return 0;
-    return align256((size_t)d->k * d->r * d->s * pad_channels(d->c, dtype) * elem_size(dtype));
+    ConvND nd(d);
+    if (!desc_ok(&nd) || (dtype != UNIT_I8 && dtype != UNIT_F16)) return 0;
+    return packed_weights_bytes_nd(&nd, dtype);
 }
 
 size_t unit_conv2d_packed_workspace(const unit_conv2d_desc *d, int dtype)
 {
     ConvGeom g;
-    if (conv_geom(d, dtype, &g) != UNIT_OK) return 0;
+    ConvND nd(d);
+    if (conv_geom(&nd, dtype, &g) != UNIT_OK) return 0;
     return conv_split_bytes(g, dtype);
 }
 
 size_t unit_conv2d_workspace(const unit_conv2d_desc *d, int dtype)
 {
     ConvGeom g;
-    if (conv_geom(d, dtype, &g) != UNIT_OK) return 0;
-    return unit_packed_act_bytes(d->n, d->c, d->h, d->w, dtype) + unit_packed_weights_bytes(d, dtype) +
-           conv_split_bytes(g, dtype);
+    ConvND nd(d);
+    if (conv_geom(&nd, dtype, &g) != UNIT_OK) return 0;
+    return packed_act_bytes_nd(&nd, dtype) + packed_weights_bytes_nd(&nd, dtype) + conv_split_bytes(g, dtype);
 }
 
 size_t unit_matmul_workspace(int32_t m, int32_t n, int32_t k, int64_t lda, int64_t ldb, int dtype)
@@ -363,7 +405,8 @@ size_t unit_matmul_workspace(int32_t m, int32_t n, int32_t k, int64_t lda, int64
 int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out)
 {
     ConvGeom g;
-    int rc = conv_geom(d, dtype, &g);
+    ConvND nd(d);
+    int rc = conv_geom(&nd, dtype, &g);
     if (rc != UNIT_OK) return rc;
     if (!out) return UNIT_EINVAL;
     fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true), out);
@@ -384,13 +427,15 @@ int unit_conv2d_i8(const unit_conv2d_desc *d, const int8_t *x, const int8_t *w,
                    int32_t *y_i32, const unit_requant *rq, int8_t *y_i8,
                    void *ws, size_t ws_bytes, void *stream)
 {
-    return conv_plain(d, UNIT_I8, x, w, y_i32, rq, y_i8, ws, ws_bytes, stream);
+    ConvND nd(d);
+    return conv_plain(&nd, UNIT_I8, x, w, y_i32, rq, y_i8, ws, ws_bytes, stream);
 }
 
 int unit_conv2d_f16(const unit_conv2d_desc *d, const uint16_t *x, const uint16_t *w,
                     float *y, void *ws, size_t ws_bytes, void *stream)
 {
-    return conv_plain(d, UNIT_F16, x, w, y, nullptr, nullptr, ws, ws_bytes, stream);
+    ConvND nd(d);
+    return conv_plain(&nd, UNIT_F16, x, w, y, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 int unit_matmul_i8(int32_t m, int32_t n, int32_t k, const int8_t *A, int64_t lda,
@@ -461,14 +506,16 @@ int unit_conv2d_packed_i8(const unit_conv2d_desc *d, const void *xp, const void 
                           int32_t *y_i32, const unit_requant *rq, int8_t *y_i8, void *y_packed,
                           void *ws, size_t ws_bytes, void *stream)
 {
-    return conv_packed(d, UNIT_I8, xp, wp, y_i32, rq, y_i8, y_packed, ws, ws_bytes, stream);
+    ConvND nd(d);
+    return conv_packed(&nd, UNIT_I8, xp, wp, y_i32, rq, y_i8, y_packed, ws, ws_bytes, stream);
 }
 
 size_t unit_conv2d_wpacked_workspace(const unit_conv2d_desc *d, int dtype)
 {
     ConvGeom g;
-    if (conv_geom(d, dtype, &g) != UNIT_OK) return 0;
-    return unit_packed_act_bytes(d->n, d->c, d->h, d->w, dtype) + conv_split_bytes(g, dtype);
+    ConvND nd(d);
+    if (conv_geom(&nd, dtype, &g) != UNIT_OK) return 0;
+    return packed_act_bytes_nd(&nd, dtype) + conv_split_bytes(g, dtype);
 }
 
 int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const void *wp,
@@ -476,20 +523,23 @@ int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const voi
                            void *ws, size_t ws_bytes, void *stream)
 {
     if (rq ? (!rq->scale || !y_i8) : (!y_i32 || y_i8)) return UNIT_EINVAL;
-    return conv_wpacked(d, UNIT_I8, x, wp, y_i32, rq, y_i8, ws, ws_bytes, stream);
+    ConvND nd(d);
+    return conv_wpacked(&nd, UNIT_I8, x, wp, y_i32, rq, y_i8, ws, ws_bytes, stream);
 }
 
 int unit_conv2d_wpacked_f16(const unit_conv2d_desc *d, const uint16_t *x, const void *wp,
                             float *y, void *ws, size_t ws_bytes, void *stream)
 {
     if (!y) return UNIT_EINVAL;
-    return conv_wpacked(d, UNIT_F16, x, wp, y, nullptr, nullptr, ws, ws_bytes, stream);
+    ConvND nd(d);
+    return conv_wpacked(&nd, UNIT_F16, x, wp, y, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 int unit_conv2d_packed_f16(const unit_conv2d_desc *d, const void *xp, const void *wp,
                            float *y, void *ws, size_t ws_bytes, void *stream)
 {
-    return conv_packed(d, UNIT_F16, xp, wp, y, nullptr, nullptr, nullptr, ws, ws_bytes, stream);
+    ConvND nd(d);
+    return conv_packed(&nd, UNIT_F16, xp, wp, y, nullptr, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 int unit_maxpool_packed_i8(int32_t n, int32_t c, int32_t h, int32_t w,
@@ -523,6 +573,38 @@ int unit_widen_residual_i8(int32_t n, int32_t c, int32_t h, int32_t w,
     UNIT_HIP(launch_widen_residual_i8(n, c, pad_channels(c, UNIT_I8), h * w, xp, mult, residual,
                                       static_cast<hipStream_t>(stream)));
     return UNIT_OK;
+}
+
+int unit_conv3d_out_dims(const unit_conv3d_desc *d, int32_t *o, int32_t *p, int32_t *q)
+{
+    ConvND nd(d);
+    if (!desc_ok(&nd) || !o || !p || !q) return UNIT_EINVAL;
+    *o = (nd.d + 2 * nd.pad_d - nd.t) / nd.stride_d + 1;
+    *p = (nd.h + 2 * nd.pad_h - nd.r) / nd.stride_h + 1;
+    *q = (nd.w + 2 * nd.pad_w - nd.s) / nd.stride_w + 1;
+    return UNIT_OK;
+}
+
+size_t unit_conv3d_workspace(const unit_conv3d_desc *d, int dtype)
+{
+    ConvGeom g;
+    ConvND nd(d);
+    if (conv_geom(&nd, dtype, &g) != UNIT_OK) return 0;
+    return packed_act_bytes_nd(&nd, dtype) + packed_weights_bytes_nd(&nd, dtype) + conv_split_bytes(g, dtype);
+}
+
+int unit_conv3d_i8(const unit_conv3d_desc *d, const int8_t *x, const int8_t *w, int32_t *y,
+                   void *ws, size_t ws_bytes, void *stream)
+{
+    ConvND nd(d);
+    return conv_plain(&nd, UNIT_I8, x, w, y, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+int unit_conv3d_f16(const unit_conv3d_desc *d, const uint16_t *x, const uint16_t *w, float *y,
+                    void *ws, size_t ws_bytes, void *stream)
+{
+    ConvND nd(d);
+    return conv_plain(&nd, UNIT_F16, x, w, y, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

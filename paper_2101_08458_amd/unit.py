@@ -22,6 +22,12 @@ class unit_conv2d_desc(ctypes.Structure):
                 ("n", "c", "h", "w", "k", "r", "s", "stride_h", "stride_w", "pad_h", "pad_w")]
 
 
+class unit_conv3d_desc(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_int32) for f in
+                ("n", "c", "d", "h", "w", "k", "t", "r", "s",
+                 "stride_d", "stride_h", "stride_w", "pad_d", "pad_h", "pad_w")]
+
+
 class unit_requant(ctypes.Structure):
     _fields_ = [("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p),
                 ("residual", ctypes.c_void_p), ("relu", ctypes.c_int32)]
@@ -53,6 +59,7 @@ EXPORTS = [
     "unit_unpack_act_i8", "unit_conv2d_packed_i8", "unit_conv2d_packed_f16",
     "unit_maxpool_packed_i8", "unit_global_avgpool_packed_i8", "unit_widen_residual_i8",
     "unit_conv2d_wpacked_workspace", "unit_conv2d_wpacked_i8", "unit_conv2d_wpacked_f16",
+    "unit_conv3d_out_dims", "unit_conv3d_workspace", "unit_conv3d_i8", "unit_conv3d_f16",
 ]
 
 
@@ -67,6 +74,7 @@ def load():
     L = ctypes.CDLL(LIB_PATH)
     i32, i64, sz, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t, ctypes.c_void_p
     dp = ctypes.POINTER(unit_conv2d_desc)
+    d3 = ctypes.POINTER(unit_conv3d_desc)
     rp = ctypes.POINTER(unit_requant)
     tp = ctypes.POINTER(unit_tile_info)
     ip = ctypes.POINTER(ctypes.c_int32)
@@ -96,6 +104,10 @@ def load():
         "unit_conv2d_wpacked_workspace": (sz, [dp, ctypes.c_int]),
         "unit_conv2d_wpacked_i8": (ctypes.c_int, [dp, vp, vp, vp, rp, vp, vp, sz, vp]),
         "unit_conv2d_wpacked_f16": (ctypes.c_int, [dp, vp, vp, vp, vp, sz, vp]),
+        "unit_conv3d_out_dims": (ctypes.c_int, [d3, ip, ip, ip]),
+        "unit_conv3d_workspace": (sz, [d3, ctypes.c_int]),
+        "unit_conv3d_i8": (ctypes.c_int, [d3, vp, vp, vp, vp, sz, vp]),
+        "unit_conv3d_f16": (ctypes.c_int, [d3, vp, vp, vp, vp, sz, vp]),
         "unit_maxpool_packed_i8": (ctypes.c_int, [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]),
         "unit_global_avgpool_packed_i8": (ctypes.c_int, [i32, i32, i32, i32, vp, vp, vp, vp]),
         "unit_widen_residual_i8": (ctypes.c_int, [i32, i32, i32, i32, vp, i32, vp, vp]),
@@ -274,6 +286,31 @@ def unit_conv2d_wpacked_f16(d, x, wp, y, ws=None, stream=None):
     wsp, wsb = _ws(ws)
     _check(load().unit_conv2d_wpacked_f16(ctypes.byref(d), _p(x), _p(wp), _p(y), wsp, wsb, _stream(stream)),
            "unit_conv2d_wpacked_f16")
+
+
+def conv3d_desc(n, c, d, h, w, k, t, r, s, stride=(1, 1, 1), pad=(0, 0, 0)):
+    return unit_conv3d_desc(n, c, d, h, w, k, t, r, s, *stride, *pad)
+
+
+def unit_conv3d_out_dims(d):
+    o, p, q = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(load().unit_conv3d_out_dims(ctypes.byref(d), ctypes.byref(o), ctypes.byref(p), ctypes.byref(q)),
+           "unit_conv3d_out_dims")
+    return o.value, p.value, q.value
+
+
+def unit_conv3d_workspace(d, dtype):
+    return load().unit_conv3d_workspace(ctypes.byref(d), dtype)
+
+
+def unit_conv3d_i8(d, x, w, y, ws, stream=None):
+    wsp, wsb = _ws(ws)
+    _check(load().unit_conv3d_i8(ctypes.byref(d), _p(x), _p(w), _p(y), wsp, wsb, _stream(stream)), "unit_conv3d_i8")
+
+
+def unit_conv3d_f16(d, x, w, y, ws, stream=None):
+    wsp, wsb = _ws(ws)
+    _check(load().unit_conv3d_f16(ctypes.byref(d), _p(x), _p(w), _p(y), wsp, wsb, _stream(stream)), "unit_conv3d_f16")
 
 
 def unit_maxpool_packed_i8(n, c, h, w, window, stride, pad, xp, yp, stream=None):
