@@ -38,7 +38,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet50_i8_b1",
                     choices=["resnet50_i8_b1", "gemm_i8_4096", "large_conv_i8", "gemm_f16_4096",
-                             "large_conv_f16", "resnet50_f16_b16", "table1_ablation"])
+                             "large_conv_f16", "resnet50_f16_b16", "table1_ablation", "conv3d_resnet18"])
     ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
@@ -190,6 +190,55 @@ def cpu_baseline(wl, budget_s=12.0):
                                         f"{macs / 1e9:.2f} GMAC in {secs:.2f} s, OpenMP direct loops"}
 
 
+def conv3d_resnet18(torch, unit, wl, out):
+    """The paper's conv3d experiment (Section VI-C): every 2-D convolution of a ResNet-18-shaped
+    network lifted to 3-D.  The paper does not give the depth; here every layer gets an input depth
+    of 8 and a cubic kernel (kernel depth = R, depth stride = stride, depth pad = pad).  Batch 1,
+    int8 -> int32 and fp16 -> fp32, NCDHW in -> NKOPQ out through unit_conv3d_* (packs both
+    operands inside the call)."""
+    from paper_2101_08458_amd.resnet18_int8 import layer_list
+    shapes = []
+    for _, sh in layer_list():
+        if sh not in shapes:
+            shapes.append(sh)
+    rows = []
+    for dtype in ("i8", "f16"):
+        i8 = dtype == "i8"
+        ut = unit.UNIT_I8 if i8 else unit.UNIT_F16
+        for idx, sh in enumerate(shapes):
+            depth = 8
+            g = wl.rng(7, idx)
+            shape_x, shape_w = (1, sh.c, depth, sh.h, sh.w), (sh.k, sh.c, sh.r, sh.r, sh.s)
+            if i8:
+                x, w = wl.int8_activations(g, shape_x), wl.int8_weights(g, shape_w)
+            else:
+                x = wl.f16_activations(g, shape_x).view(np.int16)
+                w = wl.f16_weights(g, shape_w, sh.c * sh.r ** 3).view(np.int16)
+            d = unit.conv3d_desc(1, sh.c, depth, sh.h, sh.w, sh.k, sh.r, sh.r, sh.s,
+                                 (sh.stride,) * 3, (sh.pad,) * 3)
+            o, p, q = unit.unit_conv3d_out_dims(d)
+            xd, wd = torch.from_numpy(x).to("cuda:0"), torch.from_numpy(w).to("cuda:0")
+            y = torch.empty((1, sh.k, o, p, q), dtype=torch.int32 if i8 else torch.float32, device="cuda:0")
+            ws = torch.empty(max(unit.unit_conv3d_workspace(d, ut), 256), dtype=torch.uint8, device="cuda:0")
+            f = (lambda: unit.unit_conv3d_i8(d, xd, wd, y, ws)) if i8 else (lambda: unit.unit_conv3d_f16(d, xd, wd, y, ws))
+            us = event_ms(torch, f, 10) * 1e3
+            macs = sh.k * o * p * q * sh.c * sh.r ** 2 * sh.s
+            rows.append({"dtype": dtype, "shape": [sh.c, depth, sh.h, sh.w, sh.k, sh.r, sh.stride, sh.pad],
+                         "out": [o, p, q], "us": round(us, 2), "gmac": round(macs / 1e9, 3),
+                         "value": round(2.0 * macs / us / 1e6, 2)})
+            del xd, wd, y, ws
+    tot = {dt: sum(r["us"] for r in rows if r["dtype"] == dt) for dt in ("i8", "f16")}
+    mac = {dt: sum(r["gmac"] for r in rows if r["dtype"] == dt) for dt in ("i8", "f16")}
+    out.update({"metric": "int8 conv3d TOPS", "unit": "TOPS", "dtype": "i8",
+                "value": round(2.0 * mac["i8"] * 1e9 / (tot["i8"] * 1e-6) / 1e12, 2),
+                "ms_per_step": round(tot["i8"] / 1e3, 4),
+                "fp16_tflops": round(2.0 * mac["f16"] * 1e9 / (tot["f16"] * 1e-6) / 1e12, 2),
+                "fp16_ms": round(tot["f16"] / 1e3, 4),
+                "config": {"workload": "unique conv layers of a ResNet-18-shaped network lifted to 3-D "
+                                       "(input depth 8, cubic kernels), batch 1, unit_conv3d_* calls"},
+                "layers": rows})
+
+
 def table1_ablation(torch, unit, wl, out):
     """The paper's per-kernel experiment (Table I layers; its GPU ablation Generic -> +SplitK
     -> +Tune, Section VI-B) on this hardware: batch 1, kernel only (packed operands).
@@ -300,6 +349,10 @@ def main():
         return ms, ms_eager, macs, t_conv, t_pack, byts, per_layer, t_api
 
     wlname = args.workload
+    if wlname == "conv3d_resnet18":
+        conv3d_resnet18(torch, unit, wl, out)
+        print(json.dumps(out))
+        return
     if wlname == "table1_ablation":
         table1_ablation(torch, unit, wl, out)
         print(json.dumps(out))
