@@ -172,9 +172,10 @@ int unit_conv2d_packed_f16(const unit_conv2d_desc *d, const void *x_packed, cons
 /*
  * conv2d on plain NCHW activations with pre-packed weights: the per-layer call of an
  * inference loop whose weights were packed once.  Activations are packed into the workspace
- * first, except for 1x1 / stride-1 / unpadded convs of a single image (n == 1, h*w*elem a
- * multiple of 4 bytes, 16-byte aligned x, no requantise), which read NCHW directly inside
- * the main kernel.  Outputs as in unit_conv2d_i8 / unit_conv2d_f16.
+ * first, except for 1x1 / stride-1 / unpadded convs without requantise whose channel rows
+ * can be streamed as they are (16-byte aligned x; n == 1 and h*w*elem a multiple of 4 bytes,
+ * or any n with h*w a multiple of the 16-byte chunk: 16 int8 / 8 fp16 pixels), which read
+ * NCHW directly inside the main kernel.  Outputs as in unit_conv2d_i8 / unit_conv2d_f16.
  */
 size_t unit_conv2d_wpacked_workspace(const unit_conv2d_desc *d, int dtype);
 int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const void *w_packed,

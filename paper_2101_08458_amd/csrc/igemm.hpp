@@ -238,7 +238,12 @@ igemm_kernel(const IgemmArgs g)
         if (BSRC == BSRC_NCHW) {
             // lane -> (channel row inside the DMA block, 16-byte chunk of pixels)
             const int crow = (j * NW + wave) * CRPI + lane / CPR;
-            offB[j] = (unsigned)((crow * g.PQ + col0 + (lane % CPR) * EPC) * ES);
+            // this lane's 16-byte chunk of pixels lies inside one image (the host only picks this
+            // mode when the pixels per image are a multiple of the chunk); columns past the end
+            // read whatever follows and are masked at the store
+            const int px = col0 + (lane % CPR) * EPC;
+            const int img = px / g.PQ;
+            offB[j] = (unsigned)(((img * g.Cin + crow) * g.PQ + (px - img * g.PQ)) * ES);
             bh0[j] = crow;                          // channel row of this lane inside a step
             bd0[j] = bw0[j] = 0;
         } else if (BSRC == BSRC_GATHER) {

@@ -144,15 +144,18 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
     return UNIT_OK;
 }
 
-// A 1x1, stride-1, unpadded conv of one image can read its NCHW input directly: the
+// A 1x1, stride-1, unpadded conv can read its NCHW input directly: the
 // channel rows are DMAed as they are and transposed between LDS and the fragments, which
 // saves the separate pack_act launch.  Needs 4-byte aligned channel rows.
 bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requant *rq)
 {
-    return d->n == 1 && d->t == 1 && d->r == 1 && d->s == 1 &&
+    const long px = (long)d->d * d->h * d->w;      // pixels per image
+    // one image: channel rows must be 4-byte aligned; several: every 16-byte chunk of pixels
+    // must stay inside one image
+    const bool rows_ok = (d->n == 1) ? (px * elem_size(dtype)) % 4 == 0 : px % chunk_elems(dtype) == 0;
+    return d->t == 1 && d->r == 1 && d->s == 1 &&
            d->stride_d == 1 && d->stride_h == 1 && d->stride_w == 1 &&
-           d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr &&
-           ((long)d->d * d->h * d->w * elem_size(dtype)) % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+           d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr && rows_ok && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
 }
 
 // `xp` is the packed activation tensor, or (nchw_direct) the caller's NCHW tensor itself.
@@ -180,7 +183,7 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
     a.kchunks = g.kchunks;
     a.D = d->d;  a.H = d->h;  a.W = d->w;  a.CB = g.cp * es / 16;
     a.P = g.p;  a.Q = g.q;  a.PQ = g.o * g.p * g.q;
-    a.b_bytes = nchw_direct ? (long)d->c * d->d * d->h * d->w * es : (long)d->n * d->d * d->h * d->w * g.cp * es;
+    a.b_bytes = nchw_direct ? (long)d->n * d->c * d->d * d->h * d->w * es : (long)d->n * d->d * d->h * d->w * g.cp * es;
     a.Cin = d->c;
     a.T = d->t;  a.R = d->r;  a.S = d->s;
     a.sd = d->stride_d;  a.sh = d->stride_h;  a.sw = d->stride_w;  a.pd = d->pad_d;  a.ph = d->pad_h;  a.pw = d->pad_w;

@@ -202,21 +202,25 @@ def test_conv_i8_small_all_tiles(sh, n):
                 assert same(run_conv_i8(sh, n, x, w), ref), (tile, split)
 
 
-NCHW_DIRECT = [   # 1x1 / stride 1 / one image: read straight from NCHW when h*w*elem % 4 == 0
-    wl.ConvShape(20, 14, 14, 33, 1, 1, 1, 0), wl.ConvShape(64, 56, 56, 64, 1, 1, 1, 0),
-    wl.ConvShape(70, 10, 10, 130, 1, 1, 1, 0), wl.ConvShape(256, 6, 6, 40, 1, 1, 1, 0),
-    wl.ConvShape(3, 18, 18, 5, 1, 1, 1, 0), wl.ConvShape(130, 7, 7, 64, 1, 1, 1, 0),   # 7x7: falls back to pack + gather
+NCHW_DIRECT = [   # 1x1 / stride 1: read straight from NCHW when the channel rows allow it
+    (wl.ConvShape(20, 14, 14, 33, 1, 1, 1, 0), 1), (wl.ConvShape(64, 56, 56, 64, 1, 1, 1, 0), 1),
+    (wl.ConvShape(70, 10, 10, 130, 1, 1, 1, 0), 1), (wl.ConvShape(256, 6, 6, 40, 1, 1, 1, 0), 1),
+    (wl.ConvShape(3, 18, 18, 5, 1, 1, 1, 0), 1),
+    (wl.ConvShape(130, 7, 7, 64, 1, 1, 1, 0), 1),      # 49 pixels: falls back to pack + gather
+    (wl.ConvShape(24, 8, 8, 40, 1, 1, 1, 0), 3),       # several images, 64 pixels each: direct
+    (wl.ConvShape(72, 12, 4, 96, 1, 1, 1, 0), 5),      # 48 pixels per image: direct, tiles straddle images
+    (wl.ConvShape(16, 14, 14, 24, 1, 1, 1, 0), 2),     # 196 pixels per image, n > 1: falls back
 ]
 
 
-@pytest.mark.parametrize("sh", NCHW_DIRECT)
-def test_conv_wpacked_nchw_direct(sh):
+@pytest.mark.parametrize("sh,n", NCHW_DIRECT)
+def test_conv_wpacked_nchw_direct(sh, n):
     """Pre-packed weights + NCHW activations, the per-layer call the benchmark times."""
     st, pd = (1, 1), (0, 0)
-    d = unit.conv_desc(1, sh.c, sh.h, sh.w, sh.k, 1, 1, 1, 0)
-    x, w = wl.conv_inputs_i8(sh, 1, 32, sh.c)
+    d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, 1, 1, 1, 0)
+    x, w = wl.conv_inputs_i8(sh, n, 32, sh.c)
     ref = oracle.conv2d_i8(x, w, st, pd)
-    xh, wh = wl.conv_inputs_f16(sh, 1, 33, sh.c)
+    xh, wh = wl.conv_inputs_f16(sh, n, 33, sh.c)
     refh = oracle.conv2d_f16(xh, wh, st, pd)
     truth, mag = oracle.conv2d_f16_f64(xh, wh, st, pd)
     xd, xhd = dev(x), dev(xh)
@@ -225,11 +229,11 @@ def test_conv_wpacked_nchw_direct(sh):
     unit.unit_pack_weights_i8(d, dev(w), wp)
     unit.unit_pack_weights_f16(d, dev(wh), wph)
     for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 2)]:
-        announce("wpacked", sh, "tile", tile, "split", split)
+        announce("wpacked", sh, n, "tile", tile, "split", split)
         with forced(tile=tile, split=split):
-            y = torch.full((1, sh.k, sh.h, sh.w), -7, dtype=torch.int32, device="cuda:0")
+            y = torch.full((n, sh.k, sh.h, sh.w), -7, dtype=torch.int32, device="cuda:0")
             unit.unit_conv2d_wpacked_i8(d, xd, wp, y, None, None, ws_bytes(unit.unit_conv2d_wpacked_workspace(d, unit.UNIT_I8)))
-            yh = torch.empty((1, sh.k, sh.h, sh.w), dtype=torch.float32, device="cuda:0")
+            yh = torch.empty((n, sh.k, sh.h, sh.w), dtype=torch.float32, device="cuda:0")
             unit.unit_conv2d_wpacked_f16(d, xhd, wph, yh, ws_bytes(unit.unit_conv2d_wpacked_workspace(d, unit.UNIT_F16)))
             torch.cuda.synchronize()
         assert same(host(y), ref, f"i8 tile {tile} split {split}")
