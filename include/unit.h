@@ -127,9 +127,11 @@ int unit_conv2d_f16(const unit_conv2d_desc *d, const uint16_t *x, const uint16_t
 /*
  * C[m,n] = sum_k A[m,k] * B[k,n].   A row-major (A[m,k] at A[m*lda+k]), B column-major
  * (B[k,n] at B[n*ldb+k]), C row-major (C[m*ldc+n]); leading dimensions in elements,
- * lda,ldb >= k, ldc >= n.  Operands whose base or leading dimension is not 16-byte
- * aligned, or whose k is not a multiple of 16 bytes, are first copied into the
- * workspace with zero padding (unit_matmul_workspace accounts for it).
+ * lda,ldb >= k, ldc >= n.  An operand whose leading dimension or k (in bytes) is not a
+ * multiple of 16 is first copied into the workspace with zero padding
+ * (unit_matmul_workspace accounts for it); an operand used in place must start on a
+ * 16-byte boundary (UNIT_EINVAL otherwise).  C must be 4-byte aligned.  A reduction split
+ * across workgroups is only used when ldc == n.
  * Errors: UNIT_EINVAL, UNIT_EOVERFLOW (int8, k > UNIT_MAX_REDUCTION_I8), UNIT_EWORKSPACE, UNIT_EHIP.
  */
 int unit_matmul_i8(int32_t m, int32_t n, int32_t k,
