@@ -221,6 +221,64 @@ int unit_global_avgpool_packed_i8(int32_t n, int32_t c, int32_t h, int32_t w,
 int unit_widen_residual_i8(int32_t n, int32_t c, int32_t h, int32_t w,
                            const void *x_packed, int32_t mult, int32_t *residual, void *stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Applicability inspection (Section III-B; Algorithm 1; candidate order of Section IV-A).
+ * Host-only: no device work, no stream.  Decides whether a tensorized instruction, written as
+ * a small tensor program, can execute a tile of a tensor operation, and which loops of the
+ * operation become the instruction's loops.
+ *
+ * Program text (NUL-terminated; statements separated by ';' or newlines):
+ *     loop NAME EXTENT dp|red        data-parallel / reduction loop, outermost first (<= 32)
+ *     out  NAME:DTYPE[INDEX,...]     element written
+ *     acc  NAME:DTYPE[INDEX,...]     instruction only: separate addend register (d = c + sum);
+ *                                    without it the instruction accumulates in place (+=)
+ *     body EXPR                      value reduced into the output
+ *     EXPR  := (OPCODE EXPR EXPR) | (cast DTYPE EXPR) | NAME:DTYPE[INDEX,...] | const:DTYPE:VALUE
+ *     INDEX := terms [COEF*]VAR or integers joined by + or -
+ *
+ * Step 1 (Algorithm 1): both expression trees are walked together; node types must agree
+ * (a binary node has its left child's type, a cast its destination type), leaves bind an
+ * instruction register element to one operation operand, arithmetic nodes need equal opcodes
+ * and matching children, left with left.  Step 2 (Section III-B.2): each instruction loop takes
+ * one operation loop of the same annotation such that, for every bound operand pair and for the
+ * outputs, the image of the operation's index variables lies inside the instruction's index
+ * variables; instruction loops missing from the image are broadcast directions.  Candidates are
+ * tried innermost (last declared) first, the instruction's first loop varying slowest, and the
+ * first feasible assignment is reported; num_feasible counts them all (the tuning dimension).
+ *
+ * Returns UNIT_OK with *res filled (applicable 0 or 1), UNIT_EINVAL for NULL arguments or text
+ * that does not parse, UNIT_ENOTSUP for an instruction with more than UNIT_INSPECT_MAX loops or
+ * register operands.
+ */
+#define UNIT_INSPECT_MAX  8
+#define UNIT_INSPECT_NAME 16
+typedef struct unit_inspect_result {
+    int32_t  applicable;     /* 1: both steps succeed                                          */
+    int32_t  failed_step;    /* 0 none, 1 expression trees differ, 2 no feasible loop mapping  */
+    int32_t  num_loops;      /* instruction loops, declaration order                           */
+    char     instr_loop[UNIT_INSPECT_MAX][UNIT_INSPECT_NAME];
+    char     op_loop[UNIT_INSPECT_MAX][UNIT_INSPECT_NAME];     /* operation loop tiled onto it  */
+    int32_t  num_operands;   /* instruction registers: output, addend, then body operands      */
+    char     instr_operand[UNIT_INSPECT_MAX][UNIT_INSPECT_NAME];
+    char     op_operand[UNIT_INSPECT_MAX][UNIT_INSPECT_NAME];  /* array bound to it or "const"  */
+    uint32_t broadcast[UNIT_INSPECT_MAX];  /* bit i: replicated along instr_loop[i]             */
+    int32_t  num_feasible;
+} unit_inspect_result;
+
+int unit_inspect(const char *instruction, const char *operation, unit_inspect_result *res);
+
+/* Program text of what this library executes, for unit_inspect.  Each writes at most `cap`
+ * bytes (NUL-terminated, truncated if short; buf may be NULL) and returns the bytes needed
+ * including the NUL, or UNIT_EINVAL.
+ *   unit_describe_mfma    one MFMA tile, edge 32 or 16 (Section III-A form: the instruction as
+ *                         a tensor program; accumulates in place like the paper's matrix unit)
+ *   unit_describe_conv2d  the conv on the layouts the main kernel reads
+ *                         (weights [k][r][s][c], activations [n][h][w][c])
+ *   unit_describe_matmul  C[m,n] += A[m,k] * B[k,n], B addressed column-major            */
+int unit_describe_mfma(int dtype, int32_t edge, char *buf, size_t cap);
+int unit_describe_conv2d(const unit_conv2d_desc *d, int dtype, char *buf, size_t cap);
+int unit_describe_matmul(int32_t m, int32_t n, int32_t k, int dtype, char *buf, size_t cap);
+
 #ifdef __cplusplus
 }
 #endif

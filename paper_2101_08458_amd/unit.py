@@ -39,6 +39,17 @@ class unit_tile_info(ctypes.Structure):
                  "mfma", "split_k", "workgroups")]
 
 
+UNIT_INSPECT_MAX, UNIT_INSPECT_NAME = 8, 16
+
+
+class unit_inspect_result(ctypes.Structure):
+    _names = (ctypes.c_char * UNIT_INSPECT_NAME) * UNIT_INSPECT_MAX
+    _fields_ = [("applicable", ctypes.c_int32), ("failed_step", ctypes.c_int32),
+                ("num_loops", ctypes.c_int32), ("instr_loop", _names), ("op_loop", _names),
+                ("num_operands", ctypes.c_int32), ("instr_operand", _names), ("op_operand", _names),
+                ("broadcast", ctypes.c_uint32 * UNIT_INSPECT_MAX), ("num_feasible", ctypes.c_int32)]
+
+
 class UnitError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -60,6 +71,7 @@ EXPORTS = [
     "unit_maxpool_packed_i8", "unit_global_avgpool_packed_i8", "unit_widen_residual_i8",
     "unit_conv2d_wpacked_workspace", "unit_conv2d_wpacked_i8", "unit_conv2d_wpacked_f16",
     "unit_conv3d_out_dims", "unit_conv3d_workspace", "unit_conv3d_i8", "unit_conv3d_f16",
+    "unit_inspect", "unit_describe_mfma", "unit_describe_conv2d", "unit_describe_matmul",
 ]
 
 
@@ -111,6 +123,10 @@ def load():
         "unit_maxpool_packed_i8": (ctypes.c_int, [i32, i32, i32, i32, i32, i32, i32, vp, vp, vp]),
         "unit_global_avgpool_packed_i8": (ctypes.c_int, [i32, i32, i32, i32, vp, vp, vp, vp]),
         "unit_widen_residual_i8": (ctypes.c_int, [i32, i32, i32, i32, vp, i32, vp, vp]),
+        "unit_inspect": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_char_p, ctypes.POINTER(unit_inspect_result)]),
+        "unit_describe_mfma": (ctypes.c_int, [ctypes.c_int, i32, ctypes.c_char_p, sz]),
+        "unit_describe_conv2d": (ctypes.c_int, [dp, ctypes.c_int, ctypes.c_char_p, sz]),
+        "unit_describe_matmul": (ctypes.c_int, [i32, i32, i32, ctypes.c_int, ctypes.c_char_p, sz]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(L, name)
@@ -326,3 +342,41 @@ def unit_global_avgpool_packed_i8(n, c, h, w, xp, scale, y, stream=None):
 def unit_widen_residual_i8(n, c, h, w, xp, mult, residual, stream=None):
     _check(load().unit_widen_residual_i8(n, c, h, w, _p(xp), mult, _p(residual), _stream(stream)),
            "unit_widen_residual_i8")
+
+
+# ------------------------------------------------------------------ applicability inspection (host only)
+
+def unit_inspect(instruction, operation):
+    """-> dict(applicable, failed_step, mapping {instr loop: op loop},
+    operands [(instr register, op array, [broadcast loops])], num_feasible)."""
+    res = unit_inspect_result()
+    _check(load().unit_inspect(instruction.encode(), operation.encode(), ctypes.byref(res)), "unit_inspect")
+    loops = [res.instr_loop[i].value.decode() for i in range(res.num_loops)]
+    mapping = {loops[i]: res.op_loop[i].value.decode() for i in range(res.num_loops)}
+    operands = []
+    for i in range(res.num_operands):
+        bc = [loops[b] for b in range(res.num_loops) if res.broadcast[i] >> b & 1]
+        operands.append((res.instr_operand[i].value.decode(), res.op_operand[i].value.decode(), bc))
+    return {"applicable": bool(res.applicable), "failed_step": res.failed_step, "mapping": mapping,
+            "operands": operands, "num_feasible": res.num_feasible}
+
+
+def _describe(fn, name, *args):
+    need = fn(*args, None, 0)
+    if need < 0:
+        _check(need, name)
+    buf = ctypes.create_string_buffer(need)
+    fn(*args, buf, need)
+    return buf.value.decode()
+
+
+def unit_describe_mfma(dtype, edge):
+    return _describe(load().unit_describe_mfma, "unit_describe_mfma", dtype, edge)
+
+
+def unit_describe_conv2d(d, dtype):
+    return _describe(load().unit_describe_conv2d, "unit_describe_conv2d", ctypes.byref(d), dtype)
+
+
+def unit_describe_matmul(m, n, k, dtype):
+    return _describe(load().unit_describe_matmul, "unit_describe_matmul", m, n, k, dtype)
