@@ -66,6 +66,14 @@ def _load():
     L.oracle_maxpool_i8.argtypes = [i] * 10 + [p, p]
     L.oracle_global_sumpool_requant_i8.argtypes = [i, i, i, p, p, p]
     L.oracle_widen_scale_i8.argtypes = [ctypes.c_size_t, p, ctypes.c_int32, p]
+    L.oracle_bf16_to_float.restype = ctypes.c_float
+    L.oracle_bf16_to_float.argtypes = [ctypes.c_uint16]
+    L.oracle_conv2d_u8i8.argtypes = conv_args
+    L.oracle_matmul_u8i8.argtypes = mm_args
+    L.oracle_conv2d_bf16.argtypes = conv_args + [p, p]
+    L.oracle_matmul_bf16.argtypes = [i, i, i, p, l, p, l, p, p, p, l]
+    for name in ("oracle_conv2d_u8i8", "oracle_matmul_u8i8", "oracle_conv2d_bf16", "oracle_matmul_bf16"):
+        getattr(L, name).restype = None
     for name in ("oracle_conv2d_i8", "oracle_conv2d_f16", "oracle_conv2d_f16_f64",
                  "oracle_matmul_i8", "oracle_matmul_f16", "oracle_matmul_f16_f64",
                  "oracle_requant", "oracle_maxpool_i8", "oracle_global_sumpool_requant_i8",
@@ -258,3 +266,48 @@ def widen_scale_i8(x, mult):
     y = np.empty(x.shape, np.int32)
     _load().oracle_widen_scale_i8(x.size, _ptr(x), int(mult), _ptr(y))
     return y
+
+
+# ------------------------------------------------------------------ other operand types
+
+def bf16_to_float(bits):
+    return float(_load().oracle_bf16_to_float(int(bits)))
+
+
+def conv2d_u8i8(x, w, stride=(1, 1), pad=(0, 0)):
+    """x uint8 NCHW, w int8 KCRS -> int32 NKPQ."""
+    _chk(x, np.uint8), _chk(w, np.int8)
+    dims, oshape = _conv_dims(x, w, stride, pad)
+    y = np.empty(oshape, np.int32)
+    _load().oracle_conv2d_u8i8(*dims, _ptr(x), _ptr(w), _ptr(y))
+    return y
+
+
+def matmul_u8i8(A, B):
+    """A uint8 [M,K]; B int8 [N,K] -> int32 [M,N]."""
+    _chk(A, np.uint8), _chk(B, np.int8)
+    M, N, K = _mm_dims(A, B)
+    C = np.empty((M, N), np.int32)
+    _load().oracle_matmul_u8i8(M, N, K, _ptr(A), K, _ptr(B), K, _ptr(C), N)
+    return C
+
+
+def conv2d_bf16(x, w, stride=(1, 1), pad=(0, 0)):
+    """bfloat16 bit patterns -> (fp32 result, fp64-accumulated value, sum of |products|)."""
+    _chk(x, np.uint16), _chk(w, np.uint16)
+    dims, oshape = _conv_dims(x, w, stride, pad)
+    y = np.empty(oshape, np.float32)
+    y64 = np.empty(oshape, np.float64)
+    ya = np.empty(oshape, np.float64)
+    _load().oracle_conv2d_bf16(*dims, _ptr(x), _ptr(w), _ptr(y), _ptr(y64), _ptr(ya))
+    return y, y64, ya
+
+
+def matmul_bf16(A, B):
+    _chk(A, np.uint16), _chk(B, np.uint16)
+    M, N, K = _mm_dims(A, B)
+    C = np.empty((M, N), np.float32)
+    C64 = np.empty((M, N), np.float64)
+    Ca = np.empty((M, N), np.float64)
+    _load().oracle_matmul_bf16(M, N, K, _ptr(A), K, _ptr(B), K, _ptr(C), _ptr(C64), _ptr(Ca), N)
+    return C, C64, Ca

@@ -403,3 +403,121 @@ void oracle_widen_scale_i8(size_t count, const int8_t *x, int32_t mult, int32_t 
 {
     for (size_t i = 0; i < count; ++i) y[i] = (int32_t)x[i] * mult;
 }
+
+/* ------------------------------------------------- other operand types */
+
+/*
+ * The paper presents its method as open to further operand types (Section I;
+ * Section III-A describes an unsigned-byte x signed-byte instruction).  Two more
+ * pairs, same definitions as above with only the element decoding changed:
+ *   u8 x i8 -> i32   (the x86 instruction's operand types: activations unsigned)
+ *   bf16 x bf16 -> f32
+ */
+
+/* bfloat16 bit pattern -> float: the pattern is the upper half of the binary32 word. */
+float oracle_bf16_to_float(uint16_t b)
+{
+    uint32_t word = (uint32_t)b << 16;
+    float f;
+    memcpy(&f, &word, sizeof f);
+    return f;
+}
+
+void oracle_conv2d_u8i8(int N, int C, int H, int W, int K, int R, int S,
+                        int sh, int sw, int ph, int pw,
+                        const uint8_t *x, const int8_t *w, int32_t *y)
+{
+    const int P = oracle_out_dim(H, R, sh, ph);
+    const int Q = oracle_out_dim(W, S, sw, pw);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k)
+            for (int p = 0; p < P; ++p)
+                for (int q = 0; q < Q; ++q) {
+                    int32_t acc = 0;
+                    for (int c = 0; c < C; ++c)
+                        for (int r = 0; r < R; ++r)
+                            for (int s = 0; s < S; ++s) {
+                                int h  = p * sh + r - ph;
+                                int ww = q * sw + s - pw;
+                                if (h < 0 || h >= H || ww < 0 || ww >= W) continue;
+                                int32_t a = (int32_t)x[(((size_t)n * C + c) * H + h) * W + ww];
+                                int32_t b = (int32_t)w[(((size_t)k * C + c) * R + r) * S + s];
+                                acc += a * b;
+                            }
+                    y[(((size_t)n * K + k) * P + p) * Q + q] = acc;
+                }
+}
+
+void oracle_matmul_u8i8(int M, int N, int K,
+                        const uint8_t *A, long lda, const int8_t *B, long ldb,
+                        int32_t *C, long ldc)
+{
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m)
+        for (int n = 0; n < N; ++n) {
+            int32_t acc = 0;
+            for (int k = 0; k < K; ++k)
+                acc += (int32_t)A[(size_t)m * lda + k] * (int32_t)B[(size_t)n * ldb + k];
+            C[(size_t)m * ldc + n] = acc;
+        }
+}
+
+/* bf16: products of two 8-bit significands are exact in fp32 while the exponents stay in
+ * range; y = sequential fp32 sum in c -> r -> s order, y64 / yabs as for binary16. */
+void oracle_conv2d_bf16(int N, int C, int H, int W, int K, int R, int S,
+                        int sh, int sw, int ph, int pw,
+                        const uint16_t *x, const uint16_t *w,
+                        float *y, double *y64, double *yabs)
+{
+    const int P = oracle_out_dim(H, R, sh, ph);
+    const int Q = oracle_out_dim(W, S, sw, pw);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k)
+            for (int p = 0; p < P; ++p)
+                for (int q = 0; q < Q; ++q) {
+                    float acc = 0.0f;
+                    double acc64 = 0.0, aacc = 0.0;
+                    for (int c = 0; c < C; ++c)
+                        for (int r = 0; r < R; ++r)
+                            for (int s = 0; s < S; ++s) {
+                                int h  = p * sh + r - ph;
+                                int ww = q * sw + s - pw;
+                                if (h < 0 || h >= H || ww < 0 || ww >= W) continue;
+                                float a = oracle_bf16_to_float(x[(((size_t)n * C + c) * H + h) * W + ww]);
+                                float b = oracle_bf16_to_float(w[(((size_t)k * C + c) * R + r) * S + s]);
+                                float prod = a * b;
+                                acc = acc + prod;
+                                acc64 += (double)a * (double)b;
+                                aacc  += fabs((double)a * (double)b);
+                            }
+                    size_t o = (((size_t)n * K + k) * P + p) * Q + q;
+                    y[o] = acc;
+                    if (y64)  y64[o]  = acc64;
+                    if (yabs) yabs[o] = aacc;
+                }
+}
+
+void oracle_matmul_bf16(int M, int N, int K,
+                        const uint16_t *A, long lda, const uint16_t *B, long ldb,
+                        float *C, double *C64, double *Cabs, long ldc)
+{
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m)
+        for (int n = 0; n < N; ++n) {
+            float acc = 0.0f;
+            double acc64 = 0.0, aacc = 0.0;
+            for (int k = 0; k < K; ++k) {
+                float a = oracle_bf16_to_float(A[(size_t)m * lda + k]);
+                float b = oracle_bf16_to_float(B[(size_t)n * ldb + k]);
+                float prod = a * b;
+                acc = acc + prod;
+                acc64 += (double)a * (double)b;
+                aacc  += fabs((double)a * (double)b);
+            }
+            C[(size_t)m * ldc + n] = acc;
+            if (C64)  C64[(size_t)m * ldc + n]  = acc64;
+            if (Cabs) Cabs[(size_t)m * ldc + n] = aacc;
+        }
+}

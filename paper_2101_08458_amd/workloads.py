@@ -64,6 +64,18 @@ def f16_weights(g, shape, fan_in):
     return f16_bits(g.standard_normal(size=shape) * np.sqrt(2.0 / fan_in))
 
 
+def uint8_activations(g, shape):
+    """Unsigned activations over the full byte range (post-ReLU quantised tensors)."""
+    return g.integers(0, 256, size=shape, dtype=np.int64).astype(np.uint8)
+
+
+def bf16_bits(values):
+    """float32 array -> bfloat16 bit patterns (uint16), round to nearest even."""
+    u = np.ascontiguousarray(values, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = u + 0x7FFF + ((u >> 16) & 1)
+    return (u >> 16).astype(np.uint16)
+
+
 def conv_inputs_i8(sh, n, config_id, layer_id=0):
     g = rng(config_id, layer_id)
     x = int8_activations(g, (n, sh.c, sh.h, sh.w))
@@ -76,6 +88,31 @@ def conv_inputs_f16(sh, n, config_id, layer_id=0):
     x = f16_activations(g, (n, sh.c, sh.h, sh.w))
     w = f16_weights(g, (sh.k, sh.c, sh.r, sh.s), sh.c * sh.r * sh.s)
     return x, w
+
+
+def conv_inputs_u8i8(sh, n, config_id, layer_id=0):
+    g = rng(config_id, layer_id)
+    x = uint8_activations(g, (n, sh.c, sh.h, sh.w))
+    w = int8_weights(g, (sh.k, sh.c, sh.r, sh.s))
+    return x, w
+
+
+def conv_inputs_bf16(sh, n, config_id, layer_id=0):
+    g = rng(config_id, layer_id)
+    x = bf16_bits(g.standard_normal(size=(n, sh.c, sh.h, sh.w)))
+    w = bf16_bits(g.standard_normal(size=(sh.k, sh.c, sh.r, sh.s)) * np.sqrt(2.0 / (sh.c * sh.r * sh.s)))
+    return x, w
+
+
+def gemm_inputs_u8i8(m, n, k, config_id=2, layer_id=2):
+    g = rng(config_id, layer_id)
+    return uint8_activations(g, (m, k)), int8_weights(g, (n, k))
+
+
+def gemm_inputs_bf16(m, n, k, config_id=2, layer_id=3):
+    g = rng(config_id, layer_id)
+    return (bf16_bits(g.standard_normal(size=(m, k))),
+            bf16_bits(g.standard_normal(size=(n, k)) * np.sqrt(2.0 / k)))
 
 
 def gemm_inputs_i8(m, n, k, config_id=2, layer_id=0):
