@@ -23,7 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK = {"i8": 5000.0, "f16": 2500.0}        # dense MFMA TOPS / TFLOPS (published MI355X)
+PEAK = {"i8": 5000.0, "u8i8": 5000.0, "f16": 2500.0, "bf16": 2500.0}        # dense MFMA TOPS / TFLOPS (published MI355X)
 HBM_GBS = 8000.0
 # HBM-side bytes per launch (per step for the layer set) of the main kernel, from the committed
 # rocprofv3 counter runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy in the
@@ -98,25 +98,32 @@ class ConvCase:
 
 
 class GemmCase:
+    _KINDS = {   # dtype -> (inputs, numpy view, element bytes, unit_dtype name, entry point)
+        "i8": ("gemm_inputs_i8", np.int8, 1, "UNIT_I8", "unit_matmul_i8"),
+        "f16": ("gemm_inputs_f16", np.int16, 2, "UNIT_F16", "unit_matmul_f16"),
+        "bf16": ("gemm_inputs_bf16", np.int16, 2, "UNIT_BF16", "unit_matmul_bf16"),
+        "u8i8": ("gemm_inputs_u8i8", None, 1, "UNIT_U8I8", "unit_matmul_u8i8"),
+    }
+
     def __init__(self, torch, unit, wl, m, n, k, dtype):
         dev = "cuda:0"
-        i8 = dtype == "i8"
+        gen, view, es, ut, fn = self._KINDS[dtype]
+        integer = es == 1
         self.unit, self.dtype, self.m, self.n, self.k = unit, dtype, m, n, k
-        A, B = (wl.gemm_inputs_i8 if i8 else wl.gemm_inputs_f16)(m, n, k)
-        self.A = torch.from_numpy(A.view(np.int8 if i8 else np.int16)).to(dev)
-        self.B = torch.from_numpy(B.view(np.int8 if i8 else np.int16)).to(dev)
-        self.C = torch.empty((m, n), dtype=torch.int32 if i8 else torch.float32, device=dev)
-        ut = unit.UNIT_I8 if i8 else unit.UNIT_F16
+        A, B = getattr(wl, gen)(m, n, k)
+        self.A = torch.from_numpy(A.view(view) if view else A).to(dev)
+        self.B = torch.from_numpy(B.view(view) if view else B).to(dev)
+        self.C = torch.empty((m, n), dtype=torch.int32 if integer else torch.float32, device=dev)
+        ut = getattr(unit, ut)
+        self.fn = getattr(unit, fn)
         self.ws = torch.empty(max(unit.unit_matmul_workspace(m, n, k, k, k, ut), 256), dtype=torch.uint8, device=dev)
         self.macs = m * n * k
-        self.bytes = (m * k + n * k) * (1 if i8 else 2) + m * n * 4
+        self.bytes = (m * k + n * k) * es + m * n * 4
         self.info = unit.unit_select_matmul(m, n, k, ut)
         torch.cuda.synchronize()
 
     def run(self):
-        u = self.unit
-        f = u.unit_matmul_i8 if self.dtype == "i8" else u.unit_matmul_f16
-        f(self.m, self.n, self.k, self.A, self.k, self.B, self.k, self.C, self.n, self.ws)
+        self.fn(self.m, self.n, self.k, self.A, self.k, self.B, self.k, self.C, self.n, self.ws)
 
 
 def event_ms(torch, fn, reps, warm=2):
@@ -173,23 +180,23 @@ def mfma_roofline(dtype, macs, ms, traffic=None):
 
 
 def cpu_baseline(wl, budget_s=12.0):
-    """The CPU oracle, as it stands, on the first layers of the same ResNet-50-shaped set
-    until about `budget_s` seconds of host time are used."""
+    """The CPU oracle, as it stands, on whole passes over the same ResNet-50-shaped layer set
+    (batch 1) until about `budget_s` seconds of host time are used; at least one full pass."""
     import oracle
     oracle.build()
-    macs, secs, used = 0, 0.0, 0
-    for idx, sh in enumerate(wl.resnet50_convs()):
-        x, w = wl.conv_inputs_i8(sh, 1, 3, idx)
-        t0 = time.perf_counter()
-        oracle.conv2d_i8(x, w, (sh.stride,) * 2, (sh.pad,) * 2)
-        secs += time.perf_counter() - t0
-        macs += wl.macs(sh)
-        used += 1
-        if secs > budget_s:
-            break
+    layers = wl.resnet50_convs()
+    inputs = [wl.conv_inputs_i8(sh, 1, 3, idx) for idx, sh in enumerate(layers)]
+    macs, secs, passes = 0, 0.0, 0
+    while secs < budget_s:
+        for sh, (x, w) in zip(layers, inputs):
+            t0 = time.perf_counter()
+            oracle.conv2d_i8(x, w, (sh.stride,) * 2, (sh.pad,) * 2)
+            secs += time.perf_counter() - t0
+            macs += wl.macs(sh)
+        passes += 1
     return {"value": round(2.0 * macs / secs / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
-            "kind": "oracle", "sample": f"first {used} of the 53 ResNet-50-shaped int8 conv layers at batch 1, "
-                                        f"{macs / 1e9:.2f} GMAC in {secs:.2f} s, OpenMP direct loops"}
+            "kind": "oracle", "sample": f"{passes} full passes over the 53 ResNet-50-shaped int8 conv layers at "
+                                        f"batch 1, {macs / 1e9:.2f} GMAC in {secs:.2f} s, OpenMP direct loops"}
 
 
 def vendor_context(torch):
@@ -433,7 +440,7 @@ def main():
         def add(name, dtype, macs, byts, ms, info, extra=None):
             tops = 2.0 * macs / (ms * 1e-3) / 1e12
             e = {"workload": name, "dtype": dtype, "us": round(ms * 1e3, 2), "value": round(tops, 2),
-                 "unit": "TOPS" if dtype == "i8" else "TFLOPS",
+                 "unit": "TOPS" if dtype in ("i8", "u8i8") else "TFLOPS",
                  "frac_mfma_peak": round(tops / PEAK[dtype], 4),
                  "GBps": round(byts / (ms * 1e-3) / 1e9, 1), "tile": tile_str(info)}
             if extra:
@@ -449,6 +456,10 @@ def main():
             add("large conv N=32 C=K=256 56x56 3x3, pack_act + conv", dtype, c.macs, c.bytes, event_ms(torch, c.api, 20), c.info)
             del c
             torch.cuda.empty_cache()
+        for dtype in ("u8i8", "bf16"):      # further operand types through the same kernel
+            g = GemmCase(torch, unit, wl, 4096, 4096, 4096, dtype)
+            add("gemm 4096^3", dtype, g.macs, g.bytes, event_ms(torch, g.run, 30), g.info)
+            del g
         c = ConvCase(torch, unit, wl, wl.CONFIG1, 1, "i8", 1, 0)
         add("config 1: conv 1x64x56x56 * 64x64x3x3, kernel only", "i8", c.macs, c.bytes, event_ms(torch, c.conv, 200), c.info)
         add("config 1, pack_act + conv", "i8", c.macs, c.bytes, event_ms(torch, c.api, 200), c.info)

@@ -24,8 +24,16 @@ typedef int      v16i __attribute__((ext_vector_type(16)));
 typedef float    v4f  __attribute__((ext_vector_type(4)));
 typedef float    v16f __attribute__((ext_vector_type(16)));
 typedef _Float16 v8h  __attribute__((ext_vector_type(8)));
+typedef __bf16   v8bf __attribute__((ext_vector_type(8)));
 
-enum { DT_I8 = 0, DT_F16 = 1 };
+// Operand types.  The matrix unit multiplies signed bytes only; an unsigned-byte operand u is
+// fed as u - 128 (its bytes XORed with 0x80 on the way into the fragments) and the caller
+// supplies 128 * (sum of the other operand along the reduction) as an additive correction:
+// DT_U8A has the unsigned operand on the A side (correction per output column), DT_U8B on
+// the B side (correction per output row).  Bytes the hardware zero-fills (reduction tail,
+// conv padding) become -128 the same way; the other operand is zero on the tail, and for
+// conv padding the correction sums every tap, so both cancel exactly.
+enum { DT_I8 = 0, DT_F16 = 1, DT_BF16 = 2, DT_U8A = 3, DT_U8B = 4 };
 enum { EPI_RAW = 0, EPI_REQUANT = 1 };
 // where the B operand (columns) comes from: a plain matrix, the packed-NHWC conv gather, or
 // an NCHW tensor read directly (1x1 stride-1 convs of one image: channel rows of pixels,
@@ -87,6 +95,19 @@ template <> struct Mma<DT_F16, 16> {
     static __device__ __forceinline__ void run(acc_t &c, const v4i &a, const v4i &b)
     { c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0); }
 };
+
+template <> struct Mma<DT_BF16, 32> {
+    typedef v16f acc_t;  typedef float elem_t;  enum { NACC = 16 };
+    static __device__ __forceinline__ void run(acc_t &c, const v4i &a, const v4i &b)
+    { c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0); }
+};
+template <> struct Mma<DT_BF16, 16> {
+    typedef v4f acc_t;  typedef float elem_t;  enum { NACC = 4 };
+    static __device__ __forceinline__ void run(acc_t &c, const v4i &a, const v4i &b)
+    { c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0); }
+};
+template <int MF> struct Mma<DT_U8A, MF> : Mma<DT_I8, MF> {};
+template <int MF> struct Mma<DT_U8B, MF> : Mma<DT_I8, MF> {};
 
 // Row of accumulator element e held by `lane` inside one MFMA tile (column is lane % MF).
 template <int MF> __device__ __forceinline__ int acc_row(int e, int lane)
@@ -172,7 +193,7 @@ igemm_kernel(const IgemmArgs g)
     typedef typename M::elem_t elem_t;
     constexpr int NW = C::NW, NCH = C::NCH, TM = C::TM, TN = C::TN, IA = C::IA, IB = C::IB, RPI = C::RPI;
     constexpr bool CONV = (BSRC != BSRC_PLAIN);     // conv-style output indexing
-    constexpr int ES = (DT == DT_I8) ? 1 : 2;       // operand element bytes
+    constexpr int ES = (DT == DT_F16 || DT == DT_BF16) ? 2 : 1;   // operand element bytes
     constexpr int EPC = 16 / ES;                    // elements per 16-byte chunk
     constexpr int CPR = BN * ES / 16;               // NCHW mode: 16-byte chunks per channel row of the B tile
     constexpr int CRPI = 64 / CPR;                  // NCHW mode: channel rows per DMA instruction
@@ -350,6 +371,10 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             fa[slot][i] = *reinterpret_cast<const v4i *>(sA + (a_row + i * MF) * BKB + ((ch ^ a_swz) << 4));
+        if (DT == DT_U8A) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) fa[slot][i] ^= (int)0x80808080;
+        }
         if (BSRC == BSRC_NCHW) {
             // B tile is [channel][pixel]: gather this lane's 16 bytes of consecutive channels
             // for its pixel column, one element per LDS read
@@ -376,6 +401,10 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
             for (int j = 0; j < TN; ++j)
                 fb[slot][j] = *reinterpret_cast<const v4i *>(sB + (b_row + j * MF) * BKB + ((ch ^ b_swz) << 4));
+        }
+        if (DT == DT_U8B) {
+#pragma unroll
+            for (int j = 0; j < TN; ++j) fb[slot][j] ^= (int)0x80808080;
         }
     };
 
@@ -476,6 +505,21 @@ igemm_kernel(const IgemmArgs g)
         const elem_t *tile_base = reinterpret_cast<const elem_t *>(g.out) + (long)blockIdx.z * g.split_stride +
                                   (long)row0 * g.row_stride;
         const __amdgpu_buffer_rsrc_t rsO = make_rsrc(tile_base, UNIT_OOB);   // lanes are masked explicitly
+        // Unsigned-operand correction, added once (by the first reduction slice).  Per row
+        // (DT_U8B) a lane's accumulator elements 4a..4a+3 sit in four consecutive rows: one
+        // 16-byte load each; the vector is allocated in whole 256-byte blocks, rows past the
+        // end read as zero and are never stored.
+        v4i row_fix[TM][M::NACC / 4];
+        if (DT == DT_U8B) {
+            const __amdgpu_buffer_rsrc_t rsF = make_rsrc(g.bias, (unsigned)((g.rows * 4 + 255) & ~255));
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int a4 = 0; a4 < M::NACC / 4; ++a4) {
+                    const int r = row0 + wm * C::WTM + i * MF + acc_row<MF>(4 * a4, lane);
+                    row_fix[i][a4] = buf_load16(rsF, blockIdx.z == 0 ? (unsigned)r * 4u : UNIT_OOB);
+                }
+        }
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = col0 + wn * C::WTN + j * MF + lrow;
@@ -487,6 +531,8 @@ igemm_kernel(const IgemmArgs g)
                 cbase = (unsigned)col;
             }
             const bool col_ok = col < g.cols;
+            elem_t col_fix = 0;
+            if (DT == DT_U8A && col_ok && blockIdx.z == 0) col_fix = (elem_t)g.bias[col];
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -494,7 +540,9 @@ igemm_kernel(const IgemmArgs g)
                     const int lr = wm * C::WTM + i * MF + acc_row<MF>(e, lane);
                     const bool ok = col_ok && lr < rows_here;
                     const unsigned off = ok ? (cbase + (unsigned)lr * (unsigned)g.row_stride) * 4u : UNIT_OOB;
-                    const elem_t val = acc[i][j][e];
+                    elem_t val = acc[i][j][e];
+                    if (DT == DT_U8A) val += col_fix;
+                    if (DT == DT_U8B) val += (elem_t)row_fix[i][e >> 2][e & 3];
                     __builtin_amdgcn_raw_buffer_store_b32(to_bits(val), rsO, off, 0, 0);
                 }
             }

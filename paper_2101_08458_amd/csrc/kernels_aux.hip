@@ -47,7 +47,7 @@ pack_act_kernel(const T *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW
 hipError_t launch_pack_act(int dtype, int n, int c, int h, int w, const void *x, void *xp, hipStream_t st)
 {
     const int hw = h * w;
-    if (dtype == DT_I8) {
+    if (dtype == DT_I8) {   // callers pass the storage type: one- or two-byte elements
         const int cp = (c + 15) / 16 * 16;
         dim3 grid((hw + 63) / 64, (cp + 63) / 64, n);
         hipLaunchKernelGGL(pack_act_kernel<int8_t>, grid, dim3(256), 0, st,
@@ -101,7 +101,7 @@ __global__ void pack_weights_kernel(const T *__restrict__ w, T *__restrict__ wp,
 
 hipError_t launch_pack_weights(int dtype, int k, int c, int r, int s, const void *w, void *wp, hipStream_t st)
 {
-    if (dtype == DT_I8) {
+    if (dtype == DT_I8) {   // callers pass the storage type: one- or two-byte elements
         int cp = (c + 15) / 16 * 16;
         long total = (long)k * r * s * cp;
         hipLaunchKernelGGL(pack_weights_kernel<int8_t>, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
@@ -221,6 +221,38 @@ hipError_t launch_splitk_reduce(const ReduceArgs &a, hipStream_t st)
         e = hipGetLastError();
     }
     return e;
+}
+
+// ------------------------------------------------------------------ unsigned-operand correction
+// out[r] = 128 * (sum of the signed bytes of row r); rows are `ld` bytes apart, 16-byte
+// aligned and `chunks` 16-byte chunks long.  One wave per row.
+__global__ void __launch_bounds__(256)
+rowsum128_i8_kernel(const uint8_t *__restrict__ m, long ld, int rows, int chunks, int32_t *__restrict__ out)
+{
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (row >= rows) return;
+    const v4i *p = reinterpret_cast<const v4i *>(m + (long)row * ld);
+    int sum = 0;
+    for (int c = lane; c < chunks; c += 64) {
+        v4i v = p[c];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            int w = v[d];
+            sum += (int)(int8_t)(w & 0xff) + (int)(int8_t)((w >> 8) & 0xff) +
+                   (int)(int8_t)((w >> 16) & 0xff) + (w >> 24);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    if (lane == 0) out[row] = sum * 128;
+}
+
+hipError_t launch_rowsum128_i8(const void *m, long ld, int rows, int chunks, int32_t *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(rowsum128_i8_kernel, dim3((rows + 3) / 4), dim3(256), 0, st,
+                       static_cast<const uint8_t *>(m), ld, rows, chunks, out);
+    return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ int8 network glue

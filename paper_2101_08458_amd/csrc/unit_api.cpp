@@ -9,11 +9,19 @@
 namespace unit {
 hipError_t launch_igemm_i8(int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
 hipError_t launch_igemm_f16(int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
+hipError_t launch_igemm_bf16(int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
+hipError_t launch_igemm_u8(int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
 
+// dtype is the public unit_dtype
 hipError_t launch_igemm(int dtype, int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st)
 {
-    return dtype == DT_I8 ? launch_igemm_i8(bsrc, tile, a, split_k, st)
-                          : launch_igemm_f16(bsrc, tile, a, split_k, st);
+    switch (dtype) {
+    case UNIT_I8:   return launch_igemm_i8(bsrc, tile, a, split_k, st);
+    case UNIT_F16:  return launch_igemm_f16(bsrc, tile, a, split_k, st);
+    case UNIT_BF16: return launch_igemm_bf16(bsrc, tile, a, split_k, st);
+    case UNIT_U8I8: return bsrc == BSRC_NCHW ? hipErrorInvalidValue : launch_igemm_u8(bsrc, tile, a, split_k, st);
+    default:        return hipErrorInvalidValue;
+    }
 }
 }  // namespace unit
 
@@ -52,7 +60,16 @@ int hip_fail(hipError_t e)
 #define UNIT_HIP(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) return hip_fail(e_); } while (0)
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
-inline int elem_size(int dtype) { return dtype == UNIT_I8 ? 1 : 2; }
+inline bool dtype_ok(int dtype) { return dtype >= UNIT_I8 && dtype <= UNIT_U8I8; }
+inline bool byte_type(int dtype) { return dtype == UNIT_I8 || dtype == UNIT_U8I8; }
+inline int elem_size(int dtype) { return byte_type(dtype) ? 1 : 2; }
+// what the layout kernels and the split reduce need to know: one- or two-byte elements,
+// integer or float sums
+inline int storage_dtype(int dtype) { return byte_type(dtype) ? DT_I8 : DT_F16; }
+inline long max_reduction(int dtype)
+{
+    return dtype == UNIT_I8 ? UNIT_MAX_REDUCTION_I8 : dtype == UNIT_U8I8 ? UNIT_MAX_REDUCTION_U8I8 : 0x7fffffffL;
+}
 inline int chunk_elems(int dtype) { return 16 / elem_size(dtype); }
 inline int pad_channels(int c, int dtype) { int ch = chunk_elems(dtype); return (c + ch - 1) / ch * ch; }
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -80,14 +97,14 @@ struct ConvGeom {
 
 int conv_geom(const ConvND *d, int dtype, ConvGeom *g)
 {
-    if (dtype != UNIT_I8 && dtype != UNIT_F16) return UNIT_EINVAL;
+    if (!dtype_ok(dtype)) return UNIT_EINVAL;
     if (!desc_ok(d)) return UNIT_EINVAL;
     g->o = (d->d + 2 * d->pad_d - d->t) / d->stride_d + 1;
     g->p = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
     g->q = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
     g->cp = pad_channels(d->c, dtype);
     long red = (long)d->c * d->t * d->r * d->s;
-    if (dtype == UNIT_I8 && red > UNIT_MAX_REDUCTION_I8) return UNIT_EOVERFLOW;
+    if (red > max_reduction(dtype)) return UNIT_EOVERFLOW;
     long kbytes = (long)d->t * d->r * d->s * g->cp * elem_size(dtype);
     g->kchunks = (int)(kbytes / 16);
     g->rows = d->k;
@@ -136,7 +153,7 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
     ReduceArgs r;
     std::memset(&r, 0, sizeof r);
     r.partials = ws;  r.nsplit = ch.split_k;  r.split_stride = slice;
-    r.dtype = dtype;  r.total = out_elems;  r.K = K;  r.PQ = PQ;
+    r.dtype = storage_dtype(dtype);  r.total = out_elems;  r.K = K;  r.PQ = PQ;
     r.out = (a.epi == EPI_RAW || a.store_raw) ? a.out : nullptr;
     r.epi = a.epi;  r.scale = a.scale;  r.bias = a.bias;  r.residual = a.residual;  r.relu = a.relu;
     r.out_i8 = a.out_i8;  r.out_packed = a.out_packed;  r.packed_ld = a.packed_ld;
@@ -155,13 +172,14 @@ bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requan
     const bool rows_ok = (d->n == 1) ? (px * elem_size(dtype)) % 4 == 0 : px % chunk_elems(dtype) == 0;
     return d->t == 1 && d->r == 1 && d->s == 1 &&
            d->stride_d == 1 && d->stride_h == 1 && d->stride_w == 1 &&
-           d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr && rows_ok && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+           d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr && rows_ok && dtype != UNIT_U8I8 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
 }
 
 // `xp` is the packed activation tensor, or (nchw_direct) the caller's NCHW tensor itself.
 int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
                 void *y_raw, const unit_requant *rq, int8_t *y_i8, void *y_packed,
-                void *ws, size_t ws_bytes, void *stream, bool nchw_direct = false)
+                void *ws, size_t ws_bytes, void *stream, bool nchw_direct = false,
+                const int32_t *fix = nullptr)       // fix: per-channel correction of an unsigned operand
 {
     ConvGeom g;
     int rc = conv_geom(d, dtype, &g);
@@ -174,6 +192,7 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
         if (!y_raw || y_i8 || y_packed) return UNIT_EINVAL;
     }
     if (ws && !aligned256(ws)) return UNIT_EINVAL;
+    if ((dtype == UNIT_U8I8) != (fix != nullptr)) return UNIT_EINVAL;
 
     IgemmArgs a;
     std::memset(&a, 0, sizeof a);
@@ -195,7 +214,7 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
         a.packed_ld = pad_channels(d->k, UNIT_I8);
         a.store_raw = y_raw ? 1 : 0;
     } else {
-        a.epi = EPI_RAW;  a.store_raw = 1;
+        a.epi = EPI_RAW;  a.store_raw = 1;  a.bias = fix;
     }
     return run_igemm(dtype, nchw_direct ? BSRC_NCHW : BSRC_GATHER, a, g.out_elems, d->k, a.PQ, ws, ws_bytes,
                      static_cast<hipStream_t>(stream));
@@ -210,6 +229,11 @@ size_t packed_weights_bytes_nd(const ConvND *d, int dtype)
     return align256((size_t)d->k * d->t * d->r * d->s * pad_channels(d->c, dtype) * elem_size(dtype));
 }
 
+size_t conv_fix_bytes(const ConvND *d, int dtype)
+{
+    return dtype == UNIT_U8I8 ? align256((size_t)d->k * 4) : 0;
+}
+
 size_t conv_split_bytes(const ConvGeom &g, int dtype)
 {
     TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true);
@@ -218,7 +242,7 @@ size_t conv_split_bytes(const ConvGeom &g, int dtype)
 
 int conv_wpacked(const ConvND *d, int dtype, const void *x, const void *wp,
                  void *y_raw, const unit_requant *rq, int8_t *y_i8,
-                 void *ws, size_t ws_bytes, void *stream);
+                 void *ws, size_t ws_bytes, void *stream, const int32_t *fix = nullptr);
 bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requant *rq);
 
 // workspace conv_wpacked needs for this call (after the packed weights, if any)
@@ -243,18 +267,25 @@ int conv_plain(const ConvND *d, int dtype, const void *x, const void *w,
         return UNIT_EINVAL;
     }
     size_t wt_b = packed_weights_bytes_nd(d, dtype);
-    if (!ws || ws_bytes < wt_b + wpacked_need(d, dtype, g, x, rq)) return UNIT_EWORKSPACE;
+    size_t fix_b = conv_fix_bytes(d, dtype);
+    if (!ws || ws_bytes < wt_b + fix_b + wpacked_need(d, dtype, g, x, rq)) return UNIT_EWORKSPACE;
     if (!aligned256(ws)) return UNIT_EINVAL;
     uint8_t *wp = static_cast<uint8_t *>(ws);
-    UNIT_HIP(launch_pack_weights(dtype, d->k, d->c, d->t * d->r, d->s, w, wp, static_cast<hipStream_t>(stream)));
-    return conv_wpacked(d, dtype, x, wp, y_raw, rq, y_i8, wp + wt_b, ws_bytes - wt_b, stream);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    UNIT_HIP(launch_pack_weights(storage_dtype(dtype), d->k, d->c, d->t * d->r, d->s, w, wp, st));
+    int32_t *fix = nullptr;
+    if (fix_b) {            // unsigned activations: 128 * (sum of each filter's weights)
+        fix = reinterpret_cast<int32_t *>(wp + wt_b);
+        UNIT_HIP(launch_rowsum128_i8(wp, (long)g.kchunks * 16, d->k, g.kchunks, fix, st));
+    }
+    return conv_wpacked(d, dtype, x, wp, y_raw, rq, y_i8, wp + wt_b + fix_b, ws_bytes - wt_b - fix_b, stream, fix);
 }
 
 // NCHW activations + packed weights: fused direct read when possible, else pack_act into the
 // workspace followed by the packed kernel.
 int conv_wpacked(const ConvND *d, int dtype, const void *x, const void *wp,
                  void *y_raw, const unit_requant *rq, int8_t *y_i8,
-                 void *ws, size_t ws_bytes, void *stream)
+                 void *ws, size_t ws_bytes, void *stream, const int32_t *fix)
 {
     ConvGeom g;
     int rc = conv_geom(d, dtype, &g);
@@ -270,21 +301,22 @@ int conv_wpacked(const ConvND *d, int dtype, const void *x, const void *wp,
     size_t act_b = packed_act_bytes_nd(d, dtype);
     if (!ws || ws_bytes < act_b + split_b) return UNIT_EWORKSPACE;
     uint8_t *xp = static_cast<uint8_t *>(ws);
-    UNIT_HIP(launch_pack_act(dtype, d->n, d->c, d->d * d->h, d->w, x, xp, static_cast<hipStream_t>(stream)));
-    return conv_packed(d, dtype, xp, wp, y_raw, rq, y_i8, nullptr, split_b ? xp + act_b : nullptr, split_b, stream);
+    UNIT_HIP(launch_pack_act(storage_dtype(dtype), d->n, d->c, d->d * d->h, d->w, x, xp, static_cast<hipStream_t>(stream)));
+    return conv_packed(d, dtype, xp, wp, y_raw, rq, y_i8, nullptr, split_b ? xp + act_b : nullptr, split_b, stream,
+                       false, fix);
 }
 
 struct MatmulGeom {
     int kpad_bytes, kchunks;
     bool pad_a, pad_b;
-    size_t a_bytes, b_bytes, split_bytes;
+    size_t a_bytes, b_bytes, fix_bytes, split_bytes;
 };
 
 int matmul_geom(int m, int n, int k, long lda, long ldb, int dtype, MatmulGeom *g)
 {
-    if (dtype != UNIT_I8 && dtype != UNIT_F16) return UNIT_EINVAL;
+    if (!dtype_ok(dtype)) return UNIT_EINVAL;
     if (m <= 0 || n <= 0 || k <= 0 || lda < k || ldb < k) return UNIT_EINVAL;
-    if (dtype == UNIT_I8 && k > UNIT_MAX_REDUCTION_I8) return UNIT_EOVERFLOW;
+    if (k > max_reduction(dtype)) return UNIT_EOVERFLOW;
     const int es = elem_size(dtype);
     // a 256-row tile of either operand and of C must stay below 2 GiB (buffer descriptors)
     if (lda * es * 256 >= 0x7fffffffL || ldb * es * 256 >= 0x7fffffffL) return UNIT_ENOTSUP;
@@ -295,6 +327,7 @@ int matmul_geom(int m, int n, int k, long lda, long ldb, int dtype, MatmulGeom *
     g->pad_b = ktail || (ldb * es) % 16 != 0;
     g->a_bytes = g->pad_a ? align256((size_t)m * g->kpad_bytes) : 0;
     g->b_bytes = g->pad_b ? align256((size_t)n * g->kpad_bytes) : 0;
+    g->fix_bytes = dtype == UNIT_U8I8 ? align256((size_t)n * 4) : 0;
     TileChoice ch = select_tile(m, n, g->kchunks, dtype, false);
     g->split_bytes = ch.split_k > 1 ? align256((size_t)ch.split_k * (((long)m * n + 3) & ~3L) * 4) : 0;
     return UNIT_OK;
@@ -311,7 +344,7 @@ int matmul_any(int dtype, int m, int n, int k, const void *A, long lda, const vo
     const int es = elem_size(dtype);
     if ((!g.pad_a && !aligned16(A)) || (!g.pad_b && !aligned16(B))) return UNIT_EINVAL;
     if (reinterpret_cast<uintptr_t>(C) & 3) return UNIT_EINVAL;
-    size_t need = g.a_bytes + g.b_bytes + g.split_bytes;
+    size_t need = g.a_bytes + g.b_bytes + g.fix_bytes + g.split_bytes;
     if (need && (!ws || ws_bytes < need)) return UNIT_EWORKSPACE;
     if (need && !aligned256(ws)) return UNIT_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -334,6 +367,11 @@ int matmul_any(int dtype, int m, int n, int k, const void *A, long lda, const vo
     a.kchunks = g.kchunks;
     a.out = C;  a.row_stride = ldc;  a.img_stride = 0;  a.cols_per_img = n;
     a.epi = EPI_RAW;  a.store_raw = 1;
+    if (g.fix_bytes) {      // unsigned A: 128 * (sum of each column of B) corrects every output column
+        int32_t *fix = reinterpret_cast<int32_t *>(wsp);
+        UNIT_HIP(launch_rowsum128_i8(Bp, ldb_b, n, g.kchunks, fix, st));
+        a.bias = fix;  wsp += g.fix_bytes;
+    }
     // the split reduce writes a dense [m][n] result: only usable when ldc == n
     return run_igemm(dtype, BSRC_PLAIN, a, (long)m * n, 1, n, g.split_bytes ? wsp : nullptr, g.split_bytes, st,
                      ldc == n);
@@ -351,7 +389,7 @@ const char *unit_status_str(int status)
     case UNIT_OK:         return "ok";
     case UNIT_EINVAL:     return "invalid argument";
     case UNIT_ENOTSUP:    return "unsupported shape";
-    case UNIT_EOVERFLOW:  return "int8 reduction too long for an exact int32 sum";
+    case UNIT_EOVERFLOW:  return "byte reduction too long for an exact int32 sum";
     case UNIT_EWORKSPACE: return "workspace missing or too small";
     case UNIT_EHIP:       return "HIP runtime error";
     default:              return "unknown status";
@@ -371,14 +409,14 @@ int unit_conv2d_out_dims(const unit_conv2d_desc *d, int32_t *p, int32_t *q)
 
 size_t unit_packed_act_bytes(int32_t n, int32_t c, int32_t h, int32_t w, int dtype)
 {
-    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || (dtype != UNIT_I8 && dtype != UNIT_F16)) return 0;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || !dtype_ok(dtype)) return 0;
     return align256((size_t)n * h * w * pad_channels(c, dtype) * elem_size(dtype));
 }
 
 size_t unit_packed_weights_bytes(const unit_conv2d_desc *d, int dtype)
 {
     ConvND nd(d);
-    if (!desc_ok(&nd) || (dtype != UNIT_I8 && dtype != UNIT_F16)) return 0;
+    if (!desc_ok(&nd) || !dtype_ok(dtype)) return 0;
     return packed_weights_bytes_nd(&nd, dtype);
 }
 
@@ -395,14 +433,15 @@ size_t unit_conv2d_workspace(const unit_conv2d_desc *d, int dtype)
     ConvGeom g;
     ConvND nd(d);
     if (conv_geom(&nd, dtype, &g) != UNIT_OK) return 0;
-    return packed_act_bytes_nd(&nd, dtype) + packed_weights_bytes_nd(&nd, dtype) + conv_split_bytes(g, dtype);
+    return packed_act_bytes_nd(&nd, dtype) + packed_weights_bytes_nd(&nd, dtype) + conv_fix_bytes(&nd, dtype) +
+           conv_split_bytes(g, dtype);
 }
 
 size_t unit_matmul_workspace(int32_t m, int32_t n, int32_t k, int64_t lda, int64_t ldb, int dtype)
 {
     MatmulGeom g;
     if (matmul_geom(m, n, k, lda, ldb, dtype, &g) != UNIT_OK) return 0;
-    return g.a_bytes + g.b_bytes + g.split_bytes;
+    return g.a_bytes + g.b_bytes + g.fix_bytes + g.split_bytes;
 }
 
 int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out)
@@ -453,6 +492,34 @@ int unit_matmul_f16(int32_t m, int32_t n, int32_t k, const uint16_t *A, int64_t 
                     void *ws, size_t ws_bytes, void *stream)
 {
     return matmul_any(UNIT_F16, m, n, k, A, lda, B, ldb, C, ldc, ws, ws_bytes, stream);
+}
+
+int unit_conv2d_bf16(const unit_conv2d_desc *d, const uint16_t *x, const uint16_t *w,
+                     float *y, void *ws, size_t ws_bytes, void *stream)
+{
+    ConvND nd(d);
+    return conv_plain(&nd, UNIT_BF16, x, w, y, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+int unit_matmul_bf16(int32_t m, int32_t n, int32_t k, const uint16_t *A, int64_t lda,
+                     const uint16_t *B, int64_t ldb, float *C, int64_t ldc,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    return matmul_any(UNIT_BF16, m, n, k, A, lda, B, ldb, C, ldc, ws, ws_bytes, stream);
+}
+
+int unit_conv2d_u8i8(const unit_conv2d_desc *d, const uint8_t *x, const int8_t *w,
+                     int32_t *y, void *ws, size_t ws_bytes, void *stream)
+{
+    ConvND nd(d);
+    return conv_plain(&nd, UNIT_U8I8, x, w, y, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+int unit_matmul_u8i8(int32_t m, int32_t n, int32_t k, const uint8_t *A, int64_t lda,
+                     const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    return matmul_any(UNIT_U8I8, m, n, k, A, lda, B, ldb, C, ldc, ws, ws_bytes, stream);
 }
 
 static int pack_act_any(int dtype, int32_t n, int32_t c, int32_t h, int32_t w, const void *x,
@@ -593,7 +660,8 @@ size_t unit_conv3d_workspace(const unit_conv3d_desc *d, int dtype)
     ConvGeom g;
     ConvND nd(d);
     if (conv_geom(&nd, dtype, &g) != UNIT_OK) return 0;
-    return packed_act_bytes_nd(&nd, dtype) + packed_weights_bytes_nd(&nd, dtype) + conv_split_bytes(g, dtype);
+    return packed_act_bytes_nd(&nd, dtype) + packed_weights_bytes_nd(&nd, dtype) + conv_fix_bytes(&nd, dtype) +
+           conv_split_bytes(g, dtype);
 }
 
 int unit_conv3d_i8(const unit_conv3d_desc *d, const int8_t *x, const int8_t *w, int32_t *y,

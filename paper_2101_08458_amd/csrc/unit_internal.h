@@ -39,6 +39,9 @@ hipError_t launch_unpack_act_i8(int n, int c, int h, int w, const void *xp, int8
 hipError_t launch_pad_rows(const void *src, long ld_bytes, int rows, int row_bytes,
                            void *dst, int dst_row_bytes, hipStream_t st);
 
+// out[r] = 128 * sum of the signed bytes of row r (rows 16-byte aligned, chunks*16 bytes long)
+hipError_t launch_rowsum128_i8(const void *m, long ld, int rows, int chunks, int32_t *out, hipStream_t st);
+
 struct ReduceArgs {
     const void *partials;  int nsplit;  long split_stride;      // elements
     int dtype;

@@ -27,7 +27,7 @@ def test_exports_every_declared_symbol(lib):
     for name in declared:
         assert getattr(lib, name) is not None
     assert unit.unit_version() >= 100
-    assert unit.unit_status_str(unit.UNIT_EOVERFLOW).startswith("int8 reduction")
+    assert unit.unit_status_str(unit.UNIT_EOVERFLOW).startswith("byte reduction")
 
 
 def test_out_dims_and_sizes(lib):

@@ -1,0 +1,211 @@
+"""GPU parity for the further operand types (u8 x i8 -> i32 bit-exact, bf16 x bf16 -> f32 within
+the fp16 tolerance rule) against the CPU oracle, through the C ABI, on every tile shape."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2101_08458_amd import unit, workloads as wl
+from gpu_util import announce, dev, host, forced, f16_rel_err, same
+
+pytestmark = pytest.mark.gpu
+
+ALL_TILES = [0, 1, 2, 3, 4, 5]
+
+
+def ws_bytes(nbytes):
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device="cuda:0")
+
+
+def run_matmul(kind, A, B, lda=None, ldb=None, ldc=None):
+    M, K = A.shape
+    N = B.shape[0]
+    lda, ldb, ldc = lda or K, ldb or K, ldc or N
+    Ap = np.zeros((M, lda), A.dtype); Ap[:, :K] = A
+    Bp = np.zeros((N, ldb), B.dtype); Bp[:, :K] = B
+    Ad, Bd = dev(Ap), dev(Bp)
+    if kind == "u8i8":
+        C = torch.full((M, ldc), -7, dtype=torch.int32, device="cuda:0")
+        ws = ws_bytes(unit.unit_matmul_workspace(M, N, K, lda, ldb, unit.UNIT_U8I8))
+        unit.unit_matmul_u8i8(M, N, K, Ad, lda, Bd, ldb, C, ldc, ws)
+    else:
+        C = torch.full((M, ldc), -7.0, dtype=torch.float32, device="cuda:0")
+        ws = ws_bytes(unit.unit_matmul_workspace(M, N, K, lda, ldb, unit.UNIT_BF16))
+        unit.unit_matmul_bf16(M, N, K, Ad, lda, Bd, ldb, C, ldc, ws)
+    torch.cuda.synchronize()
+    out = host(C)
+    if ldc > N:
+        assert np.all(out[:, N:] == -7)          # columns beyond n are never written
+    return out[:, :N]
+
+
+def run_conv(kind, sh, n, x, w):
+    d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
+    p, q = unit.unit_conv2d_out_dims(d)
+    if kind == "u8i8":
+        ws = ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_U8I8))
+        y = torch.full((n, sh.k, p, q), -7, dtype=torch.int32, device="cuda:0")
+        unit.unit_conv2d_u8i8(d, dev(x), dev(w), y, ws)
+    else:
+        ws = ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_BF16))
+        y = torch.empty((n, sh.k, p, q), dtype=torch.float32, device="cuda:0")
+        unit.unit_conv2d_bf16(d, dev(x), dev(w), y, ws)
+    torch.cuda.synchronize()
+    return host(y)
+
+
+# ------------------------------------------------------------------ u8 x i8
+
+@pytest.mark.parametrize("M,N,K", [(70, 90, 200), (300, 257, 1030), (16, 520, 77), (1, 1000, 2048)])
+def test_matmul_u8i8_parity(M, N, K):
+    A, B = wl.gemm_inputs_u8i8(M, N, K, 41, M + K)
+    ref = oracle.matmul_u8i8(A, B)
+    for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 3)]:
+        announce("matmul_u8i8", M, N, K, "tile", tile, "split", split)
+        with forced(tile=tile, split=split):
+            got = run_matmul("u8i8", A, B)
+        assert same(got, ref, f"tile {tile} split {split}")
+
+
+def test_matmul_u8i8_strided_and_extremes():
+    A, B = wl.gemm_inputs_u8i8(130, 75, 160, 41, 7)
+    announce("matmul_u8i8 strided")
+    assert same(run_matmul("u8i8", A, B, lda=176, ldb=192, ldc=80), oracle.matmul_u8i8(A, B))
+    announce("matmul_u8i8 unaligned ld")
+    assert same(run_matmul("u8i8", A, B, lda=161, ldb=163, ldc=75), oracle.matmul_u8i8(A, B))
+    # largest magnitudes at the longest allowed reduction: |sum| = 65793 * 255 * 128 < 2^31
+    K = unit.UNIT_MAX_REDUCTION_U8I8
+    A = np.full((3, K), 255, np.uint8); A[1] = 0; A[2, ::2] = 128
+    B = np.stack([np.full(K, -128, np.int8), np.full(K, 127, np.int8), np.full(K, -1, np.int8)])
+    announce("matmul_u8i8 extremes K", K)
+    assert same(run_matmul("u8i8", A, B), oracle.matmul_u8i8(A, B))
+    A2 = dev(np.zeros((3, K + 1), np.uint8)); B2 = dev(np.zeros((3, K + 1), np.int8))
+    C2 = torch.zeros((3, 3), dtype=torch.int32, device="cuda:0")
+    assert unit.unit_matmul_workspace(3, 3, K + 1, K + 1, K + 1, unit.UNIT_U8I8) == 0
+    with pytest.raises(unit.UnitError) as e:
+        unit.unit_matmul_u8i8(3, 3, K + 1, A2, K + 1, B2, K + 1, C2, 3, ws_bytes(1 << 20))
+    assert e.value.status == unit.UNIT_EOVERFLOW
+
+
+CONV_SMALL = [
+    (wl.conv_shape(20, 13, 24, 3, 1, 1), 2),        # padding on every side, ragged channels
+    (wl.conv_shape(64, 14, 96, 3, 2, 1), 1),        # stride 2
+    (wl.ConvShape(8, 9, 17, 40, 5, 3, 1, 2), 3),    # rectangular window, pad 2
+    (wl.conv_shape(130, 7, 70, 1, 1, 0), 4),        # 1x1
+    (wl.conv_shape(3, 32, 32, 7, 2, 3), 1),         # stem-like
+]
+
+
+@pytest.mark.parametrize("case", range(len(CONV_SMALL)))
+def test_conv_u8i8_parity(case):
+    sh, n = CONV_SMALL[case]
+    x, w = wl.conv_inputs_u8i8(sh, n, 42, case)
+    ref = oracle.conv2d_u8i8(x, w, (sh.stride, sh.stride), (sh.pad, sh.pad))
+    for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 2)]:
+        announce("conv_u8i8", tuple(sh), "n", n, "tile", tile, "split", split)
+        with forced(tile=tile, split=split):
+            got = run_conv("u8i8", sh, n, x, w)
+        assert same(got, ref, f"tile {tile} split {split}")
+
+
+def test_conv_u8i8_saturated_inputs():
+    # all-255 activations against all -128 / +127 filters with zero padding: the border outputs
+    # see fewer taps than the interior ones, so the correction must cancel exactly there too
+    sh = wl.conv_shape(48, 10, 34, 3, 1, 1)
+    x = np.full((2, sh.c, sh.h, sh.w), 255, np.uint8)
+    w = np.full((sh.k, sh.c, 3, 3), -128, np.int8); w[1::2] = 127
+    announce("conv_u8i8 saturated")
+    assert same(run_conv("u8i8", sh, 2, x, w), oracle.conv2d_u8i8(x, w, (1, 1), (1, 1)))
+    x[:] = 0
+    announce("conv_u8i8 zero image")
+    assert not run_conv("u8i8", sh, 2, x, w).any()
+
+
+def test_conv_u8i8_network_layers():
+    """A few ResNet-50-shaped layers in the configuration the selector picks."""
+    layers = wl.unique_shapes(wl.resnet50_convs())
+    for idx in (0, 1, 5, 11, 17, len(layers) - 1):
+        sh = layers[idx][0]
+        x, w = wl.conv_inputs_u8i8(sh, 1, 43, idx)
+        announce("conv_u8i8 r50 layer", idx, tuple(sh))
+        got = run_conv("u8i8", sh, 1, x, w)
+        assert same(got, oracle.conv2d_u8i8(x, w, (sh.stride, sh.stride), (sh.pad, sh.pad)), f"layer {idx}")
+
+
+def test_matmul_u8i8_full_size_sampled():
+    M = N = K = 4096
+    A, B = wl.gemm_inputs_u8i8(M, N, K)
+    announce("matmul_u8i8 4096^3")
+    got = run_matmul("u8i8", A, B)
+    rows = np.array([0, 255, 256, 1000, 4095])
+    assert same(got[rows], oracle.matmul_u8i8(np.ascontiguousarray(A[rows]), B))
+    colsum = B.astype(np.int64).sum(axis=0)
+    assert same(got.astype(np.int64).sum(axis=1), A.astype(np.int64) @ colsum)
+
+
+# ------------------------------------------------------------------ bf16
+
+@pytest.mark.parametrize("M,N,K", [(70, 90, 200), (300, 257, 1030), (16, 520, 77)])
+def test_matmul_bf16_parity(M, N, K):
+    A, B = wl.gemm_inputs_bf16(M, N, K, 44, M + K)
+    ref, truth, mag = oracle.matmul_bf16(A, B)
+    for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 2)]:
+        announce("matmul_bf16", M, N, K, "tile", tile, "split", split)
+        with forced(tile=tile, split=split):
+            got = run_matmul("bf16", A, B)
+        assert f16_rel_err(got, ref, K) <= 1e-3, (tile, split)
+        assert np.all(np.abs(got - truth) <= 2 * K * 2.0 ** -24 * mag + 1e-30), (tile, split)
+
+
+def test_matmul_bf16_exact_and_strided():
+    g = wl.rng(45)
+    Ai = g.integers(-8, 9, size=(70, 200))
+    Bi = g.integers(-8, 9, size=(90, 200))
+    A, B = wl.bf16_bits(Ai.astype(np.float32)), wl.bf16_bits(Bi.astype(np.float32))
+    announce("matmul_bf16 exact ints")
+    assert same(run_matmul("bf16", A, B).astype(np.int64), Ai @ Bi.T)
+    announce("matmul_bf16 strided")
+    assert same(run_matmul("bf16", A, B, lda=208, ldb=216, ldc=96).astype(np.int64), Ai @ Bi.T)
+    # a value binary16 cannot hold: 2^40 * 2^-30 products
+    A = wl.bf16_bits(np.full((16, 64), 2.0 ** 40, np.float32))
+    B = wl.bf16_bits(np.full((16, 64), 2.0 ** -30, np.float32))
+    announce("matmul_bf16 wide exponents")
+    assert np.all(run_matmul("bf16", A, B) == 64 * 2.0 ** 10)
+
+
+@pytest.mark.parametrize("case", range(len(CONV_SMALL)))
+def test_conv_bf16_parity(case):
+    sh, n = CONV_SMALL[case]
+    x, w = wl.conv_inputs_bf16(sh, n, 46, case)
+    ref, truth, mag = oracle.conv2d_bf16(x, w, (sh.stride, sh.stride), (sh.pad, sh.pad))
+    kred = sh.c * sh.r * sh.s
+    for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 2)]:
+        announce("conv_bf16", tuple(sh), "n", n, "tile", tile, "split", split)
+        with forced(tile=tile, split=split):
+            got = run_conv("bf16", sh, n, x, w)
+        assert f16_rel_err(got, ref, kred) <= 1e-3, (tile, split)
+        assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), (tile, split)
+
+
+def test_conv_bf16_direct_1x1():
+    """1x1 stride-1 layers read NCHW directly (channel rows transposed inside the kernel)."""
+    for sh, n in [(wl.conv_shape(256, 14, 64, 1, 1, 0), 1), (wl.conv_shape(72, 8, 40, 1, 1, 0), 3)]:
+        x, w = wl.conv_inputs_bf16(sh, n, 47, sh.c)
+        ref, truth, mag = oracle.conv2d_bf16(x, w, (1, 1), (0, 0))
+        for tile in ALL_TILES:
+            announce("conv_bf16 direct", tuple(sh), "n", n, "tile", tile)
+            with forced(tile=tile, split=1):
+                got = run_conv("bf16", sh, n, x, w)
+            assert f16_rel_err(got, ref, sh.c) <= 1e-3, tile
+            assert np.all(np.abs(got - truth) <= 2 * sh.c * 2.0 ** -24 * mag + 1e-30), tile
+
+
+def test_matmul_bf16_full_size_sampled():
+    M = N = K = 4096
+    A, B = wl.gemm_inputs_bf16(M, N, K)
+    announce("matmul_bf16 4096^3")
+    got = run_matmul("bf16", A, B)
+    rows = np.array([0, 1, 255, 256, 2047, 4095])
+    ref, truth, mag = oracle.matmul_bf16(np.ascontiguousarray(A[rows]), B)
+    assert f16_rel_err(got[rows], ref, K) <= 1e-3
+    assert np.all(np.abs(got[rows] - truth) <= 2 * K * 2.0 ** -24 * mag)
