@@ -72,6 +72,12 @@ def _load():
     L.oracle_matmul_u8i8.argtypes = mm_args
     L.oracle_conv2d_bf16.argtypes = conv_args + [p, p]
     L.oracle_matmul_bf16.argtypes = [i, i, i, p, l, p, l, p, p, p, l]
+    L.oracle_fp8_e4m3_to_float.restype = ctypes.c_float
+    L.oracle_fp8_e4m3_to_float.argtypes = [ctypes.c_uint8]
+    L.oracle_conv2d_fp8.argtypes = conv_args + [p, p]
+    L.oracle_matmul_fp8.argtypes = [i, i, i, p, l, p, l, p, p, p, l]
+    L.oracle_conv2d_fp8.restype = None
+    L.oracle_matmul_fp8.restype = None
     for name in ("oracle_conv2d_u8i8", "oracle_matmul_u8i8", "oracle_conv2d_bf16", "oracle_matmul_bf16"):
         getattr(L, name).restype = None
     for name in ("oracle_conv2d_i8", "oracle_conv2d_f16", "oracle_conv2d_f16_f64",
@@ -310,4 +316,29 @@ def matmul_bf16(A, B):
     C64 = np.empty((M, N), np.float64)
     Ca = np.empty((M, N), np.float64)
     _load().oracle_matmul_bf16(M, N, K, _ptr(A), K, _ptr(B), K, _ptr(C), _ptr(C64), _ptr(Ca), N)
+    return C, C64, Ca
+
+
+def fp8_e4m3_to_float(bits):
+    return float(_load().oracle_fp8_e4m3_to_float(int(bits)))
+
+
+def conv2d_fp8(x, w, stride=(1, 1), pad=(0, 0)):
+    """E4M3 bit patterns (uint8) -> (fp32 result, fp64-accumulated value, sum of |products|)."""
+    _chk(x, np.uint8), _chk(w, np.uint8)
+    dims, oshape = _conv_dims(x, w, stride, pad)
+    y = np.empty(oshape, np.float32)
+    y64 = np.empty(oshape, np.float64)
+    ya = np.empty(oshape, np.float64)
+    _load().oracle_conv2d_fp8(*dims, _ptr(x), _ptr(w), _ptr(y), _ptr(y64), _ptr(ya))
+    return y, y64, ya
+
+
+def matmul_fp8(A, B):
+    _chk(A, np.uint8), _chk(B, np.uint8)
+    M, N, K = _mm_dims(A, B)
+    C = np.empty((M, N), np.float32)
+    C64 = np.empty((M, N), np.float64)
+    Ca = np.empty((M, N), np.float64)
+    _load().oracle_matmul_fp8(M, N, K, _ptr(A), K, _ptr(B), K, _ptr(C), _ptr(C64), _ptr(Ca), N)
     return C, C64, Ca

@@ -521,3 +521,82 @@ void oracle_matmul_bf16(int M, int N, int K,
             if (Cabs) Cabs[(size_t)m * ldc + n] = aacc;
         }
 }
+
+/*
+ * fp8 (OCP E4M3, the finite-only "fn" variant: 1 sign, 4 exponent bits with bias 7,
+ * 3 fraction bits; no infinities; the single NaN pattern per sign is S.1111.111; largest
+ * finite value 448; subnormals are multiples of 2^-9).  Every value is exact in fp32 and so
+ * is every product of two of them.
+ */
+float oracle_fp8_e4m3_to_float(uint8_t b)
+{
+    int sign = (b >> 7) & 1;
+    int expo = (b >> 3) & 0xf;
+    int frac = b & 0x7;
+    float mag;
+    if (expo == 0xf && frac == 0x7) {
+        mag = NAN;
+    } else if (expo == 0) {
+        mag = ldexpf((float)frac, -9);                 /* 0 or subnormal: frac/8 * 2^-6 */
+    } else {
+        mag = ldexpf((float)(8 + frac), expo - 10);    /* (1 + frac/8) * 2^(expo-7) */
+    }
+    return sign ? -mag : mag;
+}
+
+void oracle_conv2d_fp8(int N, int C, int H, int W, int K, int R, int S,
+                       int sh, int sw, int ph, int pw,
+                       const uint8_t *x, const uint8_t *w,
+                       float *y, double *y64, double *yabs)
+{
+    const int P = oracle_out_dim(H, R, sh, ph);
+    const int Q = oracle_out_dim(W, S, sw, pw);
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int n = 0; n < N; ++n)
+        for (int k = 0; k < K; ++k)
+            for (int p = 0; p < P; ++p)
+                for (int q = 0; q < Q; ++q) {
+                    float acc = 0.0f;
+                    double acc64 = 0.0, aacc = 0.0;
+                    for (int c = 0; c < C; ++c)
+                        for (int r = 0; r < R; ++r)
+                            for (int s = 0; s < S; ++s) {
+                                int h  = p * sh + r - ph;
+                                int ww = q * sw + s - pw;
+                                if (h < 0 || h >= H || ww < 0 || ww >= W) continue;
+                                float a = oracle_fp8_e4m3_to_float(x[(((size_t)n * C + c) * H + h) * W + ww]);
+                                float b = oracle_fp8_e4m3_to_float(w[(((size_t)k * C + c) * R + r) * S + s]);
+                                float prod = a * b;
+                                acc = acc + prod;
+                                acc64 += (double)a * (double)b;
+                                aacc  += fabs((double)a * (double)b);
+                            }
+                    size_t o = (((size_t)n * K + k) * P + p) * Q + q;
+                    y[o] = acc;
+                    if (y64)  y64[o]  = acc64;
+                    if (yabs) yabs[o] = aacc;
+                }
+}
+
+void oracle_matmul_fp8(int M, int N, int K,
+                       const uint8_t *A, long lda, const uint8_t *B, long ldb,
+                       float *C, double *C64, double *Cabs, long ldc)
+{
+#pragma omp parallel for schedule(static)
+    for (int m = 0; m < M; ++m)
+        for (int n = 0; n < N; ++n) {
+            float acc = 0.0f;
+            double acc64 = 0.0, aacc = 0.0;
+            for (int k = 0; k < K; ++k) {
+                float a = oracle_fp8_e4m3_to_float(A[(size_t)m * lda + k]);
+                float b = oracle_fp8_e4m3_to_float(B[(size_t)n * ldb + k]);
+                float prod = a * b;
+                acc = acc + prod;
+                acc64 += (double)a * (double)b;
+                aacc  += fabs((double)a * (double)b);
+            }
+            C[(size_t)m * ldc + n] = acc;
+            if (C64)  C64[(size_t)m * ldc + n]  = acc64;
+            if (Cabs) Cabs[(size_t)m * ldc + n] = aacc;
+        }
+}

@@ -76,6 +76,39 @@ def bf16_bits(values):
     return (u >> 16).astype(np.uint16)
 
 
+def _fp8_e4m3_magnitudes():
+    """The 127 finite non-negative E4M3 values in code order (code 0x7F is NaN)."""
+    codes = np.arange(127)
+    expo, frac = codes >> 3, codes & 7
+    return np.where(expo == 0, frac * 2.0 ** -9, (8 + frac) * 2.0 ** (expo - 10.0))
+
+
+def fp8_e4m3_bits(values):
+    """float array -> OCP E4M3 (finite-only) bit patterns: round to nearest, ties to the even
+    code, magnitudes above 448 saturate."""
+    v = np.asarray(values, dtype=np.float64)
+    mags = _fp8_e4m3_magnitudes()
+    a = np.minimum(np.abs(v), mags[-1])
+    hi = np.clip(np.searchsorted(mags, a, side="left"), 1, 126)
+    lo = hi - 1
+    dlo, dhi = a - mags[lo], mags[hi] - a
+    code = np.where(dlo < dhi, lo, np.where(dhi < dlo, hi, np.where(lo % 2 == 0, lo, hi)))
+    return (code | (np.signbit(v).astype(np.int64) << 7)).astype(np.uint8)
+
+
+def conv_inputs_fp8(sh, n, config_id, layer_id=0):
+    g = rng(config_id, layer_id)
+    x = fp8_e4m3_bits(g.standard_normal(size=(n, sh.c, sh.h, sh.w)))
+    w = fp8_e4m3_bits(g.standard_normal(size=(sh.k, sh.c, sh.r, sh.s)) * np.sqrt(2.0 / (sh.c * sh.r * sh.s)))
+    return x, w
+
+
+def gemm_inputs_fp8(m, n, k, config_id=2, layer_id=4):
+    g = rng(config_id, layer_id)
+    return (fp8_e4m3_bits(g.standard_normal(size=(m, k))),
+            fp8_e4m3_bits(g.standard_normal(size=(n, k)) * np.sqrt(2.0 / k)))
+
+
 def conv_inputs_i8(sh, n, config_id, layer_id=0):
     g = rng(config_id, layer_id)
     x = int8_activations(g, (n, sh.c, sh.h, sh.w))

@@ -125,3 +125,68 @@ def test_bf16_general_values():
     for k in range(200):
         acc = np.float32(acc + np.float32(af[k] * bf[k]))
     assert C[0, 0] == acc
+
+
+# ------------------------------------------------------------------ fp8 (E4M3, finite-only)
+
+def test_fp8_decoding_all_patterns():
+    import torch
+    bits = np.arange(256, dtype=np.uint8)
+    lib = torch.from_numpy(bits.copy()).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    for b in range(256):
+        got = oracle.fp8_e4m3_to_float(b)
+        assert (np.isnan(got) and np.isnan(lib[b])) or got == lib[b], b
+    # the format's landmarks
+    assert oracle.fp8_e4m3_to_float(0x7E) == 448.0 and oracle.fp8_e4m3_to_float(0xFE) == -448.0
+    assert oracle.fp8_e4m3_to_float(0x38) == 1.0 and oracle.fp8_e4m3_to_float(0x01) == 2.0 ** -9
+    assert oracle.fp8_e4m3_to_float(0x08) == 2.0 ** -6 and np.isnan(oracle.fp8_e4m3_to_float(0x7F))
+
+
+def test_fp8_generator_rounding():
+    import torch
+    g = np.random.default_rng(35)
+    vals = np.concatenate([g.standard_normal(4000) * 3, g.standard_normal(2000) * 0.01,
+                           [0.0, 448.0, 1000.0, -1000.0, 2.0 ** -10, 3 * 2.0 ** -10, 1.0625, 1.1875]])
+    bits = wl.fp8_e4m3_bits(vals)
+    inside = np.abs(vals) <= 448
+    lib = torch.from_numpy(vals[inside].astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(bits[inside], lib)
+    assert bits[-7] == 0x7E and bits[-6] == 0x7E and bits[-5] == 0xFE     # saturation
+    assert bits[-4] == 0x00 and bits[-3] == 0x02                           # ties to even among subnormals
+    assert bits[-2] == 0x38 and bits[-1] == 0x3A                           # 1.0625 -> 1.0, 1.1875 -> 1.25
+
+
+def test_fp8_integer_valued_inputs_are_exact():
+    g = np.random.default_rng(36)
+    xi = g.integers(-8, 9, size=(2, 6, 7, 7)).astype(np.int8)
+    wi = g.integers(-8, 9, size=(5, 6, 3, 3)).astype(np.int8)
+    y, y64, ya = oracle.conv2d_fp8(wl.fp8_e4m3_bits(xi), wl.fp8_e4m3_bits(wi), (1, 1), (1, 1))
+    ref = oracle.conv2d_i8(xi, wi, (1, 1), (1, 1))
+    assert np.array_equal(y, ref.astype(np.float32)) and np.array_equal(y64, ref.astype(np.float64))
+    assert np.array_equal(ya, oracle.conv2d_i8(np.abs(xi), np.abs(wi), (1, 1), (1, 1)).astype(np.float64))
+    Ai = g.integers(-8, 9, size=(7, 40)).astype(np.int8)
+    Bi = g.integers(-8, 9, size=(5, 40)).astype(np.int8)
+    C, C64, Ca = oracle.matmul_fp8(wl.fp8_e4m3_bits(Ai), wl.fp8_e4m3_bits(Bi))
+    assert np.array_equal(C, oracle.matmul_i8(Ai, Bi).astype(np.float32))
+
+
+def test_fp8_general_values():
+    import torch
+    A, B = wl.gemm_inputs_fp8(6, 5, 200)
+    C, C64, Ca = oracle.matmul_fp8(A, B)
+    Af = torch.from_numpy(A.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    Bf = torch.from_numpy(B.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.allclose(C64, Af @ Bf.T, rtol=1e-12, atol=1e-12)
+    assert np.allclose(Ca, np.abs(Af) @ np.abs(Bf).T, rtol=1e-12, atol=1e-12)
+    assert np.all(np.abs(C - C64) <= 200 * 2.0 ** -24 * Ca)
+    acc = np.float32(0)
+    for k in range(200):
+        acc = np.float32(acc + np.float32(Af[0, k]) * np.float32(Bf[0, k]))
+    assert C[0, 0] == acc
+    sh = wl.conv_shape(10, 8, 6, 3, 2, 1)
+    x, w = wl.conv_inputs_fp8(sh, 2, 9, 2)
+    y, y64, ya = oracle.conv2d_fp8(x, w, (2, 2), (1, 1))
+    xf = torch.from_numpy(x.copy()).view(torch.float8_e4m3fn).to(torch.float64)
+    wf = torch.from_numpy(w.copy()).view(torch.float8_e4m3fn).to(torch.float64)
+    ref = torch.nn.functional.conv2d(xf, wf, stride=2, padding=1).numpy()
+    assert np.allclose(y64, ref, rtol=1e-12, atol=1e-12)
