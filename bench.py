@@ -23,7 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK = {"i8": 5000.0, "u8i8": 5000.0, "f16": 2500.0, "bf16": 2500.0}        # dense MFMA TOPS / TFLOPS (published MI355X)
+PEAK = {"i8": 5000.0, "u8i8": 5000.0, "f16": 2500.0, "bf16": 2500.0, "fp8": 5000.0}        # dense MFMA TOPS / TFLOPS (published MI355X)
 HBM_GBS = 8000.0
 # HBM-side bytes per launch (per step for the layer set) of the main kernel, from the committed
 # rocprofv3 counter runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy in the
@@ -103,12 +103,13 @@ class GemmCase:
         "f16": ("gemm_inputs_f16", np.int16, 2, "UNIT_F16", "unit_matmul_f16"),
         "bf16": ("gemm_inputs_bf16", np.int16, 2, "UNIT_BF16", "unit_matmul_bf16"),
         "u8i8": ("gemm_inputs_u8i8", None, 1, "UNIT_U8I8", "unit_matmul_u8i8"),
+        "fp8": ("gemm_inputs_fp8", None, 1, "UNIT_FP8", "unit_matmul_fp8"),
     }
 
     def __init__(self, torch, unit, wl, m, n, k, dtype):
         dev = "cuda:0"
         gen, view, es, ut, fn = self._KINDS[dtype]
-        integer = es == 1
+        integer = dtype in ("i8", "u8i8")
         self.unit, self.dtype, self.m, self.n, self.k = unit, dtype, m, n, k
         A, B = getattr(wl, gen)(m, n, k)
         self.A = torch.from_numpy(A.view(view) if view else A).to(dev)
@@ -456,7 +457,7 @@ def main():
             add("large conv N=32 C=K=256 56x56 3x3, pack_act + conv", dtype, c.macs, c.bytes, event_ms(torch, c.api, 20), c.info)
             del c
             torch.cuda.empty_cache()
-        for dtype in ("u8i8", "bf16"):      # further operand types through the same kernel
+        for dtype in ("u8i8", "bf16", "fp8"):      # further operand types through the same kernel
             g = GemmCase(torch, unit, wl, 4096, 4096, 4096, dtype)
             add("gemm 4096^3", dtype, g.macs, g.bytes, event_ms(torch, g.run, 30), g.info)
             del g

@@ -41,8 +41,8 @@ enum unit_status {
 
 /* Operand types: i8 x i8 -> i32, f16 x f16 -> f32, bf16 x bf16 -> f32, u8 x i8 -> i32
  * (unsigned activations / matmul A, signed weights / matmul B: the operand types of the
- * byte dot-product instruction of Section III-A). */
-enum unit_dtype { UNIT_I8 = 0, UNIT_F16 = 1, UNIT_BF16 = 2, UNIT_U8I8 = 3 };
+ * byte dot-product instruction of Section III-A), fp8 x fp8 -> f32 (OCP E4M3, finite-only). */
+enum unit_dtype { UNIT_I8 = 0, UNIT_F16 = 1, UNIT_BF16 = 2, UNIT_U8I8 = 3, UNIT_FP8 = 4 };
 
 /* Longest int8 reduction (c*r*s, or k for matmul) with |sum| <= len * 2^14 < 2^31. */
 #define UNIT_MAX_REDUCTION_I8 131071
@@ -231,13 +231,15 @@ int unit_widen_residual_i8(int32_t n, int32_t c, int32_t h, int32_t w,
  * Further operand types through the same kernels (Section I and Section III-A: the method is
  * meant to extend to other mixed-precision operand types; Section III-A's byte instruction
  * multiplies unsigned by signed bytes).  Same tensor conventions, workspace rules (query with
- * UNIT_BF16 / UNIT_U8I8) and error behaviour as unit_conv2d_f16 / unit_matmul_f16 and
+ * UNIT_BF16 / UNIT_U8I8 / UNIT_FP8) and error behaviour as unit_conv2d_f16 / unit_matmul_f16 and
  * unit_conv2d_i8 / unit_matmul_i8 without the requantise epilogue.
  *   bf16: uint16_t bfloat16 bit patterns, fp32 accumulation and output.
  *   u8i8: x / A unsigned bytes, w / B signed bytes, exact int32 output; reduction length at
  *         most UNIT_MAX_REDUCTION_U8I8 (UNIT_EOVERFLOW beyond).  The matrix unit multiplies
  *         signed bytes: the unsigned operand is fed as u - 128 and 128 * (sum of the signed
  *         operand over the reduction) is added back in the epilogue, which is exact.
+ *   fp8:  uint8_t OCP E4M3 bit patterns (1 sign, 4 exponent bits with bias 7, 3 fraction bits,
+ *         no infinities, NaN = S.1111.111), fp32 accumulation and output, no block scaling.
  */
 int unit_conv2d_bf16(const unit_conv2d_desc *d, const uint16_t *x, const uint16_t *w,
                      float *y, void *ws, size_t ws_bytes, void *stream);
@@ -246,6 +248,11 @@ int unit_matmul_bf16(int32_t m, int32_t n, int32_t k, const uint16_t *A, int64_t
                      void *ws, size_t ws_bytes, void *stream);
 int unit_conv2d_u8i8(const unit_conv2d_desc *d, const uint8_t *x, const int8_t *w,
                      int32_t *y, void *ws, size_t ws_bytes, void *stream);
+int unit_conv2d_fp8(const unit_conv2d_desc *d, const uint8_t *x, const uint8_t *w,
+                    float *y, void *ws, size_t ws_bytes, void *stream);
+int unit_matmul_fp8(int32_t m, int32_t n, int32_t k, const uint8_t *A, int64_t lda,
+                    const uint8_t *B, int64_t ldb, float *C, int64_t ldc,
+                    void *ws, size_t ws_bytes, void *stream);
 int unit_matmul_u8i8(int32_t m, int32_t n, int32_t k, const uint8_t *A, int64_t lda,
                      const int8_t *B, int64_t ldb, int32_t *C, int64_t ldc,
                      void *ws, size_t ws_bytes, void *stream);

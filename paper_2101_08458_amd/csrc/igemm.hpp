@@ -20,6 +20,7 @@
 namespace unit {
 
 typedef int      v4i  __attribute__((ext_vector_type(4)));
+typedef int      v8i  __attribute__((ext_vector_type(8)));
 typedef int      v16i __attribute__((ext_vector_type(16)));
 typedef float    v4f  __attribute__((ext_vector_type(4)));
 typedef float    v16f __attribute__((ext_vector_type(16)));
@@ -33,7 +34,8 @@ typedef __bf16   v8bf __attribute__((ext_vector_type(8)));
 // the B side (correction per output row).  Bytes the hardware zero-fills (reduction tail,
 // conv padding) become -128 the same way; the other operand is zero on the tail, and for
 // conv padding the correction sums every tap, so both cancel exactly.
-enum { DT_I8 = 0, DT_F16 = 1, DT_BF16 = 2, DT_U8A = 3, DT_U8B = 4 };
+// DT_FP8 (OCP E4M3) uses the 32-byte-per-lane MFMAs: its fragments are two 16-byte chunks wide.
+enum { DT_I8 = 0, DT_F16 = 1, DT_BF16 = 2, DT_U8A = 3, DT_U8B = 4, DT_FP8 = 5 };
 enum { EPI_RAW = 0, EPI_REQUANT = 1 };
 // where the B operand (columns) comes from: a plain matrix, the packed-NHWC conv gather, or
 // an NCHW tensor read directly (1x1 stride-1 convs of one image: channel rows of pixels,
@@ -76,38 +78,70 @@ __device__ __forceinline__ int requant_elem(int t, float scale, int relu)
 
 template <int DT, int MF> struct Mma;
 template <> struct Mma<DT_I8, 32> {
-    typedef v16i acc_t;  typedef int elem_t;  enum { NACC = 16 };
+    typedef v16i acc_t;  typedef int elem_t;  typedef v4i frag_t;  enum { NACC = 16, FW = 1 };
     static __device__ __forceinline__ void run(acc_t &c, const v4i &a, const v4i &b)
     { c = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
 };
 template <> struct Mma<DT_I8, 16> {
-    typedef v4i acc_t;  typedef int elem_t;  enum { NACC = 4 };
+    typedef v4i acc_t;  typedef int elem_t;  typedef v4i frag_t;  enum { NACC = 4, FW = 1 };
     static __device__ __forceinline__ void run(acc_t &c, const v4i &a, const v4i &b)
     { c = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0); }
 };
 template <> struct Mma<DT_F16, 32> {
-    typedef v16f acc_t;  typedef float elem_t;  enum { NACC = 16 };
+    typedef v16f acc_t;  typedef float elem_t;  typedef v4i frag_t;  enum { NACC = 16, FW = 1 };
     static __device__ __forceinline__ void run(acc_t &c, const v4i &a, const v4i &b)
     { c = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0); }
 };
 template <> struct Mma<DT_F16, 16> {
-    typedef v4f acc_t;  typedef float elem_t;  enum { NACC = 4 };
+    typedef v4f acc_t;  typedef float elem_t;  typedef v4i frag_t;  enum { NACC = 4, FW = 1 };
     static __device__ __forceinline__ void run(acc_t &c, const v4i &a, const v4i &b)
     { c = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0); }
 };
 
 template <> struct Mma<DT_BF16, 32> {
-    typedef v16f acc_t;  typedef float elem_t;  enum { NACC = 16 };
+    typedef v16f acc_t;  typedef float elem_t;  typedef v4i frag_t;  enum { NACC = 16, FW = 1 };
     static __device__ __forceinline__ void run(acc_t &c, const v4i &a, const v4i &b)
     { c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0); }
 };
 template <> struct Mma<DT_BF16, 16> {
-    typedef v4f acc_t;  typedef float elem_t;  enum { NACC = 4 };
+    typedef v4f acc_t;  typedef float elem_t;  typedef v4i frag_t;  enum { NACC = 4, FW = 1 };
     static __device__ __forceinline__ void run(acc_t &c, const v4i &a, const v4i &b)
     { c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0); }
 };
+// fp8: each lane feeds 32 operand bytes; format selectors 0 = E4M3 for both operands, block
+// scales zero = the unscaled form of the instruction
+template <> struct Mma<DT_FP8, 32> {
+    typedef v16f acc_t;  typedef float elem_t;  typedef v8i frag_t;  enum { NACC = 16, FW = 2 };
+    static __device__ __forceinline__ void run(acc_t &c, const v8i &a, const v8i &b)
+    { c = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0); }
+};
+template <> struct Mma<DT_FP8, 16> {
+    typedef v4f acc_t;  typedef float elem_t;  typedef v8i frag_t;  enum { NACC = 4, FW = 2 };
+    static __device__ __forceinline__ void run(acc_t &c, const v8i &a, const v8i &b)
+    { c = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0); }
+};
 template <int MF> struct Mma<DT_U8A, MF> : Mma<DT_I8, MF> {};
 template <int MF> struct Mma<DT_U8B, MF> : Mma<DT_I8, MF> {};
+
+// A fragment of FW 16-byte chunks: consecutive logical chunks ch .. ch+FW-1 of one LDS row
+// (the swizzle is applied per chunk), or FW*4 assembled words.
+template <int FW> struct Frag;
+template <> struct Frag<1> {
+    static __device__ __forceinline__ v4i load(const uint8_t *row, int ch, int sw)
+    { return *reinterpret_cast<const v4i *>(row + ((ch ^ sw) << 4)); }
+    static __device__ __forceinline__ v4i pack(const unsigned *w)
+    { return v4i{(int)w[0], (int)w[1], (int)w[2], (int)w[3]}; }
+};
+template <> struct Frag<2> {
+    static __device__ __forceinline__ v8i load(const uint8_t *row, int ch, int sw)
+    {
+        v4i lo = *reinterpret_cast<const v4i *>(row + ((ch ^ sw) << 4));
+        v4i hi = *reinterpret_cast<const v4i *>(row + (((ch + 1) ^ sw) << 4));
+        return __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    }
+    static __device__ __forceinline__ v8i pack(const unsigned *w)
+    { return v8i{(int)w[0], (int)w[1], (int)w[2], (int)w[3], (int)w[4], (int)w[5], (int)w[6], (int)w[7]}; }
+};
 
 // Row of accumulator element e held by `lane` inside one MFMA tile (column is lane % MF).
 template <int MF> __device__ __forceinline__ int acc_row(int e, int lane)
@@ -163,7 +197,8 @@ struct IgemmCfg {
         NCH   = BKB / 16,                          // 16-byte chunks per row per step
         WTM   = BM / WGM,  WTN = BN / WGN,
         TM    = WTM / MF,  TN  = WTN / MF,
-        KSUBB = (MF == 32) ? 32 : 64,              // reduction bytes per MFMA
+        FW    = (DT == DT_FP8) ? 2 : 1,            // 16-byte chunks per lane and operand
+        KSUBB = ((MF == 32) ? 32 : 64) * FW,       // reduction bytes per MFMA
         NKSUB = BKB / KSUBB,
         CPL   = KSUBB / 16,                        // 16-byte chunks per MFMA along k
         RPI   = 1024 / BKB,                        // tile rows filled by one wave-level DMA
@@ -191,6 +226,8 @@ igemm_kernel(const IgemmArgs g)
     typedef Mma<DT, MF> M;
     typedef typename M::acc_t acc_t;
     typedef typename M::elem_t elem_t;
+    typedef typename M::frag_t frag_t;
+    constexpr int FW = M::FW;
     constexpr int NW = C::NW, NCH = C::NCH, TM = C::TM, TN = C::TN, IA = C::IA, IB = C::IB, RPI = C::RPI;
     constexpr bool CONV = (BSRC != BSRC_PLAIN);     // conv-style output indexing
     constexpr int ES = (DT == DT_F16 || DT == DT_BF16) ? 2 : 1;   // operand element bytes
@@ -341,7 +378,7 @@ igemm_kernel(const IgemmArgs g)
 
     // ---- fragment addressing (lane -> row inside an MFMA tile, 16-byte chunk along k)
     const int lrow   = lane % MF;
-    const int lchunk = lane / MF;                   // 0..CPL-1
+    const int lchunk = (lane / MF) * FW;            // first of this lane's FW chunks inside one MFMA
     const int a_row  = wm * C::WTM + lrow;
     const int b_row  = wn * C::WTN + lrow;
     const int a_swz  = swz<NCH>(a_row);             // unchanged by +MF*i (multiples of 16)
@@ -363,14 +400,14 @@ igemm_kernel(const IgemmArgs g)
     // tile NST steps ahead and the first fragments of the next tile are read, so those
     // MFMAs cover barrier skew and LDS latency.
     constexpr int NS = C::NKSUB / WGK;              // sub-steps per wave per step
-    v4i fa[2][TM], fb[2][TN];
+    frag_t fa[2][TM], fb[2][TN];
     auto read_frags = [&](int stage, int sub, int slot) {
         const uint8_t *sA = smem + stage * C::STAGE_BYTES;
         const uint8_t *sB = sA + BM * BKB;
         const int ch = (sub * WGK + wk) * C::CPL + lchunk;
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            fa[slot][i] = *reinterpret_cast<const v4i *>(sA + (a_row + i * MF) * BKB + ((ch ^ a_swz) << 4));
+            fa[slot][i] = Frag<FW>::load(sA + (a_row + i * MF) * BKB, ch, a_swz);
         if (DT == DT_U8A) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) fa[slot][i] ^= (int)0x80808080;
@@ -378,29 +415,32 @@ igemm_kernel(const IgemmArgs g)
         if (BSRC == BSRC_NCHW) {
             // B tile is [channel][pixel]: gather this lane's 16 bytes of consecutive channels
             // for its pixel column, one element per LDS read
-            const int k0 = ch * EPC;                 // first channel row of this lane's chunk
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
-                const uint8_t *src = sB + k0 * (BN * ES) + (b_row + j * MF) * ES;
-                unsigned w[4];
+                unsigned w[4 * FW];
 #pragma unroll
-                for (int d = 0; d < 4; ++d) {
-                    if (ES == 1) {
-                        unsigned b0 = src[(4 * d + 0) * BN], b1 = src[(4 * d + 1) * BN];
-                        unsigned b2 = src[(4 * d + 2) * BN], b3 = src[(4 * d + 3) * BN];
-                        w[d] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
-                    } else {
-                        unsigned h0 = *reinterpret_cast<const uint16_t *>(src + (2 * d + 0) * BN * 2);
-                        unsigned h1 = *reinterpret_cast<const uint16_t *>(src + (2 * d + 1) * BN * 2);
-                        w[d] = h0 | (h1 << 16);
+                for (int f = 0; f < FW; ++f) {
+                    // first channel row of chunk ch + f
+                    const uint8_t *src = sB + (ch + f) * EPC * (BN * ES) + (b_row + j * MF) * ES;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        if (ES == 1) {
+                            unsigned b0 = src[(4 * d + 0) * BN], b1 = src[(4 * d + 1) * BN];
+                            unsigned b2 = src[(4 * d + 2) * BN], b3 = src[(4 * d + 3) * BN];
+                            w[4 * f + d] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+                        } else {
+                            unsigned h0 = *reinterpret_cast<const uint16_t *>(src + (2 * d + 0) * BN * 2);
+                            unsigned h1 = *reinterpret_cast<const uint16_t *>(src + (2 * d + 1) * BN * 2);
+                            w[4 * f + d] = h0 | (h1 << 16);
+                        }
                     }
                 }
-                fb[slot][j] = v4i{(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+                fb[slot][j] = Frag<FW>::pack(w);
             }
         } else {
 #pragma unroll
             for (int j = 0; j < TN; ++j)
-                fb[slot][j] = *reinterpret_cast<const v4i *>(sB + (b_row + j * MF) * BKB + ((ch ^ b_swz) << 4));
+                fb[slot][j] = Frag<FW>::load(sB + (b_row + j * MF) * BKB, ch, b_swz);
         }
         if (DT == DT_U8B) {
 #pragma unroll
@@ -443,10 +483,10 @@ igemm_kernel(const IgemmArgs g)
                     for (int j = 0; j < TN; ++j)
                         M::run(acc[i][j], fa[slot][i], fb[slot][j]);
                 {
-                    constexpr int NMEM = TM + TN + C::LPT;       // upper bound: reads + DMAs
+                    constexpr int NMEM = (TM + TN) * FW + C::LPT;   // upper bound: reads + DMAs
                     constexpr int PER  = (TM * TN / NMEM) > 0 ? (TM * TN / NMEM) : 1;
 #pragma unroll
-                    for (int r = 0; r < TM + TN; ++r) {
+                    for (int r = 0; r < (TM + TN) * FW; ++r) {
                         __builtin_amdgcn_sched_group_barrier(0x008, PER, 0);   // MFMA
                         __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // LDS read
                     }

@@ -208,6 +208,8 @@ __global__ void zero_pad_channels_kernel(int8_t *yp, int K, int ld, long pixels)
 
 hipError_t launch_splitk_reduce(const ReduceArgs &a, hipStream_t st)
 {
+    // the requantise epilogue derives the channel from the element index
+    if (a.total <= 0 || a.nsplit < 1 || (a.epi == EPI_REQUANT && (a.K <= 0 || a.PQ <= 0))) return hipErrorInvalidValue;
     dim3 grid((unsigned)((a.total + 1023) / 1024)), block(256);
     if (a.dtype == DT_I8) hipLaunchKernelGGL(splitk_reduce_kernel<int>, grid, block, 0, st, a);
     else                  hipLaunchKernelGGL(splitk_reduce_kernel<float>, grid, block, 0, st, a);

@@ -14,6 +14,9 @@ namespace unit {
 const TileCfg g_tiles[NUM_TILES] = {
 #include "tiles.def"
 };
+const TileCfg g_tiles_fp8[NUM_TILES] = {
+#include "tiles_fp8.def"
+};
 #undef UNIT_TILE_CASE
 
 static int env_int(const char *name, int dflt)

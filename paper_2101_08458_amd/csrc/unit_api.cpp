@@ -11,6 +11,7 @@ hipError_t launch_igemm_i8(int bsrc, int tile, const IgemmArgs &a, int split_k, 
 hipError_t launch_igemm_f16(int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
 hipError_t launch_igemm_bf16(int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
 hipError_t launch_igemm_u8(int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
+hipError_t launch_igemm_fp8(int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
 
 // dtype is the public unit_dtype
 hipError_t launch_igemm(int dtype, int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st)
@@ -20,6 +21,7 @@ hipError_t launch_igemm(int dtype, int bsrc, int tile, const IgemmArgs &a, int s
     case UNIT_F16:  return launch_igemm_f16(bsrc, tile, a, split_k, st);
     case UNIT_BF16: return launch_igemm_bf16(bsrc, tile, a, split_k, st);
     case UNIT_U8I8: return bsrc == BSRC_NCHW ? hipErrorInvalidValue : launch_igemm_u8(bsrc, tile, a, split_k, st);
+    case UNIT_FP8:  return launch_igemm_fp8(bsrc, tile, a, split_k, st);
     default:        return hipErrorInvalidValue;
     }
 }
@@ -60,12 +62,11 @@ int hip_fail(hipError_t e)
 #define UNIT_HIP(call) do { hipError_t e_ = (call); if (e_ != hipSuccess) return hip_fail(e_); } while (0)
 
 inline size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
-inline bool dtype_ok(int dtype) { return dtype >= UNIT_I8 && dtype <= UNIT_U8I8; }
-inline bool byte_type(int dtype) { return dtype == UNIT_I8 || dtype == UNIT_U8I8; }
-inline int elem_size(int dtype) { return byte_type(dtype) ? 1 : 2; }
-// what the layout kernels and the split reduce need to know: one- or two-byte elements,
-// integer or float sums
-inline int storage_dtype(int dtype) { return byte_type(dtype) ? DT_I8 : DT_F16; }
+inline bool dtype_ok(int dtype) { return dtype >= UNIT_I8 && dtype <= UNIT_FP8; }
+inline bool byte_type(int dtype) { return dtype == UNIT_I8 || dtype == UNIT_U8I8; }   // integer sums
+inline int elem_size(int dtype) { return (byte_type(dtype) || dtype == UNIT_FP8) ? 1 : 2; }
+// what the layout kernels need to know: one- or two-byte elements
+inline int storage_dtype(int dtype) { return elem_size(dtype) == 1 ? DT_I8 : DT_F16; }
 inline long max_reduction(int dtype)
 {
     return dtype == UNIT_I8 ? UNIT_MAX_REDUCTION_I8 : dtype == UNIT_U8I8 ? UNIT_MAX_REDUCTION_U8I8 : 0x7fffffffL;
@@ -118,9 +119,9 @@ int conv_geom(const ConvND *d, int dtype, ConvGeom *g)
     return UNIT_OK;
 }
 
-void fill_tile_info(const TileChoice &ch, unit_tile_info *out)
+void fill_tile_info(const TileChoice &ch, int dtype, unit_tile_info *out)
 {
-    const TileCfg &c = g_tiles[ch.tile];
+    const TileCfg &c = (dtype == UNIT_FP8 ? g_tiles_fp8 : g_tiles)[ch.tile];
     out->block_m = c.bm;  out->block_n = c.bn;  out->block_k_bytes = c.bkb;
     out->waves_m = c.wgm; out->waves_n = c.wgn; out->waves_k = c.wgk;
     out->mfma = c.mf;     out->split_k = ch.split_k;  out->workgroups = ch.workgroups;
@@ -153,7 +154,8 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
     ReduceArgs r;
     std::memset(&r, 0, sizeof r);
     r.partials = ws;  r.nsplit = ch.split_k;  r.split_stride = slice;
-    r.dtype = storage_dtype(dtype);  r.total = out_elems;  r.K = K;  r.PQ = PQ;
+    r.dtype = byte_type(dtype) ? DT_I8 : DT_F16;               // integer or float sums
+    r.total = out_elems;  r.K = K;  r.PQ = PQ;
     r.out = (a.epi == EPI_RAW || a.store_raw) ? a.out : nullptr;
     r.epi = a.epi;  r.scale = a.scale;  r.bias = a.bias;  r.residual = a.residual;  r.relu = a.relu;
     r.out_i8 = a.out_i8;  r.out_packed = a.out_packed;  r.packed_ld = a.packed_ld;
@@ -451,7 +453,7 @@ int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out
     int rc = conv_geom(&nd, dtype, &g);
     if (rc != UNIT_OK) return rc;
     if (!out) return UNIT_EINVAL;
-    fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true), out);
+    fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true), dtype, out);
     return UNIT_OK;
 }
 
@@ -461,7 +463,7 @@ int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_inf
     int rc = matmul_geom(m, n, k, k, k, dtype, &g);
     if (rc != UNIT_OK) return rc;
     if (!out) return UNIT_EINVAL;
-    fill_tile_info(select_tile(m, n, g.kchunks, dtype, false), out);
+    fill_tile_info(select_tile(m, n, g.kchunks, dtype, false), dtype, out);
     return UNIT_OK;
 }
 
@@ -506,6 +508,20 @@ int unit_matmul_bf16(int32_t m, int32_t n, int32_t k, const uint16_t *A, int64_t
                      void *ws, size_t ws_bytes, void *stream)
 {
     return matmul_any(UNIT_BF16, m, n, k, A, lda, B, ldb, C, ldc, ws, ws_bytes, stream);
+}
+
+int unit_conv2d_fp8(const unit_conv2d_desc *d, const uint8_t *x, const uint8_t *w,
+                    float *y, void *ws, size_t ws_bytes, void *stream)
+{
+    ConvND nd(d);
+    return conv_plain(&nd, UNIT_FP8, x, w, y, nullptr, nullptr, ws, ws_bytes, stream);
+}
+
+int unit_matmul_fp8(int32_t m, int32_t n, int32_t k, const uint8_t *A, int64_t lda,
+                    const uint8_t *B, int64_t ldb, float *C, int64_t ldc,
+                    void *ws, size_t ws_bytes, void *stream)
+{
+    return matmul_any(UNIT_FP8, m, n, k, A, lda, B, ldb, C, ldc, ws, ws_bytes, stream);
 }
 
 int unit_conv2d_u8i8(const unit_conv2d_desc *d, const uint8_t *x, const int8_t *w,

@@ -19,6 +19,7 @@ struct TileCfg {
 };
 enum { NUM_TILES = 6 };
 extern const TileCfg g_tiles[NUM_TILES];
+extern const TileCfg g_tiles_fp8[NUM_TILES];   // same tiles, wave grids of the fp8 kernels
 
 struct TileChoice {
     int tile;                 // index into g_tiles

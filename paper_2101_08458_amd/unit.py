@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libunit.so")
 
 UNIT_OK, UNIT_EINVAL, UNIT_ENOTSUP, UNIT_EOVERFLOW, UNIT_EWORKSPACE, UNIT_EHIP = 0, -1, -2, -3, -4, -5
-UNIT_I8, UNIT_F16, UNIT_BF16, UNIT_U8I8 = 0, 1, 2, 3
+UNIT_I8, UNIT_F16, UNIT_BF16, UNIT_U8I8, UNIT_FP8 = 0, 1, 2, 3, 4
 UNIT_MAX_REDUCTION_I8 = 131071
 UNIT_MAX_REDUCTION_U8I8 = 65793
 
@@ -73,6 +73,7 @@ EXPORTS = [
     "unit_conv2d_wpacked_workspace", "unit_conv2d_wpacked_i8", "unit_conv2d_wpacked_f16",
     "unit_conv3d_out_dims", "unit_conv3d_workspace", "unit_conv3d_i8", "unit_conv3d_f16",
     "unit_conv2d_bf16", "unit_matmul_bf16", "unit_conv2d_u8i8", "unit_matmul_u8i8",
+    "unit_conv2d_fp8", "unit_matmul_fp8",
     "unit_inspect", "unit_describe_mfma", "unit_describe_conv2d", "unit_describe_matmul",
 ]
 
@@ -127,6 +128,8 @@ def load():
         "unit_widen_residual_i8": (ctypes.c_int, [i32, i32, i32, i32, vp, i32, vp, vp]),
         "unit_conv2d_bf16": (ctypes.c_int, [dp, vp, vp, vp, vp, sz, vp]),
         "unit_conv2d_u8i8": (ctypes.c_int, [dp, vp, vp, vp, vp, sz, vp]),
+        "unit_conv2d_fp8": (ctypes.c_int, [dp, vp, vp, vp, vp, sz, vp]),
+        "unit_matmul_fp8": (ctypes.c_int, [i32, i32, i32, vp, i64, vp, i64, vp, i64, vp, sz, vp]),
         "unit_matmul_bf16": (ctypes.c_int, [i32, i32, i32, vp, i64, vp, i64, vp, i64, vp, sz, vp]),
         "unit_matmul_u8i8": (ctypes.c_int, [i32, i32, i32, vp, i64, vp, i64, vp, i64, vp, sz, vp]),
         "unit_inspect": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_char_p, ctypes.POINTER(unit_inspect_result)]),
@@ -368,6 +371,14 @@ def unit_conv2d_bf16(d, x, w, y, ws, stream=None):
 
 def unit_conv2d_u8i8(d, x, w, y, ws, stream=None):
     _conv_simple("unit_conv2d_u8i8", d, x, w, y, ws, stream)
+
+
+def unit_conv2d_fp8(d, x, w, y, ws, stream=None):
+    _conv_simple("unit_conv2d_fp8", d, x, w, y, ws, stream)
+
+
+def unit_matmul_fp8(m, n, k, A, lda, B, ldb, C, ldc, ws=None, stream=None):
+    _matmul_simple("unit_matmul_fp8", m, n, k, A, lda, B, ldb, C, ldc, ws, stream)
 
 
 def unit_matmul_bf16(m, n, k, A, lda, B, ldb, C, ldc, ws=None, stream=None):
