@@ -380,7 +380,8 @@ def main():
             t_api += mult * ta
             per_layer.append({"shape": list(sh), "x": mult, "api_us": round(ta * 1e3, 2),
                               "conv_us": round(tc * 1e3, 2), "pack_us": round(tp * 1e3, 2),
-                              "tile": tile_str(c.info)})
+                              "tile": tile_str(c.info),
+                              "input": ("packed", "direct", "direct-shifted")[unit.unit_conv2d_input_mode(c.d, c.ut, c.x)]})
         return ms, ms_eager, macs, t_conv, t_pack, byts, per_layer, t_api
 
     wlname = args.workload
@@ -404,7 +405,8 @@ def main():
             "config": {"workload": f"53 conv layers of a ResNet-50-shaped network, batch {n}, "
                                    f"{'int8->int32' if dtype == 'i8' else 'fp16->fp32'}, NCHW in -> NCHW out per layer "
                                    "(one unit_conv2d_wpacked call: pack_act + implicit-GEMM conv [+ split reduce], or the "
-                                   "fused NCHW-direct kernel for 1x1/stride-1 layers at batch 1), weights pre-packed",
+                                   "kernel reading NCHW directly where the shape allows it: see per_layer.input), "
+                                   "weights pre-packed",
                        "layers": 53, "batch": n, "gmacs_per_step": round(macs / 1e9, 3)},
             "launch": "one HIP graph per step (all kernels of the 53 layers), replayed",
             "eager_ms_per_step": round(ms_eager, 4),

@@ -113,6 +113,21 @@ size_t unit_matmul_workspace(int32_t m, int32_t n, int32_t k, int64_t lda, int64
 int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out);
 int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_info *out);
 
+/*
+ * How unit_conv2d_wpacked_* (and unit_conv2d_*) will read the NCHW activations `x` of this
+ * problem when no requantise epilogue is requested (introspection / reports; nothing is launched):
+ *   UNIT_INPUT_PACKED          pack_act into the workspace, then the gather kernel
+ *   UNIT_INPUT_DIRECT          1x1 stride-1 unpadded conv with aligned channel rows: the main
+ *                              kernel reads NCHW itself (no pack_act launch)
+ *   UNIT_INPUT_DIRECT_SHIFTED  one image, stride 1, output grid equal to the input grid ("same"
+ *                              padding, any window), whole reduction steps inside one tap: the main
+ *                              kernel reads per-tap shifted windows of the NCHW channel rows, any
+ *                              row alignment (no pack_act launch)
+ * Returns the mode (>= 0) or a negative unit_status.
+ */
+enum unit_input_mode { UNIT_INPUT_PACKED = 0, UNIT_INPUT_DIRECT = 1, UNIT_INPUT_DIRECT_SHIFTED = 2 };
+int unit_conv2d_input_mode(const unit_conv2d_desc *d, int dtype, const void *x);
+
 /* ------------------------------------------------------------------ plain-layout calls */
 
 /*

@@ -39,8 +39,14 @@ enum { DT_I8 = 0, DT_F16 = 1, DT_BF16 = 2, DT_U8A = 3, DT_U8B = 4, DT_FP8 = 5 };
 enum { EPI_RAW = 0, EPI_REQUANT = 1 };
 // where the B operand (columns) comes from: a plain matrix, the packed-NHWC conv gather, or
 // an NCHW tensor read directly (1x1 stride-1 convs of one image: channel rows of pixels,
-// transposed on the way from LDS into the fragments)
-enum { BSRC_PLAIN = 0, BSRC_GATHER = 1, BSRC_NCHW = 2 };
+// transposed on the way from LDS into the fragments).  BSRC_NCHWS is the general form of the
+// direct read for one image and stride 1 with "same" padding: output pixel m of the flattened
+// image needs input pixel m + delta(tap) of every channel, so the B tile of a step is a window of
+// each channel row shifted by the tap's delta.  The window is fetched from the enclosing 16-byte
+// grid of the tensor (so rows need no alignment), held at twice the tile width, and the byte
+// shift (0..15, per channel row) is applied when the fragments are gathered; pixels whose tap
+// falls into the padding are masked there.
+enum { BSRC_PLAIN = 0, BSRC_GATHER = 1, BSRC_NCHW = 2, BSRC_NCHWS = 3 };
 
 struct IgemmArgs {
     // operands (byte pointers; every row starts 16-byte aligned, reduction zero padded to 16 B)
@@ -189,9 +195,10 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t r, uint8_t *lds, un
 // workgroup barrier that the compiler may not move LDS traffic across
 #define UNIT_BARRIER() do { asm volatile("" ::: "memory"); __builtin_amdgcn_s_barrier(); asm volatile("" ::: "memory"); } while (0)
 
-template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, int NST>
+template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, int NST, int BSRC = BSRC_PLAIN>
 struct IgemmCfg {
     enum {
+        BMUL  = (BSRC == BSRC_NCHWS) ? 2 : 1,      // the shifted direct read holds B at twice the tile width
         NW    = WGM * WGN * WGK,                   // waves per workgroup
         NT    = NW * 64,
         NCH   = BKB / 16,                          // 16-byte chunks per row per step
@@ -203,26 +210,27 @@ struct IgemmCfg {
         CPL   = KSUBB / 16,                        // 16-byte chunks per MFMA along k
         RPI   = 1024 / BKB,                        // tile rows filled by one wave-level DMA
         IA    = BM / RPI / NW,                     // DMA instructions per wave per step, A tile
-        IB    = BN / RPI / NW,
+        IB    = BN / RPI / NW * BMUL,
         LPT   = IA + IB,
-        STAGE_BYTES  = (BM + BN) * BKB,
+        STAGE_BYTES  = (BM + BN * BMUL) * BKB,
         REDUCE_BYTES = (WGK - 1) * BM * BN * 4,
         SMEM_BYTES   = (NST * STAGE_BYTES > REDUCE_BYTES) ? NST * STAGE_BYTES : REDUCE_BYTES,
+        FITS  = (SMEM_BYTES <= 160 * 1024) && ((NST - 1) * LPT <= 63),   // LDS capacity, vmcnt range
     };
     static_assert(BM % (WGM * MF) == 0 && BN % (WGN * MF) == 0, "wave tiles must be whole MFMA tiles");
     static_assert(NKSUB % WGK == 0 && NKSUB >= WGK, "in-group split must divide the sub-steps");
     static_assert(BKB % KSUBB == 0 && 1024 % BKB == 0, "step must be whole MFMAs and divide a DMA block");
     static_assert(BM % (RPI * NW) == 0 && BN % (RPI * NW) == 0, "tiles must split evenly into per-wave DMA blocks");
     static_assert((NW * RPI) % 16 == 0, "the row swizzle must not depend on the DMA instruction index");
-    static_assert(NST >= 2 && (NST - 1) * LPT <= 63, "stage count limited by the vmcnt range");
-    static_assert(SMEM_BYTES <= 160 * 1024, "LDS capacity");
+    static_assert(NST >= 2, "at least double buffering");
 };
 
 template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, int NST, int OCC, int BSRC, int EPI>
 __global__ void __launch_bounds__(WGM * WGN * WGK * 64, OCC)
 igemm_kernel(const IgemmArgs g)
 {
-    typedef IgemmCfg<DT, BM, BN, BKB, WGM, WGN, WGK, MF, NST> C;
+    typedef IgemmCfg<DT, BM, BN, BKB, WGM, WGN, WGK, MF, NST, BSRC> C;
+    static_assert(C::FITS, "tile does not fit the LDS or the vmcnt range in this mode");
     typedef Mma<DT, MF> M;
     typedef typename M::acc_t acc_t;
     typedef typename M::elem_t elem_t;
@@ -234,6 +242,10 @@ igemm_kernel(const IgemmArgs g)
     constexpr int EPC = 16 / ES;                    // elements per 16-byte chunk
     constexpr int CPR = BN * ES / 16;               // NCHW mode: 16-byte chunks per channel row of the B tile
     constexpr int CRPI = 64 / CPR;                  // NCHW mode: channel rows per DMA instruction
+    constexpr int PITCH = 2 * BN * ES;              // shifted mode: bytes per channel row of the B tile
+    constexpr int CPR2 = PITCH / 16;                // shifted mode: chunks per channel row
+    constexpr int CRPI2 = (CPR2 >= 64) ? 1 : 64 / CPR2;
+    static_assert(BSRC != BSRC_NCHWS || CPR2 <= 64, "a channel row must fit one DMA instruction");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -293,7 +305,14 @@ igemm_kernel(const IgemmArgs g)
     for (int j = 0; j < IB; ++j) {
         int r = (j * NW + wave) * RPI + lr_blk;
         bool valid = r < cols_here;
-        if (BSRC == BSRC_NCHW) {
+        if (BSRC == BSRC_NCHWS) {
+            // lane -> (channel row inside the step, 16-byte chunk of that row's window)
+            const int crow = (j * NW + wave) * CRPI2 + lane / CPR2;
+            bh0[j] = crow;
+            bd0[j] = crow * g.PQ * ES;              // byte offset of the channel row inside the step's block
+            bw0[j] = (lane % CPR2) * 16;
+            offB[j] = 0;
+        } else if (BSRC == BSRC_NCHW) {
             // lane -> (channel row inside the DMA block, 16-byte chunk of pixels)
             const int crow = (j * NW + wave) * CRPI + lane / CPR;
             // this lane's 16-byte chunk of pixels lies inside one image (the host only picks this
@@ -333,6 +352,24 @@ igemm_kernel(const IgemmArgs g)
         cs = rs - cr * g.S;
     }
 
+    // shifted direct read: (tap row, tap column, first channel chunk) of the step being issued and of
+    // the step being read; wave-uniform, a step never straddles two taps (host-checked)
+    int it_r = 0, it_s = 0, it_cb = 0, rt_r = 0, rt_s = 0, rt_cb = 0;
+    if (BSRC == BSRC_NCHWS) {
+        const int chunk0 = ks_begin * NCH;
+        const int tap = chunk0 / g.CB;
+        it_cb = rt_cb = chunk0 - tap * g.CB;
+        it_r = rt_r = tap / g.S;
+        it_s = rt_s = tap - it_r * g.S;
+    }
+    auto next_tap = [&](int &tr, int &ts, int &tcb) {
+        tcb += NCH;
+        if (tcb >= g.CB) {
+            tcb = 0;
+            if (++ts == g.S) { ts = 0; ++tr; }
+        }
+    };
+
     // issues the DMA of the next tile (the one whose chunk for this thread is kc) into `stage`
     auto issue_tile = [&](int stage) {
         const bool kok = kc < kend;
@@ -342,7 +379,19 @@ igemm_kernel(const IgemmArgs g)
         for (int j = 0; j < IA; ++j)
             dma16(rsA, dst + j * NW * 1024, kok ? offA[j] + kbyte : UNIT_OOB);
         dst += BM * BKB;
-        if (BSRC == BSRC_NCHW) {
+        if (BSRC == BSRC_NCHWS) {
+            // first byte this step needs of channel row 0 of its block: pixel col0 + delta of
+            // channel it_cb*EPC (negative above the image: those pixels are masked at the read)
+            const int delta = (it_r - g.ph) * g.W + (it_s - g.pw);
+            const int base = (it_cb * EPC * g.PQ + col0 + delta) * ES;
+            const bool step_ok = (kc - cT) < kend;
+#pragma unroll
+            for (int j = 0; j < IB; ++j) {
+                const int off = ((base + bd0[j]) & ~15) + bw0[j];   // enclosing 16-byte grid of the tensor
+                dma16(rsB, dst + j * NW * 1024, (step_ok && off >= 0) ? (unsigned)off : UNIT_OOB);
+            }
+            next_tap(it_r, it_s, it_cb);
+        } else if (BSRC == BSRC_NCHW) {
             // channel rows of this step: chan0 .. chan0 + BKB/ES; rows past the real channel
             // count or past the slice end come back as zeros
             const int chan0 = (kc - cT) * EPC;
@@ -383,6 +432,18 @@ igemm_kernel(const IgemmArgs g)
     const int b_row  = wn * C::WTN + lrow;
     const int a_swz  = swz<NCH>(a_row);             // unchanged by +MF*i (multiples of 16)
     const int b_swz  = swz<NCH>(b_row);
+    // shifted direct read: image coordinates of this lane's output pixels (columns past the end
+    // get a row outside the image, so every tap is masked)
+    int sp[TN], sq[TN];
+    if (BSRC == BSRC_NCHWS) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = col0 + b_row + j * MF;
+            const int p = col / g.W;
+            sp[j] = (col < g.cols) ? p : -0x100000;
+            sq[j] = col - p * g.W;
+        }
+    }
 
     acc_t acc[TM][TN];
 #pragma unroll
@@ -412,7 +473,50 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
             for (int i = 0; i < TM; ++i) fa[slot][i] ^= (int)0x80808080;
         }
-        if (BSRC == BSRC_NCHW) {
+        if (BSRC == BSRC_NCHWS) {
+            // B tile is [channel][window of 2*BN pixels]; element (channel row, tile column c)
+            // sits at row*PITCH + c*ES + (byte shift of that row's window inside the 16-byte grid)
+            const int delta = (rt_r - g.ph) * g.W + (rt_s - g.pw);
+            // byte shift of channel row `row` of a chunk: the chunk's first row starts a whole
+            // number of 16-byte units after the step's first row (16 elements * pixels per row),
+            // so the shift depends on the row inside the chunk only and is wave-uniform
+            const int cbase = (col0 + delta) * ES;
+            const int pqes = g.PQ * ES;
+            const int dr = rt_r - g.ph, dc = rt_s - g.pw;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                unsigned w[4 * FW];
+#pragma unroll
+                for (int f = 0; f < FW; ++f) {
+                    const uint8_t *src = sB + (ch + f) * EPC * PITCH + (b_row + j * MF) * ES;
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        if (ES == 1) {
+                            unsigned b[4];
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) {
+                                const int row = 4 * d + e;
+                                b[e] = src[row * PITCH + ((cbase + row * pqes) & 15)];
+                            }
+                            w[4 * f + d] = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
+                        } else {
+                            unsigned h[2];
+#pragma unroll
+                            for (int e = 0; e < 2; ++e) {
+                                const int row = 2 * d + e;
+                                h[e] = *reinterpret_cast<const uint16_t *>(src + row * PITCH + ((cbase + row * pqes) & 15));
+                            }
+                            w[4 * f + d] = h[0] | (h[1] << 16);
+                        }
+                    }
+                }
+                // taps that fall into the padding (or columns past the image) contribute zero
+                const bool inside = (unsigned)(sp[j] + dr) < (unsigned)g.H && (unsigned)(sq[j] + dc) < (unsigned)g.W;
+#pragma unroll
+                for (int t = 0; t < 4 * FW; ++t) w[t] = inside ? w[t] : 0u;
+                fb[slot][j] = Frag<FW>::pack(w);
+            }
+        } else if (BSRC == BSRC_NCHW) {
             // B tile is [channel][pixel]: gather this lane's 16 bytes of consecutive channels
             // for its pixel column, one element per LDS read
 #pragma unroll
@@ -474,6 +578,7 @@ igemm_kernel(const IgemmArgs g)
                 if (!last) {
                     read_frags(stage, s2 + 1, slot ^ 1);
                 } else {
+                    if (BSRC == BSRC_NCHWS) next_tap(rt_r, rt_s, rt_cb);
                     read_frags(next_stage, 0, slot ^ 1);
                     issue_tile(stage);                           // tile ks+NST into the stage just freed
                 }

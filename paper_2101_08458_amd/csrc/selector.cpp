@@ -27,9 +27,9 @@ static int env_int(const char *name, int dflt)
 
 static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
-TileChoice select_tile(int rows, int cols, int kchunks, int dtype, bool conv, bool allow_split)
+TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split)
 {
-    (void)dtype; (void)conv;
+    (void)dtype;
     const int CUS = 256;
     int tile = -1;
     if (rows <= 16) {
@@ -58,7 +58,17 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, bool conv, bo
     // main-loop step of a small tile costs ~0.2 us of DMA latency, while the extra reduce
     // launch costs ~3 us, so it pays from about 24 steps on (slices of ~6 steps).
     int split = 1;
-    if (ksteps >= 24 && nt <= CUS / 2) {
+    if (bsrc == BSRC_NCHWS) {
+        // the shifted direct read moves twice the B bytes per step and gathers them bytewise
+        // (~0.4 us per step of a small tile), so splitting pays from about 12 steps on; slices
+        // of ~3 steps measured best on the 14x14 and 7x7 layers
+        if (ksteps >= 12 && nt <= CUS / 2) {
+            split = ksteps / 3;
+            if (split > 6) split = 6;
+            int cap = (int)(2 * CUS / nt);
+            if (split > cap) split = cap;
+        }
+    } else if (ksteps >= 24 && nt <= CUS / 2) {
         split = ksteps / 6;
         int cap = (int)(2 * CUS / nt);
         if (split > cap) split = cap;

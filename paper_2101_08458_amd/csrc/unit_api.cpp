@@ -132,7 +132,7 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
               void *ws, size_t ws_bytes, hipStream_t st, bool allow_split = true)
 {
     const bool conv = bsrc != BSRC_PLAIN;
-    TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, conv, allow_split);
+    TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, bsrc, allow_split);
     a.ksteps_per_split = ch.ksteps_per_split;
     if (ch.split_k == 1) {
         a.split_stride = 0;
@@ -177,12 +177,26 @@ bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requan
            d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr && rows_ok && dtype != UNIT_U8I8 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
 }
 
-// `xp` is the packed activation tensor, or (nchw_direct) the caller's NCHW tensor itself.
+// The general direct read (BSRC_NCHWS): one image, stride 1, output grid equal to the input grid
+// ("same" padding), whole steps inside one tap, and a tile shape that has a kernel in this mode.
+bool nchw_shift_ok(const ConvND *d, int dtype, const ConvGeom &g, const void *x, const unit_requant *rq)
+{
+    if (rq || dtype == UNIT_U8I8 || d->n != 1 || d->d != 1 || d->t != 1) return false;
+    if (d->stride_h != 1 || d->stride_w != 1) return false;
+    if (2 * d->pad_h != d->r - 1 || 2 * d->pad_w != d->s - 1) return false;
+    if (reinterpret_cast<uintptr_t>(x) & 15) return false;
+    TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_NCHWS);
+    if (ch.tile == 0) return false;                               // twice-wide B tile exceeds the LDS
+    return ((long)d->c * elem_size(dtype)) % g_tiles[ch.tile].bkb == 0;
+}
+
+// `xp` is the packed activation tensor, or (direct modes) the caller's NCHW tensor itself.
 int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
                 void *y_raw, const unit_requant *rq, int8_t *y_i8, void *y_packed,
-                void *ws, size_t ws_bytes, void *stream, bool nchw_direct = false,
+                void *ws, size_t ws_bytes, void *stream, int bsrc = BSRC_GATHER,
                 const int32_t *fix = nullptr)       // fix: per-channel correction of an unsigned operand
 {
+    const bool nchw_direct = bsrc != BSRC_GATHER;   // xp is the caller's NCHW tensor
     ConvGeom g;
     int rc = conv_geom(d, dtype, &g);
     if (rc != UNIT_OK) return rc;
@@ -218,7 +232,7 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
     } else {
         a.epi = EPI_RAW;  a.store_raw = 1;  a.bias = fix;
     }
-    return run_igemm(dtype, nchw_direct ? BSRC_NCHW : BSRC_GATHER, a, g.out_elems, d->k, a.PQ, ws, ws_bytes,
+    return run_igemm(dtype, bsrc, a, g.out_elems, d->k, a.PQ, ws, ws_bytes,
                      static_cast<hipStream_t>(stream));
 }
 
@@ -236,10 +250,16 @@ size_t conv_fix_bytes(const ConvND *d, int dtype)
     return dtype == UNIT_U8I8 ? align256((size_t)d->k * 4) : 0;
 }
 
-size_t conv_split_bytes(const ConvGeom &g, int dtype)
+size_t conv_split_bytes(const ConvGeom &g, int dtype, int bsrc)
 {
-    TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true);
+    TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, bsrc);
     return ch.split_k > 1 ? align256((size_t)ch.split_k * ((g.out_elems + 3) & ~3L) * 4) : 0;
+}
+// what a caller who does not know the input mode yet must provide
+size_t conv_split_bytes_any(const ConvGeom &g, int dtype)
+{
+    size_t a = conv_split_bytes(g, dtype, BSRC_GATHER), b = conv_split_bytes(g, dtype, BSRC_NCHWS);
+    return a > b ? a : b;
 }
 
 int conv_wpacked(const ConvND *d, int dtype, const void *x, const void *wp,
@@ -250,9 +270,9 @@ bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requan
 // workspace conv_wpacked needs for this call (after the packed weights, if any)
 size_t wpacked_need(const ConvND *d, int dtype, const ConvGeom &g, const void *x, const unit_requant *rq)
 {
-    size_t split_b = conv_split_bytes(g, dtype);
-    return nchw_direct_ok(d, dtype, x, rq) ? split_b
-                                           : packed_act_bytes_nd(d, dtype) + split_b;
+    if (nchw_direct_ok(d, dtype, x, rq)) return conv_split_bytes(g, dtype, BSRC_NCHW);
+    if (nchw_shift_ok(d, dtype, g, x, rq)) return conv_split_bytes(g, dtype, BSRC_NCHWS);
+    return packed_act_bytes_nd(d, dtype) + conv_split_bytes(g, dtype, BSRC_GATHER);
 }
 
 int conv_plain(const ConvND *d, int dtype, const void *x, const void *w,
@@ -294,18 +314,24 @@ int conv_wpacked(const ConvND *d, int dtype, const void *x, const void *wp,
     if (rc != UNIT_OK) return rc;
     if (!x || !wp) return UNIT_EINVAL;
     if (ws && !aligned256(ws)) return UNIT_EINVAL;
-    size_t split_b = conv_split_bytes(g, dtype);
     if (!aligned16(wp)) return UNIT_EINVAL;
+    size_t split_b = conv_split_bytes(g, dtype, BSRC_NCHW);
     if (nchw_direct_ok(d, dtype, x, rq)) {
         if (split_b && (!ws || ws_bytes < split_b)) return UNIT_EWORKSPACE;
-        return conv_packed(d, dtype, x, wp, y_raw, rq, y_i8, nullptr, ws, ws_bytes, stream, true);
+        return conv_packed(d, dtype, x, wp, y_raw, rq, y_i8, nullptr, ws, ws_bytes, stream, BSRC_NCHW);
     }
+    if (nchw_shift_ok(d, dtype, g, x, rq)) {
+        split_b = conv_split_bytes(g, dtype, BSRC_NCHWS);
+        if (split_b && (!ws || ws_bytes < split_b)) return UNIT_EWORKSPACE;
+        return conv_packed(d, dtype, x, wp, y_raw, rq, y_i8, nullptr, ws, ws_bytes, stream, BSRC_NCHWS);
+    }
+    split_b = conv_split_bytes(g, dtype, BSRC_GATHER);
     size_t act_b = packed_act_bytes_nd(d, dtype);
     if (!ws || ws_bytes < act_b + split_b) return UNIT_EWORKSPACE;
     uint8_t *xp = static_cast<uint8_t *>(ws);
     UNIT_HIP(launch_pack_act(storage_dtype(dtype), d->n, d->c, d->d * d->h, d->w, x, xp, static_cast<hipStream_t>(stream)));
     return conv_packed(d, dtype, xp, wp, y_raw, rq, y_i8, nullptr, split_b ? xp + act_b : nullptr, split_b, stream,
-                       false, fix);
+                       BSRC_GATHER, fix);
 }
 
 struct MatmulGeom {
@@ -330,7 +356,7 @@ int matmul_geom(int m, int n, int k, long lda, long ldb, int dtype, MatmulGeom *
     g->a_bytes = g->pad_a ? align256((size_t)m * g->kpad_bytes) : 0;
     g->b_bytes = g->pad_b ? align256((size_t)n * g->kpad_bytes) : 0;
     g->fix_bytes = dtype == UNIT_U8I8 ? align256((size_t)n * 4) : 0;
-    TileChoice ch = select_tile(m, n, g->kchunks, dtype, false);
+    TileChoice ch = select_tile(m, n, g->kchunks, dtype, BSRC_PLAIN);
     g->split_bytes = ch.split_k > 1 ? align256((size_t)ch.split_k * (((long)m * n + 3) & ~3L) * 4) : 0;
     return UNIT_OK;
 }
@@ -427,7 +453,7 @@ size_t unit_conv2d_packed_workspace(const unit_conv2d_desc *d, int dtype)
     ConvGeom g;
     ConvND nd(d);
     if (conv_geom(&nd, dtype, &g) != UNIT_OK) return 0;
-    return conv_split_bytes(g, dtype);
+    return conv_split_bytes(g, dtype, BSRC_GATHER);
 }
 
 size_t unit_conv2d_workspace(const unit_conv2d_desc *d, int dtype)
@@ -436,7 +462,7 @@ size_t unit_conv2d_workspace(const unit_conv2d_desc *d, int dtype)
     ConvND nd(d);
     if (conv_geom(&nd, dtype, &g) != UNIT_OK) return 0;
     return packed_act_bytes_nd(&nd, dtype) + packed_weights_bytes_nd(&nd, dtype) + conv_fix_bytes(&nd, dtype) +
-           conv_split_bytes(g, dtype);
+           conv_split_bytes_any(g, dtype);
 }
 
 size_t unit_matmul_workspace(int32_t m, int32_t n, int32_t k, int64_t lda, int64_t ldb, int dtype)
@@ -453,8 +479,20 @@ int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out
     int rc = conv_geom(&nd, dtype, &g);
     if (rc != UNIT_OK) return rc;
     if (!out) return UNIT_EINVAL;
-    fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, true), dtype, out);
+    fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_GATHER), dtype, out);
     return UNIT_OK;
+}
+
+int unit_conv2d_input_mode(const unit_conv2d_desc *d, int dtype, const void *x)
+{
+    ConvGeom g;
+    ConvND nd(d);
+    int rc = conv_geom(&nd, dtype, &g);
+    if (rc != UNIT_OK) return rc;
+    if (!x) return UNIT_EINVAL;
+    if (nchw_direct_ok(&nd, dtype, x, nullptr)) return UNIT_INPUT_DIRECT;
+    if (nchw_shift_ok(&nd, dtype, g, x, nullptr)) return UNIT_INPUT_DIRECT_SHIFTED;
+    return UNIT_INPUT_PACKED;
 }
 
 int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_info *out)
@@ -463,7 +501,7 @@ int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_inf
     int rc = matmul_geom(m, n, k, k, k, dtype, &g);
     if (rc != UNIT_OK) return rc;
     if (!out) return UNIT_EINVAL;
-    fill_tile_info(select_tile(m, n, g.kchunks, dtype, false), dtype, out);
+    fill_tile_info(select_tile(m, n, g.kchunks, dtype, BSRC_PLAIN), dtype, out);
     return UNIT_OK;
 }
 
@@ -601,7 +639,7 @@ size_t unit_conv2d_wpacked_workspace(const unit_conv2d_desc *d, int dtype)
     ConvGeom g;
     ConvND nd(d);
     if (conv_geom(&nd, dtype, &g) != UNIT_OK) return 0;
-    return packed_act_bytes_nd(&nd, dtype) + conv_split_bytes(g, dtype);
+    return packed_act_bytes_nd(&nd, dtype) + conv_split_bytes_any(g, dtype);
 }
 
 int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const void *wp,
@@ -677,7 +715,7 @@ size_t unit_conv3d_workspace(const unit_conv3d_desc *d, int dtype)
     ConvND nd(d);
     if (conv_geom(&nd, dtype, &g) != UNIT_OK) return 0;
     return packed_act_bytes_nd(&nd, dtype) + packed_weights_bytes_nd(&nd, dtype) + conv_fix_bytes(&nd, dtype) +
-           conv_split_bytes(g, dtype);
+           conv_split_bytes_any(g, dtype);
 }
 
 int unit_conv3d_i8(const unit_conv3d_desc *d, const int8_t *x, const int8_t *w, int32_t *y,

@@ -29,7 +29,8 @@ struct TileChoice {
 };
 
 // selector.cpp (pure host arithmetic)
-TileChoice select_tile(int rows, int cols, int kchunks, int dtype, bool conv, bool allow_split = true);
+// bsrc: where the B operand comes from (BSRC_*); the tile depends on the shape only, the split also on bsrc
+TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split = true);
 
 // launchers (kernels_*.hip).  All return hipError_t from the launch.
 hipError_t launch_igemm(int dtype, int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);

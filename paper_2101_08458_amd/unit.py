@@ -74,6 +74,7 @@ EXPORTS = [
     "unit_conv3d_out_dims", "unit_conv3d_workspace", "unit_conv3d_i8", "unit_conv3d_f16",
     "unit_conv2d_bf16", "unit_matmul_bf16", "unit_conv2d_u8i8", "unit_matmul_u8i8",
     "unit_conv2d_fp8", "unit_matmul_fp8",
+    "unit_conv2d_input_mode",
     "unit_inspect", "unit_describe_mfma", "unit_describe_conv2d", "unit_describe_matmul",
 ]
 
@@ -132,6 +133,7 @@ def load():
         "unit_matmul_fp8": (ctypes.c_int, [i32, i32, i32, vp, i64, vp, i64, vp, i64, vp, sz, vp]),
         "unit_matmul_bf16": (ctypes.c_int, [i32, i32, i32, vp, i64, vp, i64, vp, i64, vp, sz, vp]),
         "unit_matmul_u8i8": (ctypes.c_int, [i32, i32, i32, vp, i64, vp, i64, vp, i64, vp, sz, vp]),
+        "unit_conv2d_input_mode": (ctypes.c_int, [dp, ctypes.c_int, vp]),
         "unit_inspect": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_char_p, ctypes.POINTER(unit_inspect_result)]),
         "unit_describe_mfma": (ctypes.c_int, [ctypes.c_int, i32, ctypes.c_char_p, sz]),
         "unit_describe_conv2d": (ctypes.c_int, [dp, ctypes.c_int, ctypes.c_char_p, sz]),
@@ -351,6 +353,16 @@ def unit_global_avgpool_packed_i8(n, c, h, w, xp, scale, y, stream=None):
 def unit_widen_residual_i8(n, c, h, w, xp, mult, residual, stream=None):
     _check(load().unit_widen_residual_i8(n, c, h, w, _p(xp), mult, _p(residual), _stream(stream)),
            "unit_widen_residual_i8")
+
+
+UNIT_INPUT_PACKED, UNIT_INPUT_DIRECT, UNIT_INPUT_DIRECT_SHIFTED = 0, 1, 2
+
+
+def unit_conv2d_input_mode(d, dtype, x):
+    rc = load().unit_conv2d_input_mode(ctypes.byref(d), dtype, _p(x))
+    if rc < 0:
+        _check(rc, "unit_conv2d_input_mode")
+    return rc
 
 
 # ------------------------------------------------------------------ further operand types
