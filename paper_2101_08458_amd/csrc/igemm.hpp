@@ -131,6 +131,20 @@ template <int MF> struct Mma<DT_U8B, MF> : Mma<DT_I8, MF> {};
 
 // A fragment of FW 16-byte chunks: consecutive logical chunks ch .. ch+FW-1 of one LDS row
 // (the swizzle is applied per chunk), or FW*4 assembled words.
+// a / b for 0 <= a < 2^22, 0 < b: float reciprocal plus one correction step (a hardware integer
+// division is ~40 instructions, and a small kernel's prologue does about ten of them)
+__device__ __forceinline__ int div_small(int a, int b)
+{
+    int q = (int)((float)a * __builtin_amdgcn_rcpf((float)b));
+    int r = a - q * b;
+    q += (r >= b) ? 1 : 0;
+    q -= (r < 0) ? 1 : 0;
+    return q;
+}
+__device__ __forceinline__ int div_any(int a, int b) { return (a < (1 << 22)) ? div_small(a, b) : a / b; }
+
+template <int V> struct IntC { static constexpr int value = V; };
+
 template <int FW> struct Frag;
 template <> struct Frag<1> {
     static __device__ __forceinline__ v4i load(const uint8_t *row, int ch, int sw)
@@ -251,7 +265,7 @@ igemm_kernel(const IgemmArgs g)
 
     const int tid  = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS addresses scalar
     const int wk   = wave / (WGM * WGN);
     const int wm   = (wave % (WGM * WGN)) / WGN;
     const int wn   = wave % WGN;
@@ -265,12 +279,12 @@ igemm_kernel(const IgemmArgs g)
     int bid = blockIdx.x;
     if ((ntiles & 7) == 0) bid = (bid & 7) * (ntiles >> 3) + (bid >> 3);
     constexpr int BAND = 8;
-    const int band      = bid / (BAND * tiles_n);
+    const int band      = div_any(bid, BAND * tiles_n);
     const int band_m0   = band * BAND;
     const int band_rows = (tiles_m - band_m0 < BAND) ? tiles_m - band_m0 : BAND;
     const int in_band   = bid - band * BAND * tiles_n;
-    const int tm = band_m0 + in_band % band_rows;
-    const int tn = in_band / band_rows;
+    const int tn = div_any(in_band, band_rows);
+    const int tm = band_m0 + in_band - tn * band_rows;
     const int row0 = tm * BM, col0 = tn * BN;
 
     const int ksteps_total = (g.kchunks + NCH - 1) / NCH;
@@ -319,15 +333,18 @@ igemm_kernel(const IgemmArgs g)
             // mode when the pixels per image are a multiple of the chunk); columns past the end
             // read whatever follows and are masked at the store
             const int px = col0 + (lane % CPR) * EPC;
-            const int img = px / g.PQ;
+            const int img = (g.cols > g.PQ) ? div_any(px, g.PQ) : 0;
             offB[j] = (unsigned)(((img * g.Cin + crow) * g.PQ + (px - img * g.PQ)) * ES);
             bh0[j] = crow;                          // channel row of this lane inside a step
             bd0[j] = bw0[j] = 0;
         } else if (BSRC == BSRC_GATHER) {
             int cc = valid ? col0 + r : 0;
-            int n = cc / g.PQ, opq = cc - n * g.PQ;
-            int o = opq / (g.P * g.Q), pq = opq - o * (g.P * g.Q);
-            int p = pq / g.Q, q = pq - p * g.Q;
+            // (integer divisions are ~40 instructions each: skip the ones whose result is known)
+            int n = 0, opq = cc;
+            if (g.cols > g.PQ) { n = div_any(cc, g.PQ); opq = cc - n * g.PQ; }   // more than one image
+            int o = 0, pq = opq;
+            if (g.PQ > g.P * g.Q) { o = div_any(opq, g.P * g.Q); pq = opq - o * (g.P * g.Q); }   // output depth > 1
+            int p = div_any(pq, g.Q), q = pq - p * g.Q;
             // an invalid column gets a row far outside the image: its bounds test always fails
             const int bd = o * g.sd - g.pd, bh = p * g.sh - g.ph, bw = q * g.sw - g.pw;
             bd0[j] = bd;
@@ -343,7 +360,8 @@ igemm_kernel(const IgemmArgs g)
     // conv: reduction chunk kc -> (r, s, channel chunk cb), advanced incrementally per step
     int kc = ks_begin * NCH + cT;
     int ct = 0, cr = 0, cs = 0, ccb = 0;
-    if (BSRC == BSRC_GATHER) {
+    const bool uni_tap = (BSRC == BSRC_GATHER) && (g.CB % NCH == 0);
+    if (BSRC == BSRC_GATHER && !uni_tap) {
         int trs = kc / g.CB;
         ccb = kc - trs * g.CB;
         ct = trs / (g.R * g.S);
@@ -352,10 +370,32 @@ igemm_kernel(const IgemmArgs g)
         cs = rs - cr * g.S;
     }
 
+    // Gather fast path: when the channel chunks of a pixel are a whole number of steps
+    // (CB % NCH == 0) every lane of a step works on the same tap, so the tap walk is scalar:
+    // (ut, ur, us) and the byte offset `utap` of (tap, first chunk of the step) inside the packed
+    // tensor.  Consecutive chunks are consecutive in memory across the s axis, so utap only
+    // jumps when a tap row or plane ends.
+    int ut = 0, ur = 0, us = 0, ucb = 0;
+    unsigned utap = 0;
+    if (uni_tap) {
+        if (ks_begin != 0) {                    // only the later slices of a split reduction
+            const int chunk0 = ks_begin * NCH;
+            const int trs = chunk0 / g.CB;
+            ucb = chunk0 - trs * g.CB;
+            ut = trs / (g.R * g.S);
+            const int rs = trs - ut * (g.R * g.S);
+            ur = rs / g.S;
+            us = rs - ur * g.S;
+            utap = (unsigned)(((ut * g.H + ur) * g.W + us) * g.CB + ucb) * 16u;
+        }
+#pragma unroll
+        for (int j = 0; j < IB; ++j) offB[j] += (unsigned)cT * 16u;   // this lane's chunk inside the step
+    }
+
     // shifted direct read: (tap row, tap column, first channel chunk) of the step being issued and of
     // the step being read; wave-uniform, a step never straddles two taps (host-checked)
     int it_r = 0, it_s = 0, it_cb = 0, rt_r = 0, rt_s = 0, rt_cb = 0;
-    if (BSRC == BSRC_NCHWS) {
+    if (BSRC == BSRC_NCHWS && ks_begin != 0) {
         const int chunk0 = ks_begin * NCH;
         const int tap = chunk0 / g.CB;
         it_cb = rt_cb = chunk0 - tap * g.CB;
@@ -401,12 +441,36 @@ igemm_kernel(const IgemmArgs g)
                 bool ok = chan0 + bh0[j] < chan_end;
                 dma16(rsB, dst + j * NW * 1024, ok ? offB[j] + (unsigned)(chan0 * g.PQ * ES) : UNIT_OOB);
             }
+        } else if (BSRC == BSRC_GATHER && uni_tap) {
+            const bool step_ok = (kc - cT) < kend;
+#pragma unroll
+            for (int j = 0; j < IB; ++j) {
+                const int dd = bd0[j] + ut, h = bh0[j] + ur, w = bw0[j] + us;
+                const bool ok = step_ok & ((unsigned)dd < (unsigned)g.D) & ((unsigned)h < (unsigned)g.H) &
+                                ((unsigned)w < (unsigned)g.W);
+                dma16(rsB, dst + j * NW * 1024, ok ? offB[j] + utap : UNIT_OOB);
+            }
+            ucb += NCH;
+            utap += NCH * 16u;
+            if (ucb >= g.CB) {
+                ucb = 0;
+                if (++us == g.S) {
+                    us = 0;
+                    utap += (unsigned)((g.W - g.S) * g.CB) * 16u;
+                    if (++ur == g.R) {
+                        ur = 0;
+                        ++ut;
+                        utap += (unsigned)((g.H - g.R) * g.W * g.CB) * 16u;
+                    }
+                }
+            }
         } else if (BSRC == BSRC_GATHER) {
             const unsigned tap = (unsigned)(((ct * g.H + cr) * g.W + cs) * g.CB + ccb) * 16u;
 #pragma unroll
             for (int j = 0; j < IB; ++j) {
-                int dd = bd0[j] + ct, h = bh0[j] + cr, w = bw0[j] + cs;
-                bool ok = kok && (unsigned)dd < (unsigned)g.D && (unsigned)h < (unsigned)g.H && (unsigned)w < (unsigned)g.W;
+                const int dd = bd0[j] + ct, h = bh0[j] + cr, w = bw0[j] + cs;
+                const bool ok = kok & ((unsigned)dd < (unsigned)g.D) & ((unsigned)h < (unsigned)g.H) &
+                                ((unsigned)w < (unsigned)g.W);
                 dma16(rsB, dst + j * NW * 1024, ok ? offB[j] + tap : UNIT_OOB);
             }
             ccb += NCH;
@@ -439,7 +503,7 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = col0 + b_row + j * MF;
-            const int p = col / g.W;
+            const int p = div_any(col, g.W);
             sp[j] = (col < g.cols) ? p : -0x100000;
             sq[j] = col - p * g.W;
         }
@@ -461,7 +525,13 @@ igemm_kernel(const IgemmArgs g)
     // tile NST steps ahead and the first fragments of the next tile are read, so those
     // MFMAs cover barrier skew and LDS latency.
     constexpr int NS = C::NKSUB / WGK;              // sub-steps per wave per step
-    frag_t fa[2][TM], fb[2][TN];
+    // Small wave tiles (at most 4 MFMAs per sub-step) cannot hide an LDS read behind one
+    // sub-step's MFMAs, so they keep whole steps in registers instead: while the MFMAs of step
+    // ks run, all fragments of step ks+1 are read into the other register set (slots
+    // set*NS + sub), and the step loop is unrolled by two so that the set is a constant.
+    constexpr bool WHOLE = (TM * TN <= 4);
+    constexpr int NSLOT = WHOLE ? 2 * NS : 2;
+    frag_t fa[NSLOT][TM], fb[NSLOT][TN];
     auto read_frags = [&](int stage, int sub, int slot) {
         const uint8_t *sA = smem + stage * C::STAGE_BYTES;
         const uint8_t *sB = sA + BM * BKB;
@@ -557,8 +627,50 @@ igemm_kernel(const IgemmArgs g)
         for (int t = 0; t < NST; ++t) issue_tile(t);            // tiles 0..NST-1 (zeros past the slice end)
         UNIT_WAIT_VM_LGKM0((NST - 1) * C::LPT);                 // own part of tile 0 has landed
         UNIT_BARRIER();
-        read_frags(0, 0, 0);
         int stage = 0;
+        if (WHOLE) {
+#pragma unroll
+            for (int s2 = 0; s2 < NS; ++s2) read_frags(0, s2, s2);
+            auto whole_step = [&](auto set_c) {
+                constexpr int SET = decltype(set_c)::value;
+                const int next_stage = (stage + 1 == NST) ? 0 : stage + 1;
+                UNIT_WAIT_VM_LGKM0((NST - 2) * C::LPT);         // next tile landed, my reads of this one done
+                UNIT_BARRIER();
+                __builtin_amdgcn_sched_barrier(0);
+                if (BSRC == BSRC_NCHWS) next_tap(rt_r, rt_s, rt_cb);
+#pragma unroll
+                for (int s2 = 0; s2 < NS; ++s2) read_frags(next_stage, s2, (SET ^ 1) * NS + s2);
+                issue_tile(stage);                               // tile ks+NST into the stage just freed
+#pragma unroll
+                for (int s2 = 0; s2 < NS; ++s2)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int j = 0; j < TN; ++j)
+                            M::run(acc[i][j], fa[SET * NS + s2][i], fb[SET * NS + s2][j]);
+                {
+                    // the reads go first (their data is due one step later), then the DMAs are
+                    // spread between the MFMAs
+                    constexpr int NMFMA = NS * TM * TN;
+                    constexpr int VPM = (C::LPT + NMFMA - 1) / NMFMA;
+                    __builtin_amdgcn_sched_group_barrier(0x100, NS * (TM + TN) * FW, 0);
+#pragma unroll
+                    for (int r = 0; r < NMFMA; ++r) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);      // MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x020, VPM, 0);    // global -> LDS DMA
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                stage = next_stage;
+            };
+            for (int ks = ks_begin;;) {
+                whole_step(IntC<0>{});
+                if (++ks >= ks_end) break;
+                whole_step(IntC<1>{});
+                if (++ks >= ks_end) break;
+            }
+        } else {
+        read_frags(0, 0, 0);
         for (int ks = ks_begin; ks < ks_end; ++ks) {
             const int next_stage = (stage + 1 == NST) ? 0 : stage + 1;
 #pragma unroll
@@ -612,6 +724,7 @@ igemm_kernel(const IgemmArgs g)
                 for (int j = 0; j < TN; ++j) fb[0][j] = fb[1][j];
             }
             stage = next_stage;
+        }
         }
         UNIT_WAIT_VM_LGKM0(0);                       // drain the (zero-fill) DMAs of the tiles past the end
         UNIT_BARRIER();
@@ -670,7 +783,7 @@ igemm_kernel(const IgemmArgs g)
             const int col = col0 + wn * C::WTN + j * MF + lrow;
             unsigned cbase;
             if (CONV) {
-                int n = col / g.cols_per_img;
+                int n = (g.cols > g.cols_per_img) ? div_any(col, g.cols_per_img) : 0;
                 cbase = (unsigned)((long)n * g.img_stride + (col - n * g.cols_per_img));
             } else {
                 cbase = (unsigned)col;
@@ -700,7 +813,7 @@ igemm_kernel(const IgemmArgs g)
             if (col >= g.cols) continue;
             long cbase;
             if (CONV) {
-                int n = col / g.cols_per_img;
+                int n = (g.cols > g.cols_per_img) ? div_any(col, g.cols_per_img) : 0;
                 cbase = (long)n * g.img_stride + (col - n * g.cols_per_img);
             } else {
                 cbase = col;
