@@ -206,6 +206,8 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t r, uint8_t *lds, un
 }
 // s_waitcnt vmcnt(N) lgkmcnt(0)  (expcnt left alone); N <= 63
 #define UNIT_WAIT_VM_LGKM0(N) __builtin_amdgcn_s_waitcnt((((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4)))
+// s_waitcnt vmcnt(N) only (lgkmcnt and expcnt left alone)
+#define UNIT_WAIT_VM(N) __builtin_amdgcn_s_waitcnt((((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4) | (0xF << 8)))
 // workgroup barrier that the compiler may not move LDS traffic across
 #define UNIT_BARRIER() do { asm volatile("" ::: "memory"); __builtin_amdgcn_s_barrier(); asm volatile("" ::: "memory"); } while (0)
 
@@ -529,7 +531,11 @@ igemm_kernel(const IgemmArgs g)
     // sub-step's MFMAs, so they keep whole steps in registers instead: while the MFMAs of step
     // ks run, all fragments of step ks+1 are read into the other register set (slots
     // set*NS + sub), and the step loop is unrolled by two so that the set is a constant.
+    // The DMA then runs NST-1 tiles ahead and refills the stage read one step EARLIER (whose
+    // reads every wave has consumed in its previous step's MFMAs), so the step's barrier needs
+    // no wait on outstanding LDS reads: they complete behind the MFMAs and the DMA issue.
     constexpr bool WHOLE = (TM * TN <= 4);
+    static_assert(!WHOLE || NST >= 3, "the register-prefetch schedule needs three LDS stages");
     constexpr int NSLOT = WHOLE ? 2 * NS : 2;
     frag_t fa[NSLOT][TM], fb[NSLOT][TN];
     auto read_frags = [&](int stage, int sub, int slot) {
@@ -623,9 +629,10 @@ igemm_kernel(const IgemmArgs g)
     };
 
     if (ks_begin < ks_end) {
+        constexpr int AHEAD = WHOLE ? NST - 1 : NST;            // tiles in flight after the prologue
 #pragma unroll
-        for (int t = 0; t < NST; ++t) issue_tile(t);            // tiles 0..NST-1 (zeros past the slice end)
-        UNIT_WAIT_VM_LGKM0((NST - 1) * C::LPT);                 // own part of tile 0 has landed
+        for (int t = 0; t < AHEAD; ++t) issue_tile(t);          // (zeros past the slice end)
+        UNIT_WAIT_VM_LGKM0((AHEAD - 1) * C::LPT);               // own part of tile 0 has landed
         UNIT_BARRIER();
         int stage = 0;
         if (WHOLE) {
@@ -634,13 +641,14 @@ igemm_kernel(const IgemmArgs g)
             auto whole_step = [&](auto set_c) {
                 constexpr int SET = decltype(set_c)::value;
                 const int next_stage = (stage + 1 == NST) ? 0 : stage + 1;
-                UNIT_WAIT_VM_LGKM0((NST - 2) * C::LPT);         // next tile landed, my reads of this one done
+                const int prev_stage = (stage == 0) ? NST - 1 : stage - 1;
+                UNIT_WAIT_VM((NST - 3) * C::LPT);               // own part of the next tile has landed
                 UNIT_BARRIER();
                 __builtin_amdgcn_sched_barrier(0);
                 if (BSRC == BSRC_NCHWS) next_tap(rt_r, rt_s, rt_cb);
 #pragma unroll
                 for (int s2 = 0; s2 < NS; ++s2) read_frags(next_stage, s2, (SET ^ 1) * NS + s2);
-                issue_tile(stage);                               // tile ks+NST into the stage just freed
+                issue_tile(prev_stage);                          // tile ks+NST-1 into the stage read one step ago
 #pragma unroll
                 for (int s2 = 0; s2 < NS; ++s2)
 #pragma unroll
