@@ -107,3 +107,31 @@ def test_size_limits_and_wpacked_errors(lib):
     assert f(ctypes.byref(d3), fake, fake, fake, None, None, None, 0, st) == unit.UNIT_EWORKSPACE
     assert unit.unit_conv2d_wpacked_workspace(d3, unit.UNIT_I8) >= 64 * 64
     assert lib.unit_conv2d_wpacked_f16(ctypes.byref(d), fake, fake, None, None, 0, st) == unit.UNIT_EINVAL
+
+
+def test_input_mode_decisions_are_host_logic(lib):
+    """Which layers skip pack_act is decided on the host from the shape and the alignment of
+    `x` alone (nothing is dereferenced), so the rule can be checked without a GPU."""
+    x = 0x7f0000000000            # 16-byte aligned, never dereferenced
+    mode = lambda *a, dtype=unit.UNIT_I8, ptr=x: lib.unit_conv2d_input_mode(
+        ctypes.byref(unit.conv_desc(*a)), dtype, ctypes.c_void_p(ptr))
+    P, D, S = unit.UNIT_INPUT_PACKED, unit.UNIT_INPUT_DIRECT, unit.UNIT_INPUT_DIRECT_SHIFTED
+    assert mode(1, 64, 56, 56, 256, 1, 1, 1, 0) == D              # aligned 1x1
+    assert mode(16, 64, 56, 56, 256, 1, 1, 1, 0, dtype=unit.UNIT_F16) == D   # batches: whole chunks per image
+    assert mode(1, 512, 7, 7, 2048, 1, 1, 1, 0) == S              # 49-byte rows
+    assert mode(1, 256, 14, 14, 256, 3, 3, 1, 1) == S             # 3x3, same padding
+    assert mode(1, 128, 11, 10, 33, 5, 5, 1, 2) == S
+    assert mode(1, 64, 56, 56, 64, 3, 3, 1, 1) == P               # 64 int8 channels: half a step
+    assert mode(1, 64, 56, 56, 64, 3, 3, 1, 1, dtype=unit.UNIT_F16) == S
+    assert mode(2, 256, 14, 14, 256, 3, 3, 1, 1) == P             # more than one image
+    assert mode(1, 256, 14, 14, 256, 3, 3, 2, 1) == P             # stride 2
+    assert mode(1, 256, 14, 14, 256, 3, 3, 1, 0) == P             # output grid smaller than the input
+    assert mode(1, 256, 14, 14, 256, 3, 3, 1, 1, dtype=unit.UNIT_U8I8) == P
+    assert mode(1, 256, 14, 14, 256, 3, 3, 1, 1, ptr=x + 8) == P  # misaligned tensor
+    assert mode(1, 3, 224, 224, 64, 7, 7, 2, 3) == P              # the stem
+    assert lib.unit_conv2d_input_mode(ctypes.byref(unit.conv_desc(1, 8, 8, 8, 8, 3, 3, 1, 1)),
+                                      unit.UNIT_I8, None) == unit.UNIT_EINVAL
+    assert mode(1, 8, 2, 2, 8, 5, 5, 1, 0) == unit.UNIT_EINVAL    # empty output
+    # the ResNet-50-shaped set at batch 1: 43 of the 53 layers read NCHW directly
+    direct = sum(mode(1, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad) != P for sh in wl.resnet50_convs())
+    assert direct == 43
