@@ -131,3 +131,29 @@ def test_modes_that_must_not_use_the_shifted_read():
     assert mode(unit.conv_desc(1, 128, 14, 14, 64, 1, 1, 1, 0)) == DIRECT          # aligned rows: plain direct read
     assert mode(unit.conv_desc(1, 128, 14, 14, 64, 3, 3, 1, 1), x=xd[4:]) == PACKED   # misaligned tensor base
     assert mode(unit.conv_desc(1, 128, 14, 14, 64, 3, 3, 1, 1)) == SHIFTED
+
+
+def test_shifted_direct_odd_geometries():
+    """Windows with different extents per axis, single-row and single-pixel images."""
+    geoms = [   # (c, h, w, k, r, s, pad_h, pad_w)
+        (128, 6, 9, 24, 1, 3, 0, 1), (128, 9, 6, 24, 3, 1, 1, 0), (128, 1, 17, 40, 3, 3, 1, 1),
+        (128, 13, 1, 40, 3, 3, 1, 1), (256, 1, 1, 64, 3, 3, 1, 1), (128, 2, 2, 33, 5, 5, 2, 2),
+        (128, 3, 40, 16, 3, 7, 1, 3),
+    ]
+    for i, (c, h, w, k, r, s, ph, pw) in enumerate(geoms):
+        d = unit.conv_desc(1, c, h, w, k, r, s, (1, 1), (ph, pw))
+        g = wl.rng(63, i)
+        x = wl.int8_activations(g, (1, c, h, w))
+        wt = wl.int8_weights(g, (k, c, r, s))
+        ref = oracle.conv2d_i8(x, wt, (1, 1), (ph, pw))
+        xd = dev(x)
+        for tile in (None, 1, 3, 4):
+            with forced(tile=tile):
+                mode = unit.unit_conv2d_input_mode(d, unit.UNIT_I8, xd)
+                announce("shifted odd geometry", (c, h, w, k, r, s, ph, pw), "tile", tile, "mode", mode)
+                if tile is None and k > 16:
+                    assert mode == SHIFTED
+                y = torch.full(ref.shape, -7, dtype=torch.int32, device="cuda:0")
+                unit.unit_conv2d_i8(d, xd, dev(wt), y, None, None, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_I8)))
+                torch.cuda.synchronize()
+            assert same(host(y), ref, f"geometry {i} tile {tile}")
