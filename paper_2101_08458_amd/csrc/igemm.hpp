@@ -642,7 +642,7 @@ igemm_kernel(const IgemmArgs g)
                 constexpr int SET = decltype(set_c)::value;
                 const int next_stage = (stage + 1 == NST) ? 0 : stage + 1;
                 const int prev_stage = (stage == 0) ? NST - 1 : stage - 1;
-                UNIT_WAIT_VM((NST - 3) * C::LPT);               // own part of the next tile has landed
+                UNIT_WAIT_VM((NST >= 3 ? NST - 3 : 0) * C::LPT);   // own part of the next tile has landed
                 UNIT_BARRIER();
                 __builtin_amdgcn_sched_barrier(0);
                 if (BSRC == BSRC_NCHWS) next_tap(rt_r, rt_s, rt_cb);
