@@ -43,6 +43,12 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
             double fill = (double)rows * cols / ((double)nt * c.bm * c.bn);
             if (nt >= CUS * 3 / 4 && fill >= 0.6) { tile = t; break; }
         }
+        // Few output rows (<= 64 channels) but very many columns (network stems and first
+        // stages at batch >= 8): a 64x64 tile starves its waves (one accumulator each).  The
+        // 64x256 tile gives every wave a 64x64 window without wasted rows; for short reductions
+        // the 128x128 tile is as fast even with half of its rows empty (they cost no traffic).
+        if (tile < 0 && rows <= 64 && (long)cdiv(cols, 256) >= CUS * 3 / 4)
+            tile = (kchunks >= 32) ? 6 : 1;
         // small problems are launch- and latency-bound: measured over the ResNet-50 batch-1
         // layers, 64x64 (2x2 waves) wins once it yields ~100 workgroups, 32x32 below that
         if (tile < 0) tile = ((long)cdiv(rows, 64) * cdiv(cols, 64) >= 96) ? 3 : 4;
