@@ -58,6 +58,9 @@ struct IgemmArgs {
     // (D, T, sd, pd describe the depth axis; conv2d is D = T = 1)
     int D, H, W, CB, P, Q, PQ, T, R, S, sd, sh, sw, pd, ph, pw;
     int Cin;                                        // NCHW-direct kernels: real channel count
+    int per_img;                                    // NCHW-direct: column tiles never straddle images (each image's
+                                                    // pixels are tiled on their own; needed when an image does not
+                                                    // hold a whole number of 16-byte pixel chunks)
     // output: element (row, col) of image n = col / cols_per_img lives at
     //   out[n*img_stride + row*row_stride + col % cols_per_img]   (4-byte elements)
     void *out;  long row_stride;  long img_stride;  int cols_per_img;
@@ -276,7 +279,9 @@ igemm_kernel(const IgemmArgs g)
     // its own L2): give every XCD one contiguous run of the tile order, and walk that
     // order in bands of 8 row-tiles so the tiles resident together share A and B rows.
     const int tiles_m = (g.rows + BM - 1) / BM;
-    const int tiles_n = (g.cols + BN - 1) / BN;
+    const int tiles_img = (g.PQ + BN - 1) / BN;     // per-image tiling only
+    const bool per_img = (BSRC == BSRC_NCHW) && g.per_img;
+    const int tiles_n = per_img ? tiles_img * div_any(g.cols, g.PQ) : (g.cols + BN - 1) / BN;
     const int ntiles  = tiles_m * tiles_n;
     int bid = blockIdx.x;
     if ((ntiles & 7) == 0) bid = (bid & 7) * (ntiles >> 3) + (bid >> 3);
@@ -287,7 +292,13 @@ igemm_kernel(const IgemmArgs g)
     const int in_band   = bid - band * BAND * tiles_n;
     const int tn = div_any(in_band, band_rows);
     const int tm = band_m0 + in_band - tn * band_rows;
-    const int row0 = tm * BM, col0 = tn * BN;
+    const int row0 = tm * BM;
+    int col0 = tn * BN, col_end = g.cols;           // first column of the tile, end of its column range
+    if (per_img) {
+        const int img = div_any(tn, tiles_img);
+        col0 = img * g.PQ + (tn - img * tiles_img) * BN;
+        col_end = (img + 1) * g.PQ;
+    }
 
     const int ksteps_total = (g.kchunks + NCH - 1) / NCH;
     const int ks_begin = blockIdx.z * g.ksteps_per_split;
@@ -311,7 +322,7 @@ igemm_kernel(const IgemmArgs g)
         int r = (j * NW + wave) * RPI + lr_blk;
         offA[j] = (r < rows_here) ? (unsigned)(r * (int)g.lda + cT * 16) : UNIT_OOB;
     }
-    const int cols_here = (g.cols - col0 < BN) ? g.cols - col0 : BN;
+    const int cols_here = (col_end - col0 < BN) ? col_end - col0 : BN;
     const __amdgpu_buffer_rsrc_t rsB = (BSRC != BSRC_PLAIN)
         ? make_rsrc(g.B, (unsigned)g.b_bytes)
         : make_rsrc(g.B + (long)col0 * g.ldb, (unsigned)((long)(cols_here - 1) * g.ldb + (long)g.kchunks * 16));
@@ -796,7 +807,7 @@ igemm_kernel(const IgemmArgs g)
             } else {
                 cbase = (unsigned)col;
             }
-            const bool col_ok = col < g.cols;
+            const bool col_ok = col < col_end;
             elem_t col_fix = 0;
             if (DT == DT_U8A && col_ok && blockIdx.z == 0) col_fix = (elem_t)g.bias[col];
 #pragma unroll
@@ -818,7 +829,7 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = col0 + wn * C::WTN + j * MF + lrow;
-            if (col >= g.cols) continue;
+            if (col >= col_end) continue;
             long cbase;
             if (CONV) {
                 int n = (g.cols > g.cols_per_img) ? div_any(col, g.cols_per_img) : 0;

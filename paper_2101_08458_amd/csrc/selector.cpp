@@ -41,6 +41,8 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
             const TileCfg &c = g_tiles[t];
             long nt = (long)cdiv(rows, c.bm) * cdiv(cols, c.bn);
             double fill = (double)rows * cols / ((double)nt * c.bm * c.bn);
+            // the 256x256 tile's prologue and epilogue only amortise over a long reduction
+            if (t == 0 && kchunks < 32) continue;
             if (nt >= CUS * 3 / 4 && fill >= 0.6) { tile = t; break; }
         }
         // Few output rows (<= 64 channels) but very many columns (network stems and first

@@ -169,9 +169,9 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
 bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requant *rq)
 {
     const long px = (long)d->d * d->h * d->w;      // pixels per image
-    // one image: channel rows must be 4-byte aligned; several: every 16-byte chunk of pixels
-    // must stay inside one image
-    const bool rows_ok = (d->n == 1) ? (px * elem_size(dtype)) % 4 == 0 : px % chunk_elems(dtype) == 0;
+    // channel rows must be 4-byte aligned; with several images whose pixel count is not a whole
+    // number of 16-byte chunks the columns are tiled per image (conv_packed sets per_img)
+    const bool rows_ok = (px * elem_size(dtype)) % 4 == 0;
     return d->t == 1 && d->r == 1 && d->s == 1 &&
            d->stride_d == 1 && d->stride_h == 1 && d->stride_w == 1 &&
            d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr && rows_ok && dtype != UNIT_U8I8 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
@@ -220,6 +220,7 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
     a.P = g.p;  a.Q = g.q;  a.PQ = g.o * g.p * g.q;
     a.b_bytes = nchw_direct ? (long)d->n * d->c * d->d * d->h * d->w * es : (long)d->n * d->d * d->h * d->w * g.cp * es;
     a.Cin = d->c;
+    a.per_img = (bsrc == BSRC_NCHW && d->n > 1 && ((long)d->d * d->h * d->w) % chunk_elems(dtype) != 0) ? 1 : 0;
     a.T = d->t;  a.R = d->r;  a.S = d->s;
     a.sd = d->stride_d;  a.sh = d->stride_h;  a.sw = d->stride_w;  a.pd = d->pad_d;  a.ph = d->pad_h;  a.pw = d->pad_w;
     a.out = y_raw;  a.row_stride = a.PQ;  a.img_stride = (long)d->k * a.PQ;  a.cols_per_img = a.PQ;

@@ -118,6 +118,8 @@ def test_input_mode_decisions_are_host_logic(lib):
     P, D, S = unit.UNIT_INPUT_PACKED, unit.UNIT_INPUT_DIRECT, unit.UNIT_INPUT_DIRECT_SHIFTED
     assert mode(1, 64, 56, 56, 256, 1, 1, 1, 0) == D              # aligned 1x1
     assert mode(16, 64, 56, 56, 256, 1, 1, 1, 0, dtype=unit.UNIT_F16) == D   # batches: whole chunks per image
+    assert mode(16, 256, 14, 14, 1024, 1, 1, 1, 0, dtype=unit.UNIT_F16) == D  # batches: columns tiled per image
+    assert mode(16, 512, 7, 7, 2048, 1, 1, 1, 0) == P             # batches of 49-byte rows: unaligned
     assert mode(1, 512, 7, 7, 2048, 1, 1, 1, 0) == S              # 49-byte rows
     assert mode(1, 256, 14, 14, 256, 3, 3, 1, 1) == S             # 3x3, same padding
     assert mode(1, 128, 11, 10, 33, 5, 5, 1, 2) == S

@@ -209,7 +209,10 @@ NCHW_DIRECT = [   # 1x1 / stride 1: read straight from NCHW when the channel row
     (wl.ConvShape(130, 7, 7, 64, 1, 1, 1, 0), 1),      # 49 pixels: falls back to pack + gather
     (wl.ConvShape(24, 8, 8, 40, 1, 1, 1, 0), 3),       # several images, 64 pixels each: direct
     (wl.ConvShape(72, 12, 4, 96, 1, 1, 1, 0), 5),      # 48 pixels per image: direct, tiles straddle images
-    (wl.ConvShape(16, 14, 14, 24, 1, 1, 1, 0), 2),     # 196 pixels per image, n > 1: falls back
+    (wl.ConvShape(16, 14, 14, 24, 1, 1, 1, 0), 2),     # 196 pixels per image, n > 1: columns tiled per image
+    (wl.ConvShape(40, 6, 6, 24, 1, 1, 1, 0), 5),       # 36 pixels per image: per-image tiles, mostly empty
+    (wl.ConvShape(256, 14, 14, 70, 1, 1, 1, 0), 3),    # several reduction steps, per-image tiles
+    (wl.ConvShape(32, 5, 10, 16, 1, 1, 1, 0), 4),      # 50 pixels: int8 rows unaligned (packs), fp16 rows aligned (direct)
 ]
 
 
