@@ -8,9 +8,12 @@ namespace unit {
 // NCHW -> [n][h*w][cp] with cp = channels padded to 16 bytes (zero filled): the graph
 // level layout change of the paper (Section V-C; Section II-C.1 for the padding) done as
 // one tiled transpose through LDS.  T = int8_t (16 channels per chunk) or uint16_t (8).
+// With Q > 0 only the pixels (p*srow_step, q*scol_step) of each input image are packed
+// (HW = P*Q output pixels, HWin = pixels per input channel): the input of a strided 1x1 conv.
 template <typename T>
 __global__ void __launch_bounds__(256)
-pack_act_kernel(const T *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW, int cp)
+pack_act_kernel(const T *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW, int cp,
+                int HWin, int Q, int srow, int scol)
 {
     constexpr int CH = 16 / sizeof(T);            // channels per 16-byte chunk
     constexpr int TP = 64;                        // pixels per tile
@@ -18,14 +21,19 @@ pack_act_kernel(const T *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW
     __shared__ T tile[TC][TP + 4 / sizeof(T)];
     const int tid = threadIdx.x;
     const int hw0 = blockIdx.x * TP, c0 = blockIdx.y * TC, n = blockIdx.z;
-    const T *xn = x + (long)n * C * HW;
+    const T *xn = x + (long)n * C * HWin;
     {
         const int px = tid & 63;
+        int src = hw0 + px;
+        if (Q > 0) {                               // subsampled source pixel
+            const int p = src / Q;
+            src = p * srow + (src - p * Q) * scol;
+        }
 #pragma unroll
         for (int i = 0; i < TC / 4; ++i) {
             int c = (tid >> 6) + 4 * i;
             T v = 0;
-            if (c0 + c < C && hw0 + px < HW) v = xn[(long)(c0 + c) * HW + hw0 + px];
+            if (c0 + c < C && hw0 + px < HW) v = xn[(long)(c0 + c) * HWin + src];
             tile[c][px] = v;
         }
     }
@@ -44,21 +52,30 @@ pack_act_kernel(const T *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW
     }
 }
 
-hipError_t launch_pack_act(int dtype, int n, int c, int h, int w, const void *x, void *xp, hipStream_t st)
+// sh, sw > 1 with p, q > 0: pack only the pixels (i*sh, j*sw), i < p, j < q (output [n][p*q][cp])
+hipError_t launch_pack_act_sub(int dtype, int n, int c, int h, int w, int sh, int sw, int p, int q,
+                               const void *x, void *xp, hipStream_t st)
 {
-    const int hw = h * w;
+    const bool sub = p > 0;
+    const int hw_in = h * w, hw = sub ? p * q : hw_in;
+    const int Q = sub ? q : 0, srow = sh * w, scol = sw;
     if (dtype == DT_I8) {   // callers pass the storage type: one- or two-byte elements
         const int cp = (c + 15) / 16 * 16;
         dim3 grid((hw + 63) / 64, (cp + 63) / 64, n);
         hipLaunchKernelGGL(pack_act_kernel<int8_t>, grid, dim3(256), 0, st,
-                           (const int8_t *)x, (uint8_t *)xp, c, hw, cp);
+                           (const int8_t *)x, (uint8_t *)xp, c, hw, cp, hw_in, Q, srow, scol);
     } else {
         const int cp = (c + 7) / 8 * 8;
         dim3 grid((hw + 63) / 64, (cp + 63) / 64, n);
         hipLaunchKernelGGL(pack_act_kernel<uint16_t>, grid, dim3(256), 0, st,
-                           (const uint16_t *)x, (uint8_t *)xp, c, hw, cp);
+                           (const uint16_t *)x, (uint8_t *)xp, c, hw, cp, hw_in, Q, srow, scol);
     }
     return hipGetLastError();
+}
+
+hipError_t launch_pack_act(int dtype, int n, int c, int h, int w, const void *x, void *xp, hipStream_t st)
+{
+    return launch_pack_act_sub(dtype, n, c, h, w, 1, 1, 0, 0, x, xp, st);
 }
 
 // packed int8 [n][hw][cp] -> NCHW

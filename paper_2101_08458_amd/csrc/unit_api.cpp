@@ -330,6 +330,17 @@ int conv_wpacked(const ConvND *d, int dtype, const void *x, const void *wp,
     size_t act_b = packed_act_bytes_nd(d, dtype);
     if (!ws || ws_bytes < act_b + split_b) return UNIT_EWORKSPACE;
     uint8_t *xp = static_cast<uint8_t *>(ws);
+    // A strided 1x1 conv reads one pixel in stride_h*stride_w: pack only those and run the
+    // unit-stride 1x1 conv on the subsampled tensor (same reduction, same output).
+    if (d->d == 1 && d->t == 1 && d->r == 1 && d->s == 1 && d->pad_h == 0 && d->pad_w == 0 &&
+        (d->stride_h > 1 || d->stride_w > 1)) {
+        ConvND sub = *d;
+        sub.h = g.p;  sub.w = g.q;  sub.stride_h = sub.stride_w = 1;
+        UNIT_HIP(launch_pack_act_sub(storage_dtype(dtype), d->n, d->c, d->h, d->w, d->stride_h, d->stride_w,
+                                     g.p, g.q, x, xp, static_cast<hipStream_t>(stream)));
+        return conv_packed(&sub, dtype, xp, wp, y_raw, rq, y_i8, nullptr, split_b ? xp + act_b : nullptr, split_b,
+                           stream, BSRC_GATHER, fix);
+    }
     UNIT_HIP(launch_pack_act(storage_dtype(dtype), d->n, d->c, d->d * d->h, d->w, x, xp, static_cast<hipStream_t>(stream)));
     return conv_packed(d, dtype, xp, wp, y_raw, rq, y_i8, nullptr, split_b ? xp + act_b : nullptr, split_b, stream,
                        BSRC_GATHER, fix);

@@ -36,6 +36,8 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
 hipError_t launch_igemm(int dtype, int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);
 
 hipError_t launch_pack_act(int dtype, int n, int c, int h, int w, const void *x, void *xp, hipStream_t st);
+hipError_t launch_pack_act_sub(int dtype, int n, int c, int h, int w, int sh, int sw, int p, int q,
+                               const void *x, void *xp, hipStream_t st);
 hipError_t launch_pack_weights(int dtype, int k, int c, int r, int s, const void *w, void *wp, hipStream_t st);
 hipError_t launch_unpack_act_i8(int n, int c, int h, int w, const void *xp, int8_t *x, hipStream_t st);
 hipError_t launch_pad_rows(const void *src, long ld_bytes, int rows, int row_bytes,

@@ -157,3 +157,27 @@ def test_shifted_direct_odd_geometries():
                 unit.unit_conv2d_i8(d, xd, dev(wt), y, None, None, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_I8)))
                 torch.cuda.synchronize()
             assert same(host(y), ref, f"geometry {i} tile {tile}")
+
+
+def test_strided_1x1_packs_only_the_pixels_it_reads():
+    """1x1 convs with stride > 1 run as unit-stride convs on a subsampled packed tensor."""
+    geoms = [(3, 70, 13, 9, 40, 2, 2), (2, 24, 8, 11, 17, 2, 3), (1, 130, 7, 7, 64, 3, 1), (4, 16, 5, 6, 8, 1, 2)]
+    for i, (n, c, h, w, k, sh, sw) in enumerate(geoms):
+        d = unit.conv_desc(n, c, h, w, k, 1, 1, (sh, sw), (0, 0))
+        g = wl.rng(64, i)
+        x = wl.int8_activations(g, (n, c, h, w))
+        wt = wl.int8_weights(g, (k, c, 1, 1))
+        ref = oracle.conv2d_i8(x, wt, (sh, sw), (0, 0))
+        xh = wl.f16_activations(g, (n, c, h, w))
+        wh = wl.f16_weights(g, (k, c, 1, 1), c)
+        refh = oracle.conv2d_f16(xh, wh, (sh, sw), (0, 0))
+        for tile, split in [(None, None), (3, 2), (4, 1), (1, 1)]:
+            announce("strided 1x1", (n, c, h, w, k, sh, sw), "tile", tile, "split", split)
+            with forced(tile=tile, split=split):
+                y = torch.full(ref.shape, -7, dtype=torch.int32, device="cuda:0")
+                unit.unit_conv2d_i8(d, dev(x), dev(wt), y, None, None, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_I8)))
+                yh = torch.empty(ref.shape, dtype=torch.float32, device="cuda:0")
+                unit.unit_conv2d_f16(d, dev(xh), dev(wh), yh, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_F16)))
+                torch.cuda.synchronize()
+            assert same(host(y), ref, f"geometry {i} tile {tile}")
+            assert f16_rel_err(host(yh), refh, c) <= 1e-3, (i, tile)
