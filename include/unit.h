@@ -185,6 +185,8 @@ int unit_unpack_act_i8(int32_t n, int32_t c, int32_t h, int32_t w, const void *x
  *   y_i8     NKPQ int8 requantised            (needs rq)
  *   y_packed [n][p][q][kp] int8 requantised, kp = k rounded up to 16: the next layer's
  *            packed input; its padding channels are written as 0   (needs rq)
+ * x_packed, w_packed and y_packed must be 16-byte aligned (UNIT_EINVAL otherwise): packed
+ * operands are read in 16-byte chunks and y_packed is written four channels per store.
  */
 int unit_conv2d_packed_i8(const unit_conv2d_desc *d, const void *x_packed, const void *w_packed,
                           int32_t *y_i32, const unit_requant *rq, int8_t *y_i8, void *y_packed,

@@ -839,22 +839,29 @@ igemm_kernel(const IgemmArgs g)
             }
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
+                // accumulator elements 4a..4a+3 of a lane are four consecutive output channels of its
+                // pixel: their int8 results leave as one 32-bit store into the packed (NHWC) output
+                // (padding channels beyond the real ones stay zero)
 #pragma unroll
-                for (int e = 0; e < M::NACC; ++e) {
-                    const int row = row0 + wm * C::WTM + i * MF + acc_row<MF>(e, lane);
-                    if (row >= g.rows) {
-                        // padding channels of a packed int8 output are defined to be zero
-                        if (g.out_packed && row < g.packed_ld) g.out_packed[(long)col * g.packed_ld + row] = 0;
-                        continue;
+                for (int a4 = 0; a4 < M::NACC / 4; ++a4) {
+                    const int rbase = row0 + wm * C::WTM + i * MF + acc_row<MF>(4 * a4, lane);
+                    unsigned four = 0;
+#pragma unroll
+                    for (int b = 0; b < 4; ++b) {
+                        const int e = 4 * a4 + b;
+                        const int row = rbase + b;
+                        if (row >= g.rows) continue;
+                        const long addr = cbase + (long)row * g.row_stride;
+                        int t = (int)acc[i][j][e];
+                        if (g.store_raw) out[addr] = acc[i][j][e];
+                        if (g.bias) t += g.bias[row];
+                        if (g.residual) t += g.residual[addr];
+                        const int v = requant_elem(t, g.scale[row], g.relu);
+                        if (g.out_i8) g.out_i8[addr] = (int8_t)v;
+                        four |= ((unsigned)v & 0xffu) << (8 * b);
                     }
-                    const long addr = cbase + (long)row * g.row_stride;
-                    int t = (int)acc[i][j][e];
-                    if (g.store_raw) out[addr] = acc[i][j][e];
-                    if (g.bias) t += g.bias[row];
-                    if (g.residual) t += g.residual[addr];
-                    int v = requant_elem(t, g.scale[row], g.relu);
-                    if (g.out_i8) g.out_i8[addr] = (int8_t)v;
-                    if (g.out_packed) g.out_packed[(long)col * g.packed_ld + row] = (int8_t)v;
+                    if (g.out_packed && rbase < g.packed_ld)
+                        *reinterpret_cast<unsigned *>(g.out_packed + (long)col * g.packed_ld + rbase) = four;
                 }
             }
         }

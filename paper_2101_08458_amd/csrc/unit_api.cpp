@@ -208,6 +208,7 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
         if (!y_raw || y_i8 || y_packed) return UNIT_EINVAL;
     }
     if (ws && !aligned256(ws)) return UNIT_EINVAL;
+    if (y_packed && !aligned16(y_packed)) return UNIT_EINVAL;     // written with 32-bit stores, read back as 16-byte chunks
     if ((dtype == UNIT_U8I8) != (fix != nullptr)) return UNIT_EINVAL;
 
     IgemmArgs a;
