@@ -64,15 +64,22 @@ typedef struct unit_conv2d_desc {
 /*
  * Fused epilogue back to int8 (the quantised-inference use the paper targets,
  * Section II-A, Section V-C):
- *   t = acc + bias[k] + residual[n,k,p,q]           (int32; caller keeps |t| < 2^31)
+ *   t = acc + bias[k] + residual[n,k,p,q] + residual_mult * residual_packed[n,p,q,k]
+ *                                                    (int32; caller keeps |t| < 2^31)
  *   g = (float)t * scale[k]                          (RNE conversion, one fp32 multiply)
  *   i = round-half-to-even(g); if relu: i = max(i,0); clamp to [-128,127]
+ * The packed residual is the skip connection of a quantised residual block taken straight
+ * from the int8 activations an earlier layer wrote (y_packed layout of this layer's output,
+ * 16-byte aligned), rescaled by an integer; either residual form may be NULL, both may be given.
  */
 typedef struct unit_requant {
-    const float   *scale;      /* device [k]; finite                    */
-    const int32_t *bias;       /* device [k] or NULL                    */
-    const int32_t *residual;   /* device [n,k,p,q] int32 (NCHW) or NULL */
-    int32_t        relu;       /* 0 or 1                                */
+    const float   *scale;            /* device [k]; finite                              */
+    const int32_t *bias;             /* device [k] or NULL                              */
+    const int32_t *residual;         /* device [n,k,p,q] int32 (NCHW) or NULL           */
+    int32_t        relu;             /* 0 or 1                                          */
+    int32_t        residual_mult;    /* multiplier of residual_packed                   */
+    const void    *residual_packed;  /* device [n][p][q][kp] int8, kp = k rounded up to
+                                        16, or NULL                                     */
 } unit_requant;
 
 /* Tile choice made by the selector for one problem (introspection / reports). */

@@ -69,6 +69,7 @@ struct IgemmArgs {
     // fused epilogue (EPI_REQUANT): int8 results
     int epi;
     const float *scale;  const int32_t *bias;  const int32_t *residual;  int relu;
+    const int8_t *res_packed;  int res_mult;        // int8 residual [col][packed_ld] times res_mult, or NULL
     int8_t *out_i8;                                 // same indexing as out, or NULL
     int8_t *out_packed;  int packed_ld;             // [col][packed_ld] int8, or NULL
     int store_raw;                                  // also store raw accumulators to out
@@ -845,7 +846,9 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
                 for (int a4 = 0; a4 < M::NACC / 4; ++a4) {
                     const int rbase = row0 + wm * C::WTM + i * MF + acc_row<MF>(4 * a4, lane);
-                    unsigned four = 0;
+                    unsigned four = 0, res4 = 0;
+                    if (g.res_packed && rbase < g.packed_ld)
+                        res4 = *reinterpret_cast<const unsigned *>(g.res_packed + (long)col * g.packed_ld + rbase);
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const int e = 4 * a4 + b;
@@ -856,6 +859,7 @@ igemm_kernel(const IgemmArgs g)
                         if (g.store_raw) out[addr] = acc[i][j][e];
                         if (g.bias) t += g.bias[row];
                         if (g.residual) t += g.residual[addr];
+                        t += (int)(int8_t)(res4 >> (8 * b)) * g.res_mult;
                         const int v = requant_elem(t, g.scale[row], g.relu);
                         if (g.out_i8) g.out_i8[addr] = (int8_t)v;
                         four |= ((unsigned)v & 0xffu) << (8 * b);

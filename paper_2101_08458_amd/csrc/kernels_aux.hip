@@ -172,6 +172,7 @@ __device__ __forceinline__ void reduce_epilogue(const ReduceArgs &a, long i, E s
         int t = (int)sum;
         if (a.bias) t += a.bias[k];
         if (a.residual) t += a.residual[i];
+        if (a.res_packed) t += (int)a.res_packed[(n * a.PQ + px) * a.packed_ld + k] * a.res_mult;
         int v = requant_elem(t, a.scale[k], a.relu);
         if (a.out_i8) a.out_i8[i] = (int8_t)v;
         if (a.out_packed) a.out_packed[(n * a.PQ + px) * a.packed_ld + k] = (int8_t)v;
@@ -318,26 +319,47 @@ hipError_t launch_maxpool_packed_i8(int n, int cp, int h, int w, int window, int
     return hipGetLastError();
 }
 
-// global average pool: integer sum then requantise; one thread per (n, channel)
-__global__ void avgpool_packed_i8_kernel(const int8_t *__restrict__ x, const float *__restrict__ scale,
-                                         int8_t *__restrict__ y, int C, int cp, int HW, long total)
+// global average pool: integer sum then requantise.  One workgroup per (image, 64 channels):
+// thread = (pixel slice, channel quad); every thread sums its slice of the pixels with 32-bit
+// loads of four channels, the 16 slices are added through LDS, and 64 threads requantise.
+__global__ void __launch_bounds__(256)
+avgpool_packed_i8_kernel(const int8_t *__restrict__ x, const float *__restrict__ scale,
+                         int8_t *__restrict__ y, int C, int cp, int HW, int groups)
 {
-    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= total) return;
-    int c = i % cp;
-    long n = i / cp;
-    if (c >= C) { y[i] = 0; return; }
-    int sum = 0;
-    for (int px = 0; px < HW; ++px) sum += (int)x[(n * HW + px) * cp + c];
-    y[i] = (int8_t)requant_elem(sum, scale[c], 0);
+    __shared__ int part[16][64];
+    const int quad = threadIdx.x & 15, slice = threadIdx.x >> 4;
+    const int grp = blockIdx.x % groups;
+    const long n = blockIdx.x / groups;
+    const int c0 = (grp * 16 + quad) * 4;               // first of this thread's four channels
+    int s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+    if (c0 < cp) {
+        const int8_t *px = x + (n * HW + slice) * (long)cp + c0;
+        for (int i = slice; i < HW; i += 16, px += 16L * cp) {
+            const unsigned v = *reinterpret_cast<const unsigned *>(px);
+            s0 += (int)(int8_t)v;  s1 += (int)(int8_t)(v >> 8);
+            s2 += (int)(int8_t)(v >> 16);  s3 += (int)(int8_t)(v >> 24);
+        }
+    }
+    part[slice][quad * 4 + 0] = s0;  part[slice][quad * 4 + 1] = s1;
+    part[slice][quad * 4 + 2] = s2;  part[slice][quad * 4 + 3] = s3;
+    __syncthreads();
+    if (threadIdx.x < 64) {
+        const int c = grp * 64 + threadIdx.x;
+        if (c < cp) {
+            int sum = 0;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) sum += part[t][threadIdx.x];
+            y[n * cp + c] = c < C ? (int8_t)requant_elem(sum, scale[c], 0) : (int8_t)0;
+        }
+    }
 }
 
 hipError_t launch_avgpool_packed_i8(int n, int c, int cp, int hw, const void *x, const float *scale,
                                     int8_t *y, hipStream_t st)
 {
-    long total = (long)n * cp;
-    hipLaunchKernelGGL(avgpool_packed_i8_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       (const int8_t *)x, scale, y, c, cp, hw, total);
+    const int groups = (cp + 63) / 64;
+    hipLaunchKernelGGL(avgpool_packed_i8_kernel, dim3((unsigned)((long)n * groups)), dim3(256), 0, st,
+                       (const int8_t *)x, scale, y, c, cp, hw, groups);
     return hipGetLastError();
 }
 

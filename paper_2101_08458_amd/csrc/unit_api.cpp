@@ -158,6 +158,7 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
     r.total = out_elems;  r.K = K;  r.PQ = PQ;
     r.out = (a.epi == EPI_RAW || a.store_raw) ? a.out : nullptr;
     r.epi = a.epi;  r.scale = a.scale;  r.bias = a.bias;  r.residual = a.residual;  r.relu = a.relu;
+    r.res_packed = a.res_packed;  r.res_mult = a.res_mult;
     r.out_i8 = a.out_i8;  r.out_packed = a.out_packed;  r.packed_ld = a.packed_ld;
     UNIT_HIP(launch_splitk_reduce(r, st));
     return UNIT_OK;
@@ -204,6 +205,7 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
     if (!aligned16(xp) || !aligned16(wp)) return UNIT_EINVAL;
     if (rq) {
         if (dtype != UNIT_I8 || !rq->scale || (!y_i8 && !y_packed)) return UNIT_EINVAL;
+        if (rq->residual_packed && !aligned16(rq->residual_packed)) return UNIT_EINVAL;
     } else {
         if (!y_raw || y_i8 || y_packed) return UNIT_EINVAL;
     }
@@ -228,6 +230,8 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
     if (rq) {
         a.epi = EPI_REQUANT;  a.scale = rq->scale;  a.bias = rq->bias;  a.residual = rq->residual;
         a.relu = rq->relu ? 1 : 0;
+        a.res_packed = static_cast<const int8_t *>(rq->residual_packed);
+        a.res_mult = rq->residual_packed ? rq->residual_mult : 0;
         a.out_i8 = y_i8;  a.out_packed = static_cast<int8_t *>(y_packed);
         a.packed_ld = pad_channels(d->k, UNIT_I8);
         a.store_raw = y_raw ? 1 : 0;
@@ -697,6 +701,7 @@ int unit_global_avgpool_packed_i8(int32_t n, int32_t c, int32_t h, int32_t w,
                                   const void *xp, const float *scale, int8_t *y, void *stream)
 {
     if (n <= 0 || c <= 0 || h <= 0 || w <= 0 || !xp || !scale || !y) return UNIT_EINVAL;
+    if (!aligned16(xp)) return UNIT_EINVAL;
     if ((long)h * w > 16777216L) return UNIT_EOVERFLOW;
     UNIT_HIP(launch_avgpool_packed_i8(n, c, pad_channels(c, UNIT_I8), h * w, xp, scale, y,
                                       static_cast<hipStream_t>(stream)));

@@ -53,6 +53,7 @@ struct ReduceArgs {
     int K, PQ;                                                   // channel = (idx / PQ) % K
     void *out;                                                   // int32 / float or NULL
     int epi;  const float *scale;  const int32_t *bias;  const int32_t *residual;  int relu;
+    const int8_t *res_packed;  int res_mult;                     // [n*pq][packed_ld] int8 residual, or NULL
     int8_t *out_i8;  int8_t *out_packed;  int packed_ld;
 };
 hipError_t launch_splitk_reduce(const ReduceArgs &a, hipStream_t st);

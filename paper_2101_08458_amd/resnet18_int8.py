@@ -1,14 +1,14 @@
 """Chained int8 inference of a ResNet-18-shaped network on libunit.
 
 Orchestration only: every operator is one call into the C library (conv with the fused
-requantise + ReLU epilogue writing the next layer's packed input, max-pool, residual
-widening, global average pool, and the int8 fully connected layer as a matmul).  The
+requantise + ReLU epilogue writing the next layer's packed input, max-pool, global average
+pool, and the int8 fully connected layer as a matmul).  The
 weights, biases, per-channel scales and residual multipliers are inputs; the harness that
 calibrates them is not part of this module.
 
 Block wiring:  a = relu_rq(conv1(x));  y = relu_rq(conv2(a) + residual), where residual is
 the raw int32 accumulator of the 1x1 projection, or int32(x) * res_mult for an identity
-shortcut.
+shortcut (read by conv2's epilogue straight from x's packed int8 form).
 """
 import numpy as np
 
@@ -87,15 +87,16 @@ class ResNet18Int8:
             p, q = wl.out_hw(c1)
             self.act_a.append(packed(c1.k, p, q))
             self.act_y.append(packed(c2.k, p, q))
-            self.res.append(torch.empty((batch, c2.k, p, q), dtype=torch.int32, device=device))
+            self.res.append(torch.empty((batch, c2.k, p, q), dtype=torch.int32, device=device)
+                            if proj is not None else None)
         self.pooled = torch.empty((batch, 512), dtype=torch.int8, device=device)
         self.logits = torch.empty((batch, 1000), dtype=torch.int32, device=device)
 
-    def _conv(self, name, xin, y_packed, relu, residual=None, y_i32=None):
+    def _conv(self, name, xin, y_packed, relu, residual=None, y_i32=None, skip=None, skip_mult=0):
         L = self.layers[name]
         rq = None
         if y_packed is not None:
-            rq = unit.make_requant(L["scale"], L["bias"], residual, relu)
+            rq = unit.make_requant(L["scale"], L["bias"], residual, relu, skip, skip_mult)
         unit.unit_conv2d_packed_i8(L["d"], xin, L["wp"], y_i32, rq, None, y_packed, self.ws)
 
     def forward(self, x_nchw):
@@ -110,9 +111,10 @@ class ResNet18Int8:
             self._conv(f"b{i}.c1", x, self.act_a[i], relu=True)
             if proj is not None:
                 self._conv(f"b{i}.proj", x, None, relu=False, y_i32=self.res[i])
+                self._conv(f"b{i}.c2", self.act_a[i], self.act_y[i], relu=True, residual=self.res[i])
             else:
-                unit.unit_widen_residual_i8(n, c1.c, c1.h, c1.w, x, self.res_mult[i], self.res[i])
-            self._conv(f"b{i}.c2", self.act_a[i], self.act_y[i], relu=True, residual=self.res[i])
+                self._conv(f"b{i}.c2", self.act_a[i], self.act_y[i], relu=True,
+                           skip=x, skip_mult=self.res_mult[i])
             x = self.act_y[i]
         unit.unit_global_avgpool_packed_i8(n, 512, 7, 7, x, self.pool_scale, self.pooled)
         unit.unit_matmul_i8(n, 1000, 512, self.pooled, 512, self.fc_w, 512, self.logits, 1000, self.ws)

@@ -31,7 +31,8 @@ class unit_conv3d_desc(ctypes.Structure):
 
 class unit_requant(ctypes.Structure):
     _fields_ = [("scale", ctypes.c_void_p), ("bias", ctypes.c_void_p),
-                ("residual", ctypes.c_void_p), ("relu", ctypes.c_int32)]
+                ("residual", ctypes.c_void_p), ("relu", ctypes.c_int32),
+                ("residual_mult", ctypes.c_int32), ("residual_packed", ctypes.c_void_p)]
 
 
 class unit_tile_info(ctypes.Structure):
@@ -183,8 +184,9 @@ def conv_desc(n, c, h, w, k, r, s, stride=(1, 1), pad=(0, 0)):
     return unit_conv2d_desc(n, c, h, w, k, r, s, sh, sw, ph, pw)
 
 
-def make_requant(scale, bias=None, residual=None, relu=False):
-    return unit_requant(_p(scale), _p(bias), _p(residual), int(bool(relu)))
+def make_requant(scale, bias=None, residual=None, relu=False, residual_packed=None, residual_mult=0):
+    return unit_requant(_p(scale), _p(bias), _p(residual), int(bool(relu)),
+                        int(residual_mult), _p(residual_packed))
 
 
 # ------------------------------------------------------------------ entry points (same names as the C ABI)

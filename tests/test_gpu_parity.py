@@ -390,11 +390,23 @@ def test_requant_epilogue_all_paths():
         unit.unit_pack_weights_i8(d, dev(w), wp)
         sd, bd, rd = dev(scale), dev(bias), dev(res)
         kp = (sh.k + 15) // 16 * 16
-        for use_bias, use_res, relu in [(0, 0, 0), (1, 0, 1), (0, 1, 1), (1, 1, 0), (1, 1, 1)]:
-            exp = oracle.requant(acc, scale, bias if use_bias else None, res if use_res else None, relu)
-            rq = unit.make_requant(sd, bd if use_bias else None, rd if use_res else None, relu)
+        # skip connection in the packed int8 form an earlier layer would have written
+        skip = wl.int8_weights(g, acc.shape)
+        skip_mult = 217
+        skp = ws_bytes(unit.unit_packed_act_bytes(n, sh.k, p, q, unit.UNIT_I8))
+        unit.unit_pack_act_i8(n, sh.k, p, q, dev(skip), skp)
+        for use_bias, use_res, relu, use_skip in [(0, 0, 0, 0), (1, 0, 1, 0), (0, 1, 1, 0), (1, 1, 0, 0), (1, 1, 1, 0),
+                                                  (1, 0, 1, 1), (0, 1, 0, 1)]:
+            total_res = None
+            if use_res or use_skip:
+                total_res = (res if use_res else 0) + (skip.astype(np.int32) * skip_mult if use_skip else 0)
+                total_res = np.ascontiguousarray(total_res, dtype=np.int32)
+            exp = oracle.requant(acc, scale, bias if use_bias else None, total_res, relu)
+            rq = unit.make_requant(sd, bd if use_bias else None, rd if use_res else None, relu,
+                                   skp if use_skip else None, skip_mult)
             for tile, split in [(None, None), (2, 1), (2, 2), (3, 1), (4, 3), (5, 1), (1, 1)]:
-                announce("requant", sh, "bias", use_bias, "res", use_res, "relu", relu, "tile", tile, "split", split)
+                announce("requant", sh, "bias", use_bias, "res", use_res, "skip", use_skip, "relu", relu,
+                         "tile", tile, "split", split)
                 y8 = torch.full((n, sh.k, p, q), 99, dtype=torch.int8, device="cuda:0")
                 y32 = torch.full((n, sh.k, p, q), -7, dtype=torch.int32, device="cuda:0")
                 ypk = torch.full((n, p, q, kp), 99, dtype=torch.int8, device="cuda:0")
@@ -467,6 +479,19 @@ def test_pack_roundtrip_and_glue_ops():
     torch.cuda.synchronize()
     assert same(host(ya)[:, :c], oracle.global_sumpool_requant_i8(x, scale))
     assert np.all(host(ya)[:, c:] == 0)
+
+    for n2, c2, h2, w2 in [(3, 150, 7, 7), (1, 512, 7, 7), (2, 70, 1, 1), (1, 16, 20, 21)]:
+        announce("avgpool", n2, c2, h2, w2)       # several channel groups, pixel counts around the 16 slices
+        x2 = wl.int8_weights(g, (n2, c2, h2, w2))
+        xp2 = ws_bytes(unit.unit_packed_act_bytes(n2, c2, h2, w2, unit.UNIT_I8))
+        unit.unit_pack_act_i8(n2, c2, h2, w2, dev(x2), xp2)
+        cp2 = (c2 + 15) // 16 * 16
+        scale2 = g.uniform(0.002, 0.02, c2).astype(np.float32)
+        ya2 = torch.full((n2, cp2), 99, dtype=torch.int8, device="cuda:0")
+        unit.unit_global_avgpool_packed_i8(n2, c2, h2, w2, xp2, dev(scale2), ya2)
+        torch.cuda.synchronize()
+        assert same(host(ya2)[:, :c2], oracle.global_sumpool_requant_i8(x2, scale2))
+        assert np.all(host(ya2)[:, c2:] == 0)
 
     announce("widen residual")
     res = torch.empty((n, c, h, w_), dtype=torch.int32, device="cuda:0")
