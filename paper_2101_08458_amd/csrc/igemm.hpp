@@ -826,41 +826,75 @@ igemm_kernel(const IgemmArgs g)
             }
         }
     } else {
+        // Every load of a sub-tile (scale, bias, both residual forms) is issued before its first
+        // store, through buffer descriptors: absent inputs get an empty range and masked lanes an
+        // offset beyond it, both read as zero, so the loads need no branches and wait only once.
         elem_t *out = reinterpret_cast<elem_t *>(g.out);
+        constexpr int NA = M::NACC;
+        const __amdgpu_buffer_rsrc_t rsS = make_rsrc(g.scale, UNIT_OOB);
+        const __amdgpu_buffer_rsrc_t rsBi = make_rsrc(g.bias, g.bias ? UNIT_OOB : 0u);
+        const __amdgpu_buffer_rsrc_t rsR = make_rsrc(g.residual, g.residual ? UNIT_OOB : 0u);
+        const __amdgpu_buffer_rsrc_t rsP = make_rsrc(g.res_packed, g.res_packed ? UNIT_OOB : 0u);
+        int colv[TN];
+        long cbase[TN];
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = col0 + wn * C::WTN + j * MF + lrow;
-            if (col >= col_end) continue;
-            long cbase;
+            colv[j] = col;
             if (CONV) {
                 int n = (g.cols > g.cols_per_img) ? div_any(col, g.cols_per_img) : 0;
-                cbase = (long)n * g.img_stride + (col - n * g.cols_per_img);
+                cbase[j] = (long)n * g.img_stride + (col - n * g.cols_per_img);
             } else {
-                cbase = col;
+                cbase[j] = col;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < TM; ++i) {
+            const int rtile = row0 + wm * C::WTM + i * MF;
+            float sc[NA];
+            int bi[NA];
+#pragma unroll
+            for (int e = 0; e < NA; ++e) {
+                const int row = rtile + acc_row<MF>(e, lane);
+                const unsigned off = row < g.rows ? (unsigned)row * 4u : UNIT_OOB;
+                sc[e] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsS, off, 0, 0));
+                bi[e] = (int)__builtin_amdgcn_raw_buffer_load_b32(rsBi, off, 0, 0);
             }
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                // accumulator elements 4a..4a+3 of a lane are four consecutive output channels of its
-                // pixel: their int8 results leave as one 32-bit store into the packed (NHWC) output
-                // (padding channels beyond the real ones stay zero)
+            for (int j = 0; j < TN; ++j) {
+                const int col = colv[j];
+                if (col >= col_end) continue;
+                unsigned add[NA];                   // modular sums: the caller bounds only the total
 #pragma unroll
-                for (int a4 = 0; a4 < M::NACC / 4; ++a4) {
-                    const int rbase = row0 + wm * C::WTM + i * MF + acc_row<MF>(4 * a4, lane);
-                    unsigned four = 0, res4 = 0;
-                    if (g.res_packed && rbase < g.packed_ld)
-                        res4 = *reinterpret_cast<const unsigned *>(g.res_packed + (long)col * g.packed_ld + rbase);
+                for (int e = 0; e < NA; ++e) {
+                    const int row = rtile + acc_row<MF>(e, lane);
+                    const unsigned off = row < g.rows ? (unsigned)(cbase[j] + (long)row * g.row_stride) * 4u : UNIT_OOB;
+                    add[e] = (unsigned)bi[e] + __builtin_amdgcn_raw_buffer_load_b32(rsR, off, 0, 0);
+                }
+                // accumulator elements 4a..4a+3 of a lane are four consecutive output channels of its
+                // pixel: the packed residual arrives as one 32-bit load, and the int8 results leave as
+                // one 32-bit store into the packed (NHWC) output (padding channels stay zero)
+                unsigned res4[NA / 4];
+#pragma unroll
+                for (int a4 = 0; a4 < NA / 4; ++a4) {
+                    const int rbase = rtile + acc_row<MF>(4 * a4, lane);
+                    res4[a4] = __builtin_amdgcn_raw_buffer_load_b32(
+                        rsP, rbase < g.packed_ld ? (unsigned)((long)col * g.packed_ld + rbase) : UNIT_OOB, 0, 0);
+                }
+#pragma unroll
+                for (int a4 = 0; a4 < NA / 4; ++a4) {
+                    const int rbase = rtile + acc_row<MF>(4 * a4, lane);
+                    unsigned four = 0;
 #pragma unroll
                     for (int b = 0; b < 4; ++b) {
                         const int e = 4 * a4 + b;
                         const int row = rbase + b;
                         if (row >= g.rows) continue;
-                        const long addr = cbase + (long)row * g.row_stride;
-                        int t = (int)acc[i][j][e];
+                        const long addr = cbase[j] + (long)row * g.row_stride;
+                        const int t = (int)((unsigned)(int)acc[i][j][e] + add[e] +
+                                            (unsigned)((int)(int8_t)(res4[a4] >> (8 * b)) * g.res_mult));
                         if (g.store_raw) out[addr] = acc[i][j][e];
-                        if (g.bias) t += g.bias[row];
-                        if (g.residual) t += g.residual[addr];
-                        t += (int)(int8_t)(res4 >> (8 * b)) * g.res_mult;
-                        const int v = requant_elem(t, g.scale[row], g.relu);
+                        const int v = requant_elem(t, sc[e], g.relu);
                         if (g.out_i8) g.out_i8[addr] = (int8_t)v;
                         four |= ((unsigned)v & 0xffu) << (8 * b);
                     }

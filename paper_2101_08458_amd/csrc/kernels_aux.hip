@@ -160,27 +160,45 @@ hipError_t launch_pad_rows(const void *src, long ld_bytes, int rows, int row_byt
 // are run-to-run identical), then applies the same epilogue as the main kernel.  The
 // split reduction is the paper's "split reduction" tuning step (Section III-C.3) carried
 // across workgroups; the in-group part lives in the main kernel.
-template <typename E>
-__device__ __forceinline__ void reduce_epilogue(const ReduceArgs &a, long i, E sum)
+//
+// NV consecutive outputs starting at i.  All loads of the requantise inputs come before the
+// first store (the stores may alias them as far as the compiler knows).
+template <typename E, int NV>
+__device__ __forceinline__ void reduce_epilogue(const ReduceArgs &a, long i, const E *sum)
 {
-    if (a.out) reinterpret_cast<E *>(a.out)[i] = sum;
+    if (a.out) {
+#pragma unroll
+        for (int e = 0; e < NV; ++e) reinterpret_cast<E *>(a.out)[i + e] = sum[e];
+    }
     if (a.epi == EPI_REQUANT) {
-        int px = i % a.PQ;
-        long nk = i / a.PQ;
-        int k = nk % a.K;
-        long n = nk / a.K;
-        int t = (int)sum;
-        if (a.bias) t += a.bias[k];
-        if (a.residual) t += a.residual[i];
-        if (a.res_packed) t += (int)a.res_packed[(n * a.PQ + px) * a.packed_ld + k] * a.res_mult;
-        int v = requant_elem(t, a.scale[k], a.relu);
-        if (a.out_i8) a.out_i8[i] = (int8_t)v;
-        if (a.out_packed) a.out_packed[(n * a.PQ + px) * a.packed_ld + k] = (int8_t)v;
+        int t[NV];  float sc[NV];  long pk[NV];
+#pragma unroll
+        for (int e = 0; e < NV; ++e) {
+            const long idx = i + e;
+            const int px = idx % a.PQ;
+            const long nk = idx / a.PQ;
+            const int k = nk % a.K;
+            const long n = nk / a.K;
+            pk[e] = (n * a.PQ + px) * a.packed_ld + k;
+            unsigned u = (unsigned)(int)sum[e];
+            if (a.bias) u += (unsigned)a.bias[k];
+            if (a.residual) u += (unsigned)a.residual[idx];
+            if (a.res_packed) u += (unsigned)((int)a.res_packed[pk[e]] * a.res_mult);
+            t[e] = (int)u;
+            sc[e] = a.scale[k];
+        }
+#pragma unroll
+        for (int e = 0; e < NV; ++e) {
+            const int v = requant_elem(t[e], sc[e], a.relu);
+            if (a.out_i8) a.out_i8[i + e] = (int8_t)v;
+            if (a.out_packed) a.out_packed[pk[e]] = (int8_t)v;
+        }
     }
 }
 
-// Each thread owns four consecutive outputs and walks the slices with 16-byte loads, four
-// slices in flight (the slice stride is kept a multiple of four elements by the host).
+// Each thread owns four consecutive outputs and walks the slices with 16-byte loads: the
+// first eight slices in flight at once, further ones four at a time (the slice stride is kept
+// a multiple of four elements by the host).
 template <typename E>
 __global__ void __launch_bounds__(256)
 splitk_reduce_kernel(const ReduceArgs a)
@@ -190,9 +208,18 @@ splitk_reduce_kernel(const ReduceArgs a)
     if (i >= a.total) return;
     const E *p = reinterpret_cast<const E *>(a.partials) + i;
     if (i + 3 < a.total) {
-        v4e sum = *reinterpret_cast<const v4e *>(p);
-        int z = 1;
-        for (; z + 3 < a.nsplit; z += 4) {          // fixed order z = 1, 2, 3, ...: deterministic for fp32
+        v4e head[8];
+#pragma unroll
+        for (int z = 0; z < 8; ++z) {
+            v4e zero = {0, 0, 0, 0};
+            head[z] = z < a.nsplit ? *reinterpret_cast<const v4e *>(p + (long)z * a.split_stride) : zero;
+        }
+        v4e sum = head[0];
+#pragma unroll
+        for (int z = 1; z < 8; ++z)                  // fixed order z = 1, 2, 3, ...: deterministic for fp32
+            if (z < a.nsplit) sum += head[z];
+        int z = 8;
+        for (; z + 3 < a.nsplit; z += 4) {
             v4e t0 = *reinterpret_cast<const v4e *>(p + (long)z * a.split_stride);
             v4e t1 = *reinterpret_cast<const v4e *>(p + (long)(z + 1) * a.split_stride);
             v4e t2 = *reinterpret_cast<const v4e *>(p + (long)(z + 2) * a.split_stride);
@@ -203,14 +230,14 @@ splitk_reduce_kernel(const ReduceArgs a)
         if (a.epi == EPI_RAW && a.out && (i & 3) == 0) {
             *reinterpret_cast<v4e *>(reinterpret_cast<E *>(a.out) + i) = sum;
         } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) reduce_epilogue<E>(a, i + e, sum[e]);
+            E four[4] = {sum[0], sum[1], sum[2], sum[3]};
+            reduce_epilogue<E, 4>(a, i, four);
         }
     } else {
         for (long j = i; j < a.total; ++j) {
             E sum = reinterpret_cast<const E *>(a.partials)[j];
             for (int z = 1; z < a.nsplit; ++z) sum += reinterpret_cast<const E *>(a.partials)[j + (long)z * a.split_stride];
-            reduce_epilogue<E>(a, j, sum);
+            reduce_epilogue<E, 1>(a, j, &sum);
         }
     }
 }
