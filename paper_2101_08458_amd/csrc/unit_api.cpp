@@ -1,6 +1,7 @@
 // C boundary of libunit: argument validation, workspace carving, tile selection and
 // kernel dispatch.  Every error path returns before the first HIP call.
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 
 #include "../../include/unit.h"
@@ -127,6 +128,15 @@ void fill_tile_info(const TileChoice &ch, int dtype, unit_tile_info *out)
     out->mfma = c.mf;     out->split_k = ch.split_k;  out->workgroups = ch.workgroups;
 }
 
+// Steps between the starting points of consecutive workgroups' reduction walks (matrix operands).
+// UNIT_KROT overrides it for experiments (0 switches the rotation off).
+int reduction_rotation()
+{
+    const char *e = std::getenv("UNIT_KROT");
+    if (e && *e) return std::atoi(e) > 0 ? std::atoi(e) : 0;
+    return 0;
+}
+
 // Runs the main kernel (+ the split reduce when the selector splits across workgroups).
 int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
               void *ws, size_t ws_bytes, hipStream_t st, bool allow_split = true)
@@ -134,6 +144,7 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
     const bool conv = bsrc != BSRC_PLAIN;
     TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, bsrc, allow_split);
     a.ksteps_per_split = ch.ksteps_per_split;
+    a.krot = conv ? 0 : reduction_rotation();
     if (ch.split_k == 1) {
         a.split_stride = 0;
         UNIT_HIP(launch_igemm(dtype, bsrc, ch.tile, a, 1, st));
@@ -187,7 +198,8 @@ bool nchw_shift_ok(const ConvND *d, int dtype, const ConvGeom &g, const void *x,
     if (2 * d->pad_h != d->r - 1 || 2 * d->pad_w != d->s - 1) return false;
     if (reinterpret_cast<uintptr_t>(x) & 15) return false;
     TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_NCHWS);
-    if (ch.tile == 0) return false;                               // twice-wide B tile exceeds the LDS
+    const TileCfg &t = g_tiles[ch.tile];
+    if ((long)(t.bm + 2 * t.bn) * t.bkb * t.nst > 160 * 1024) return false;   // twice-wide B tile exceeds the LDS
     return ((long)d->c * elem_size(dtype)) % g_tiles[ch.tile].bkb == 0;
 }
 
