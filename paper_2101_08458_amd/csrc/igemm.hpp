@@ -54,8 +54,6 @@ struct IgemmArgs {
     const uint8_t *B;  long ldb;  int cols;        // plain B: ldb in bytes
     int kchunks;                                    // reduction length in 16-byte chunks
     int ksteps_per_split;                           // main-loop steps per grid.z slice
-    int krot;                                       // matrix operands: workgroup `w` starts its reduction walk at step
-                                                    // (w * krot) % steps and wraps around (0 = every workgroup at step 0)
     // conv gather of B (CONV kernels only): packed activations [n][H][W][CB*16 bytes]
     // (D, T, sd, pd describe the depth axis; conv2d is D = T = 1)
     int D, H, W, CB, P, Q, PQ, T, R, S, sd, sh, sw, pd, ph, pw;
@@ -373,16 +371,8 @@ igemm_kernel(const IgemmArgs g)
             bd0[j] = bh0[j] = bw0[j] = 0;
         }
     }
-    // Matrix operands with a power-of-two row pitch put the same reduction offset of every row on
-    // the same L2 channel; workgroups that walk the reduction in step hit that channel together.
-    // Each workgroup therefore starts at its own step and wraps around (any order gives the same
-    // integer sum; a float sum keeps one fixed order per tile).
-    const int nsteps = ks_end - ks_begin;
-    int krot0 = 0;
-    if (BSRC == BSRC_PLAIN && g.krot > 0 && nsteps > 1) krot0 = (int)(((unsigned)bid * (unsigned)g.krot) % (unsigned)nsteps);
-    int n_issued = 0;
     // conv: reduction chunk kc -> (r, s, channel chunk cb), advanced incrementally per step
-    int kc = (ks_begin + krot0) * NCH + cT;
+    int kc = ks_begin * NCH + cT;
     int ct = 0, cr = 0, cs = 0, ccb = 0;
     const bool uni_tap = (BSRC == BSRC_GATHER) && (g.CB % NCH == 0);
     if (BSRC == BSRC_GATHER && !uni_tap) {
@@ -436,7 +426,7 @@ igemm_kernel(const IgemmArgs g)
 
     // issues the DMA of the next tile (the one whose chunk for this thread is kc) into `stage`
     auto issue_tile = [&](int stage) {
-        const bool kok = (BSRC == BSRC_PLAIN) ? (kc < kend && n_issued < nsteps) : kc < kend;
+        const bool kok = kc < kend;
         const unsigned kbyte = (unsigned)(kc - cT) * 16u;          // = step * BKB
         uint8_t *dst = smem + stage * C::STAGE_BYTES + wave * 1024;
 #pragma unroll
@@ -498,10 +488,12 @@ igemm_kernel(const IgemmArgs g)
                 dma16(rsB, dst + j * NW * 1024, ok ? offB[j] + tap : UNIT_OOB);
             }
             ccb += NCH;
-            while (ccb >= g.CB) {
-                ccb -= g.CB;
-                if (++cs == g.S) {
-                    cs = 0;
+            if (ccb >= g.CB) {                       // whole taps to move on by (several when a pixel
+                const int adv = div_small(ccb, g.CB);  // holds fewer chunks than a step)
+                ccb -= adv * g.CB;
+                cs += adv;
+                while (cs >= g.S) {
+                    cs -= g.S;
                     if (++cr == g.R) { cr = 0; ++ct; }
                 }
             }
@@ -511,10 +503,6 @@ igemm_kernel(const IgemmArgs g)
                 dma16(rsB, dst + j * NW * 1024, kok ? offB[j] + kbyte : UNIT_OOB);
         }
         kc += NCH;
-        if (BSRC == BSRC_PLAIN) {
-            ++n_issued;
-            if (kc - cT >= ks_end * NCH) kc -= nsteps * NCH;       // wrap to the first step of the slice
-        }
     };
 
     // ---- fragment addressing (lane -> row inside an MFMA tile, 16-byte chunk along k)

@@ -128,15 +128,6 @@ void fill_tile_info(const TileChoice &ch, int dtype, unit_tile_info *out)
     out->mfma = c.mf;     out->split_k = ch.split_k;  out->workgroups = ch.workgroups;
 }
 
-// Steps between the starting points of consecutive workgroups' reduction walks (matrix operands).
-// UNIT_KROT overrides it for experiments (0 switches the rotation off).
-int reduction_rotation()
-{
-    const char *e = std::getenv("UNIT_KROT");
-    if (e && *e) return std::atoi(e) > 0 ? std::atoi(e) : 0;
-    return 0;
-}
-
 // Runs the main kernel (+ the split reduce when the selector splits across workgroups).
 int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
               void *ws, size_t ws_bytes, hipStream_t st, bool allow_split = true)
@@ -144,7 +135,6 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
     const bool conv = bsrc != BSRC_PLAIN;
     TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, bsrc, allow_split);
     a.ksteps_per_split = ch.ksteps_per_split;
-    a.krot = conv ? 0 : reduction_rotation();
     if (ch.split_k == 1) {
         a.split_stride = 0;
         UNIT_HIP(launch_igemm(dtype, bsrc, ch.tile, a, 1, st));
