@@ -161,84 +161,73 @@ hipError_t launch_pad_rows(const void *src, long ld_bytes, int rows, int row_byt
 // split reduction is the paper's "split reduction" tuning step (Section III-C.3) carried
 // across workgroups; the in-group part lives in the main kernel.
 //
-// NV consecutive outputs starting at i.  All loads of the requantise inputs come before the
-// first store (the stores may alias them as far as the compiler knows).
-template <typename E, int NV>
-__device__ __forceinline__ void reduce_epilogue(const ReduceArgs &a, long i, const E *sum)
-{
-    if (a.out) {
-#pragma unroll
-        for (int e = 0; e < NV; ++e) reinterpret_cast<E *>(a.out)[i + e] = sum[e];
-    }
-    if (a.epi == EPI_REQUANT) {
-        int t[NV];  float sc[NV];  long pk[NV];
-#pragma unroll
-        for (int e = 0; e < NV; ++e) {
-            const long idx = i + e;
-            const int px = idx % a.PQ;
-            const long nk = idx / a.PQ;
-            const int k = nk % a.K;
-            const long n = nk / a.K;
-            pk[e] = (n * a.PQ + px) * a.packed_ld + k;
-            unsigned u = (unsigned)(int)sum[e];
-            if (a.bias) u += (unsigned)a.bias[k];
-            if (a.residual) u += (unsigned)a.residual[idx];
-            if (a.res_packed) u += (unsigned)((int)a.res_packed[pk[e]] * a.res_mult);
-            t[e] = (int)u;
-            sc[e] = a.scale[k];
-        }
-#pragma unroll
-        for (int e = 0; e < NV; ++e) {
-            const int v = requant_elem(t[e], sc[e], a.relu);
-            if (a.out_i8) a.out_i8[i + e] = (int8_t)v;
-            if (a.out_packed) a.out_packed[pk[e]] = (int8_t)v;
-        }
-    }
-}
-
-// Each thread owns four consecutive outputs and walks the slices with 16-byte loads: the
-// first eight slices in flight at once, further ones four at a time (the slice stride is kept
-// a multiple of four elements by the host).
+// Each thread owns four consecutive outputs (the host keeps every slice a multiple of four
+// elements long, so the 16-byte loads stay inside their slice) and reads the first eight slices
+// at once: a slice index past the last one re-reads the last slice and is not added, which keeps
+// the loads free of branches.  All loads of the requantise inputs go through buffer descriptors
+// (an absent input has an empty range and reads as zero) and come before the first store.
 template <typename E>
 __global__ void __launch_bounds__(256)
 splitk_reduce_kernel(const ReduceArgs a)
 {
     typedef E v4e __attribute__((ext_vector_type(4)));
-    const long i = ((long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-    if (i >= a.total) return;
+    const int total = (int)a.total;                  // < 2^29: the output stays below 2 GiB
+    const int i = (int)(blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= total) return;
     const E *p = reinterpret_cast<const E *>(a.partials) + i;
-    if (i + 3 < a.total) {
-        v4e head[8];
+    const int last = a.nsplit - 1;
+    v4e head[8];
 #pragma unroll
-        for (int z = 0; z < 8; ++z) {
-            v4e zero = {0, 0, 0, 0};
-            head[z] = z < a.nsplit ? *reinterpret_cast<const v4e *>(p + (long)z * a.split_stride) : zero;
-        }
-        v4e sum = head[0];
+    for (int z = 0; z < 8; ++z)
+        head[z] = *reinterpret_cast<const v4e *>(p + (long)(z < last ? z : last) * a.split_stride);
+    v4e sum = head[0];
 #pragma unroll
-        for (int z = 1; z < 8; ++z)                  // fixed order z = 1, 2, 3, ...: deterministic for fp32
-            if (z < a.nsplit) sum += head[z];
-        int z = 8;
-        for (; z + 3 < a.nsplit; z += 4) {
-            v4e t0 = *reinterpret_cast<const v4e *>(p + (long)z * a.split_stride);
-            v4e t1 = *reinterpret_cast<const v4e *>(p + (long)(z + 1) * a.split_stride);
-            v4e t2 = *reinterpret_cast<const v4e *>(p + (long)(z + 2) * a.split_stride);
-            v4e t3 = *reinterpret_cast<const v4e *>(p + (long)(z + 3) * a.split_stride);
-            sum += t0;  sum += t1;  sum += t2;  sum += t3;
-        }
-        for (; z < a.nsplit; ++z) sum += *reinterpret_cast<const v4e *>(p + (long)z * a.split_stride);
-        if (a.epi == EPI_RAW && a.out && (i & 3) == 0) {
-            *reinterpret_cast<v4e *>(reinterpret_cast<E *>(a.out) + i) = sum;
+    for (int z = 1; z < 8; ++z) {                    // fixed order z = 1, 2, 3, ...: deterministic for fp32
+        const v4e zero = {0, 0, 0, 0};
+        sum += (z <= last) ? head[z] : zero;
+    }
+    for (int z = 8; z <= last; ++z) sum += *reinterpret_cast<const v4e *>(p + (long)z * a.split_stride);
+
+    const bool full = i + 3 < total;
+    if (a.out) {
+        E *o = reinterpret_cast<E *>(a.out) + i;
+        if (full) {
+            *reinterpret_cast<v4e *>(o) = sum;       // (a global 16-byte store needs 4-byte alignment only)
         } else {
-            E four[4] = {sum[0], sum[1], sum[2], sum[3]};
-            reduce_epilogue<E, 4>(a, i, four);
+#pragma unroll
+            for (int e = 0; e < 3; ++e)
+                if (i + e < total) o[e] = sum[e];
         }
-    } else {
-        for (long j = i; j < a.total; ++j) {
-            E sum = reinterpret_cast<const E *>(a.partials)[j];
-            for (int z = 1; z < a.nsplit; ++z) sum += reinterpret_cast<const E *>(a.partials)[j + (long)z * a.split_stride];
-            reduce_epilogue<E, 1>(a, j, &sum);
-        }
+    }
+    if (a.epi != EPI_REQUANT) return;
+
+    const __amdgpu_buffer_rsrc_t rsS = make_rsrc(a.scale, UNIT_OOB);
+    const __amdgpu_buffer_rsrc_t rsB = make_rsrc(a.bias, a.bias ? UNIT_OOB : 0u);
+    const __amdgpu_buffer_rsrc_t rsR = make_rsrc(a.residual, a.residual ? UNIT_OOB : 0u);
+    const __amdgpu_buffer_rsrc_t rsP = make_rsrc(a.res_packed, a.res_packed ? UNIT_OOB : 0u);
+    int t[4];  float sc[4];  unsigned pk[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const int idx = (i + e < total) ? i + e : i;              // a lane past the end repeats element i
+        const int nk = div_any(idx, a.PQ);
+        const int px = idx - nk * a.PQ;
+        const int n = div_any(nk, a.K);
+        const int k = nk - n * a.K;
+        pk[e] = (unsigned)((n * a.PQ + px) * a.packed_ld + k);
+        unsigned u = (unsigned)(int)sum[e];
+        u += __builtin_amdgcn_raw_buffer_load_b32(rsB, (unsigned)k * 4u, 0, 0);
+        u += __builtin_amdgcn_raw_buffer_load_b32(rsR, (unsigned)idx * 4u, 0, 0);
+        const int r8 = (int)(int8_t)__builtin_amdgcn_raw_buffer_load_b8(rsP, pk[e], 0, 0);
+        u += (unsigned)(r8 * a.res_mult);
+        t[e] = (int)u;
+        sc[e] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsS, (unsigned)k * 4u, 0, 0));
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        if (i + e >= total) break;
+        const int v = requant_elem(t[e], sc[e], a.relu);
+        if (a.out_i8) a.out_i8[i + e] = (int8_t)v;
+        if (a.out_packed) a.out_packed[pk[e]] = (int8_t)v;
     }
 }
 
