@@ -29,12 +29,20 @@ pack_act_kernel(const T *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW
             const int p = src / Q;
             src = p * srow + (src - p * Q) * scol;
         }
+        // every load is issued before the first LDS store: a masked element reads element 0 of
+        // the image instead of branching around its load, and is zeroed afterwards
+        const bool px_ok = hw0 + px < HW;
+        T v[TC / 4];
 #pragma unroll
         for (int i = 0; i < TC / 4; ++i) {
-            int c = (tid >> 6) + 4 * i;
-            T v = 0;
-            if (c0 + c < C && hw0 + px < HW) v = xn[(long)(c0 + c) * HWin + src];
-            tile[c][px] = v;
+            const int c = (tid >> 6) + 4 * i;
+            const bool ok = px_ok && c0 + c < C;
+            v[i] = xn[ok ? (long)(c0 + c) * HWin + src : 0];
+        }
+#pragma unroll
+        for (int i = 0; i < TC / 4; ++i) {
+            const int c = (tid >> 6) + 4 * i;
+            tile[c][px] = (px_ok && c0 + c < C) ? v[i] : (T)0;
         }
     }
     __syncthreads();
@@ -292,46 +300,83 @@ hipError_t launch_rowsum128_i8(const void *m, long ld, int rows, int chunks, int
 }
 
 // ------------------------------------------------------------------ int8 network glue
-// max-pool on packed int8: one thread per (n, p, q, 16-channel chunk)
-__global__ void maxpool_packed_i8_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y,
-                                         int cp, int H, int W, int P, int Q,
-                                         int window, int stride, int pad, long total)
+// max-pool on packed int8: one thread per (n, p, q, 16-channel chunk).  With a compile-time
+// window (WIN > 0) all window loads are issued at once through a buffer descriptor (taps in the
+// padding get an out-of-range offset and are replaced by -128 afterwards); WIN == 0 walks a
+// window of any size.
+template <int WIN>
+__global__ void __launch_bounds__(256)
+maxpool_packed_i8_kernel(const int8_t *__restrict__ x, int8_t *__restrict__ y,
+                         int cp, int H, int W, int P, int Q,
+                         int window, int stride, int pad, int total, unsigned x_bytes)
 {
-    long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+    const int i = (int)(blockIdx.x * 256 + threadIdx.x);
     if (i >= total) return;
     const int chunks = cp / 16;
-    int cc = i % chunks;
-    long t = i / chunks;
-    int q = t % Q;  t /= Q;
-    int p = t % P;
-    long n = t / P;
+    int t = div_any(i, chunks);
+    const int cc = i - t * chunks;
+    const int t2 = div_any(t, Q);
+    const int q = t - t2 * Q;
+    const int n = div_any(t2, P);
+    const int p = t2 - n * P;
     int best[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) best[e] = -128;
-    for (int r = 0; r < window; ++r) {
-        int h = p * stride + r - pad;
-        if (h < 0 || h >= H) continue;
-        for (int s = 0; s < window; ++s) {
-            int w = q * stride + s - pad;
-            if (w < 0 || w >= W) continue;
-            v4i raw = *reinterpret_cast<const v4i *>(x + ((n * H + h) * W + w) * cp + cc * 16);
-            const int8_t *b = reinterpret_cast<const int8_t *>(&raw);
+    auto take = [&](const v4i &raw) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) best[e] = (b[e] > best[e]) ? b[e] : best[e];
+        for (int e = 0; e < 16; ++e) {
+            const int b = (int)(int8_t)((unsigned)raw[e >> 2] >> (8 * (e & 3)));
+            best[e] = (b > best[e]) ? b : best[e];
+        }
+    };
+    if (WIN > 0) {
+        const __amdgpu_buffer_rsrc_t rs = make_rsrc(x, x_bytes);
+        v4i raw[WIN > 0 ? WIN * WIN : 1];
+#pragma unroll
+        for (int r = 0; r < WIN; ++r)
+#pragma unroll
+            for (int s2 = 0; s2 < WIN; ++s2) {
+                const int h = p * stride + r - pad, w = q * stride + s2 - pad;
+                const bool ok = (unsigned)h < (unsigned)H && (unsigned)w < (unsigned)W;
+                v4i v = buf_load16(rs, ok ? (unsigned)(((n * H + h) * W + w) * cp + cc * 16) : UNIT_OOB);
+                const v4i lowest = {(int)0x80808080, (int)0x80808080, (int)0x80808080, (int)0x80808080};
+                raw[r * WIN + s2] = ok ? v : lowest;
+            }
+#pragma unroll
+        for (int k = 0; k < WIN * WIN; ++k) take(raw[k]);
+    } else {
+        for (int r = 0; r < window; ++r) {
+            const int h = p * stride + r - pad;
+            if (h < 0 || h >= H) continue;
+            for (int s2 = 0; s2 < window; ++s2) {
+                const int w = q * stride + s2 - pad;
+                if (w < 0 || w >= W) continue;
+                take(*reinterpret_cast<const v4i *>(x + ((long)(n * H + h) * W + w) * cp + cc * 16));
+            }
         }
     }
     __attribute__((aligned(16))) int8_t outv[16];
 #pragma unroll
     for (int e = 0; e < 16; ++e) outv[e] = (int8_t)best[e];
-    *reinterpret_cast<v4i *>(y + ((n * P + p) * Q + q) * cp + cc * 16) = *reinterpret_cast<const v4i *>(outv);
+    *reinterpret_cast<v4i *>(y + ((long)(n * P + p) * Q + q) * cp + cc * 16) = *reinterpret_cast<const v4i *>(outv);
 }
 
 hipError_t launch_maxpool_packed_i8(int n, int cp, int h, int w, int window, int stride, int pad,
                                     int p, int q, const void *x, void *y, hipStream_t st)
 {
-    long total = (long)n * p * q * (cp / 16);
-    hipLaunchKernelGGL(maxpool_packed_i8_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       (const int8_t *)x, (int8_t *)y, cp, h, w, p, q, window, stride, pad, total);
+    const long total = (long)n * p * q * (cp / 16);
+    const long x_bytes = (long)n * h * w * cp;
+    if (total >= (1L << 31) || x_bytes >= (1L << 31)) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    if (window == 3)
+        hipLaunchKernelGGL(maxpool_packed_i8_kernel<3>, grid, block, 0, st, (const int8_t *)x, (int8_t *)y, cp, h, w,
+                           p, q, window, stride, pad, (int)total, (unsigned)x_bytes);
+    else if (window == 2)
+        hipLaunchKernelGGL(maxpool_packed_i8_kernel<2>, grid, block, 0, st, (const int8_t *)x, (int8_t *)y, cp, h, w,
+                           p, q, window, stride, pad, (int)total, (unsigned)x_bytes);
+    else
+        hipLaunchKernelGGL(maxpool_packed_i8_kernel<0>, grid, block, 0, st, (const int8_t *)x, (int8_t *)y, cp, h, w,
+                           p, q, window, stride, pad, (int)total, (unsigned)x_bytes);
     return hipGetLastError();
 }
 

@@ -694,6 +694,8 @@ int unit_maxpool_packed_i8(int32_t n, int32_t c, int32_t h, int32_t w,
     if (pad >= window || h + 2 * pad < window || w + 2 * pad < window) return UNIT_EINVAL;
     if (!aligned16(xp) || !aligned16(yp)) return UNIT_EINVAL;
     int p = (h + 2 * pad - window) / stride + 1, q = (w + 2 * pad - window) / stride + 1;
+    const long cpl = pad_channels(c, UNIT_I8);
+    if ((long)n * h * w * cpl >= (1L << 31)) return UNIT_ENOTSUP;     // addressed through a buffer descriptor
     UNIT_HIP(launch_maxpool_packed_i8(n, pad_channels(c, UNIT_I8), h, w, window, stride, pad, p, q,
                                       xp, yp, static_cast<hipStream_t>(stream)));
     return UNIT_OK;

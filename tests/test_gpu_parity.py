@@ -471,6 +471,15 @@ def test_pack_roundtrip_and_glue_ops():
     unit.unit_unpack_act_i8(n, c, p, q, yp, mp)
     torch.cuda.synchronize()
     assert same(host(mp), oracle.maxpool_i8(x))
+    for win, st, pd in [(2, 2, 0), (3, 1, 1), (3, 2, 0), (5, 2, 2), (2, 1, 1)]:
+        announce("maxpool", win, st, pd)             # compile-time windows 2 and 3, and the general walk
+        p2, q2 = (h + 2 * pd - win) // st + 1, (w_ + 2 * pd - win) // st + 1
+        yp2 = ws_bytes(unit.unit_packed_act_bytes(n, c, p2, q2, unit.UNIT_I8))
+        unit.unit_maxpool_packed_i8(n, c, h, w_, win, st, pd, xp, yp2)
+        mp2 = torch.empty((n, c, p2, q2), dtype=torch.int8, device="cuda:0")
+        unit.unit_unpack_act_i8(n, c, p2, q2, yp2, mp2)
+        torch.cuda.synchronize()
+        assert same(host(mp2), oracle.maxpool_i8(x, (win, win), (st, st), (pd, pd)))
 
     announce("avgpool")
     scale = g.uniform(0.002, 0.02, c).astype(np.float32)
