@@ -52,7 +52,7 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
         if (tile < 0 && rows <= 64 && (long)cdiv(cols, 256) >= CUS * 3 / 4)
             tile = (kchunks >= 32) ? 6 : 1;
         // small problems are launch- and latency-bound: measured over the ResNet-50 batch-1
-        // layers, 64x64 (2x2 waves) wins once it yields ~100 workgroups, 32x32 below that
+        // layers, 64x64 (2x2x2 waves) wins once it yields ~100 workgroups, 32x32 below that
         if (tile < 0) tile = ((long)cdiv(rows, 64) * cdiv(cols, 64) >= 96) ? 3 : 4;
     }
     int forced = env_int("UNIT_TILE", -1);
