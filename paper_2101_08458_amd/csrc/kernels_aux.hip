@@ -60,6 +60,48 @@ pack_act_kernel(const T *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW
     }
 }
 
+// Images whose channels fit one 16-byte chunk (network inputs): one thread per pixel reads its
+// CL >= C channel values (coalesced along the pixels; channels past C re-read channel 0 and are
+// zeroed) and writes the pixel's chunk.  The tiled transpose above would spend a 64-channel tile
+// on them.
+template <typename T, int CL>
+__global__ void __launch_bounds__(256)
+pack_act_smallc_kernel(const T *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW,
+                       int HWin, int Q, int srow, int scol)
+{
+    constexpr int CH = 16 / sizeof(T);
+    const int px = blockIdx.x * 256 + threadIdx.x, n = blockIdx.y;
+    if (px >= HW) return;
+    int src = px;
+    if (Q > 0) {
+        const int p = px / Q;
+        src = p * srow + (px - p * Q) * scol;
+    }
+    const T *xn = x + (long)n * C * HWin + src;
+    __attribute__((aligned(16))) T vals[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) vals[c] = 0;
+    T v[CL];
+#pragma unroll
+    for (int c = 0; c < CL; ++c) v[c] = xn[(long)(c < C ? c : 0) * HWin];
+#pragma unroll
+    for (int c = 0; c < CL; ++c) vals[c] = c < C ? v[c] : (T)0;
+    *reinterpret_cast<v4i *>(xp + ((long)n * HW + px) * 16) = *reinterpret_cast<const v4i *>(vals);
+}
+
+template <typename T>
+static void launch_pack_small(const T *x, uint8_t *xp, int n, int c, int hw, int hw_in, int Q, int srow, int scol,
+                              hipStream_t st)
+{
+    const dim3 grid((hw + 255) / 256, n), block(256);
+    if (c <= 4)
+        hipLaunchKernelGGL((pack_act_smallc_kernel<T, 4>), grid, block, 0, st, x, xp, c, hw, hw_in, Q, srow, scol);
+    else if (c <= 8 || sizeof(T) == 2)
+        hipLaunchKernelGGL((pack_act_smallc_kernel<T, 8>), grid, block, 0, st, x, xp, c, hw, hw_in, Q, srow, scol);
+    else
+        hipLaunchKernelGGL((pack_act_smallc_kernel<T, 16 / sizeof(T)>), grid, block, 0, st, x, xp, c, hw, hw_in, Q, srow, scol);
+}
+
 // sh, sw > 1 with p, q > 0: pack only the pixels (i*sh, j*sw), i < p, j < q (output [n][p*q][cp])
 hipError_t launch_pack_act_sub(int dtype, int n, int c, int h, int w, int sh, int sw, int p, int q,
                                const void *x, void *xp, hipStream_t st)
@@ -67,6 +109,12 @@ hipError_t launch_pack_act_sub(int dtype, int n, int c, int h, int w, int sh, in
     const bool sub = p > 0;
     const int hw_in = h * w, hw = sub ? p * q : hw_in;
     const int Q = sub ? q : 0, srow = sh * w, scol = sw;
+    const int chunk = (dtype == DT_I8) ? 16 : 8;
+    if (c <= chunk && n <= 65535) {
+        if (dtype == DT_I8) launch_pack_small((const int8_t *)x, (uint8_t *)xp, n, c, hw, hw_in, Q, srow, scol, st);
+        else                launch_pack_small((const uint16_t *)x, (uint8_t *)xp, n, c, hw, hw_in, Q, srow, scol, st);
+        return hipGetLastError();
+    }
     if (dtype == DT_I8) {   // callers pass the storage type: one- or two-byte elements
         const int cp = (c + 15) / 16 * 16;
         dim3 grid((hw + 63) / 64, (cp + 63) / 64, n);

@@ -161,7 +161,8 @@ def test_shifted_direct_odd_geometries():
 
 def test_strided_1x1_packs_only_the_pixels_it_reads():
     """1x1 convs with stride > 1 run as unit-stride convs on a subsampled packed tensor."""
-    geoms = [(3, 70, 13, 9, 40, 2, 2), (2, 24, 8, 11, 17, 2, 3), (1, 130, 7, 7, 64, 3, 1), (4, 16, 5, 6, 8, 1, 2)]
+    geoms = [(3, 70, 13, 9, 40, 2, 2), (2, 24, 8, 11, 17, 2, 3), (1, 130, 7, 7, 64, 3, 1), (4, 16, 5, 6, 8, 1, 2),
+             (2, 5, 9, 10, 12, 2, 2)]               # (channels within one chunk: the per-pixel pack kernel)
     for i, (n, c, h, w, k, sh, sw) in enumerate(geoms):
         d = unit.conv_desc(n, c, h, w, k, 1, 1, (sh, sw), (0, 0))
         g = wl.rng(64, i)

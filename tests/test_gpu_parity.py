@@ -463,6 +463,22 @@ def test_pack_roundtrip_and_glue_ops():
     raw = host(xp)[: n * h * w_ * cp].reshape(n, h, w_, cp)
     assert same(raw[..., :c].view(np.int8).transpose(0, 3, 1, 2), x) and np.all(raw[..., c:] == 0)
 
+    for cs in (1, 3, 4, 5, 8, 9, 16):                # images whose channels fit one chunk: one thread per pixel
+        announce("pack small C", cs)
+        xs = wl.int8_weights(g, (3, cs, 9, 31))
+        xps = ws_bytes(unit.unit_packed_act_bytes(3, cs, 9, 31, unit.UNIT_I8))
+        unit.unit_pack_act_i8(3, cs, 9, 31, dev(xs), xps)
+        torch.cuda.synchronize()
+        raw = host(xps)[: 3 * 9 * 31 * 16].reshape(3, 9, 31, 16)
+        assert same(raw[..., :cs].view(np.int8).transpose(0, 3, 1, 2), xs) and np.all(raw[..., cs:] == 0)
+        if cs <= 8:
+            xh = g.integers(0, 65536, size=(2, cs, 7, 33)).astype(np.uint16)
+            xph = ws_bytes(unit.unit_packed_act_bytes(2, cs, 7, 33, unit.UNIT_F16))
+            unit.unit_pack_act_f16(2, cs, 7, 33, dev(xh.view(np.int16)), xph)
+            torch.cuda.synchronize()
+            rawh = host(xph)[: 2 * 7 * 33 * 16].view(np.uint16).reshape(2, 7, 33, 8)
+            assert same(rawh[..., :cs].transpose(0, 3, 1, 2), xh) and np.all(rawh[..., cs:] == 0)
+
     announce("maxpool")
     p, q = oracle.out_dim(h, 3, 2, 1), oracle.out_dim(w_, 3, 2, 1)
     yp = ws_bytes(unit.unit_packed_act_bytes(n, c, p, q, unit.UNIT_I8))
