@@ -548,8 +548,7 @@ igemm_kernel(const IgemmArgs g)
     // The DMA then runs NST-1 tiles ahead and refills the stage read one step EARLIER (whose
     // reads every wave has consumed in its previous step's MFMAs), so the step's barrier needs
     // no wait on outstanding LDS reads: they complete behind the MFMAs and the DMA issue.
-    constexpr bool WHOLE = (TM * TN <= 4);
-    static_assert(!WHOLE || NST >= 3, "the register-prefetch schedule needs three LDS stages");
+    constexpr bool WHOLE = (TM * TN <= 4) && NST >= 3;      // (the register-prefetch schedule needs three LDS stages)
     constexpr int NSLOT = WHOLE ? 2 * NS : 2;
     frag_t fa[NSLOT][TM], fb[NSLOT][TN];
     auto read_frags = [&](int stage, int sub, int slot) {

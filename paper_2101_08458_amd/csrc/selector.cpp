@@ -36,13 +36,13 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
         tile = 5;
     } else {
         // largest tile that still gives every compute unit a workgroup
-        static const int order[] = {7, 1};          // (tile 0, the same tile on four waves, measured 5-13 % slower)
+        static const int order[] = {8, 1};
         for (int t : order) {
             const TileCfg &c = g_tiles[t];
             long nt = (long)cdiv(rows, c.bm) * cdiv(cols, c.bn);
             double fill = (double)rows * cols / ((double)nt * c.bm * c.bn);
             // the 256x256 tile's prologue and epilogue only amortise over a long reduction
-            if (t == 7 && kchunks < 32) continue;
+            if (t == 8 && kchunks < 32) continue;
             if (nt >= CUS * 3 / 4 && fill >= 0.6) { tile = t; break; }
         }
         // Few output rows (<= 64 channels) but very many columns (network stems and first
