@@ -67,6 +67,11 @@ def test_error_paths_return_before_launch(lib):
     # requant without an int8 output / without scale
     rq = unit.unit_requant(None, None, None, 0)
     assert f(ctypes.byref(d), fake, fake, fake, ctypes.byref(rq), fake, fake, 1 << 20, st) == unit.UNIT_EINVAL
+    sc = 0x2000
+    rq2 = unit.unit_requant(sc, None, None, 1, 3, fake + 4)   # packed residual not 16-byte aligned
+    assert lib.unit_conv2d_packed_i8(ctypes.byref(d), fake, fake, None, ctypes.byref(rq2), fake, None, None, 0, st) == unit.UNIT_EINVAL
+    rq3 = unit.unit_requant(sc, None, None, 1, 0, None)
+    assert lib.unit_conv2d_packed_i8(ctypes.byref(d), fake, fake, None, ctypes.byref(rq3), None, fake + 8, None, 0, st) == unit.UNIT_EINVAL  # packed output misaligned
     bad = unit.conv_desc(1, 8, 2, 2, 8, 3, 3, 1, 0)          # window larger than the image
     assert f(ctypes.byref(bad), fake, fake, fake, None, null, fake, 1 << 20, st) == unit.UNIT_EINVAL
     neg = unit.conv_desc(1, 8, 8, 8, 8, 3, 3, 0, 1)          # stride 0
