@@ -20,6 +20,8 @@
 namespace unit {
 
 typedef int      v4i  __attribute__((ext_vector_type(4)));
+typedef int      v2i  __attribute__((ext_vector_type(2)));
+typedef short    v4s  __attribute__((ext_vector_type(4)));
 typedef int      v8i  __attribute__((ext_vector_type(8)));
 typedef int      v16i __attribute__((ext_vector_type(16)));
 typedef float    v4f  __attribute__((ext_vector_type(4)));
@@ -262,6 +264,14 @@ igemm_kernel(const IgemmArgs g)
     constexpr int EPC = 16 / ES;                    // elements per 16-byte chunk
     constexpr int CPR = BN * ES / 16;               // NCHW mode: 16-byte chunks per channel row of the B tile
     constexpr int CRPI = 64 / CPR;                  // NCHW mode: channel rows per DMA instruction
+    // NCHW mode: the 16-byte pixel chunks of channel row r are stored XOR-swizzled by nchw_swz(r), so that the
+    // rows a transposing read touches together (8 for 1-byte, 4 for 2-byte elements, two or four chunks each)
+    // fall into distinct LDS banks whatever the row pitch
+    constexpr int SWZ_UNIT = (ES == 1) ? 2 : 4;                             // chunks that must stay adjacent
+    constexpr int SWZ_DIV  = (16 / CPR > 1) ? 16 / CPR : 1;
+    constexpr int SWZ_ROWS = (ES == 1) ? 8 : 4;                             // rows one transposing read touches
+    constexpr int SWZ_MOD  = (CPR / SWZ_UNIT < SWZ_ROWS) ? CPR / SWZ_UNIT : SWZ_ROWS;
+    auto nchw_swz = [&](int r) { return SWZ_MOD > 1 ? SWZ_UNIT * ((r / SWZ_DIV) % SWZ_MOD) : 0; };
     constexpr int PITCH = 2 * BN * ES;              // shifted mode: bytes per channel row of the B tile
     constexpr int CPR2 = PITCH / 16;                // shifted mode: chunks per channel row
     constexpr int CRPI2 = (CPR2 >= 64) ? 1 : 64 / CPR2;
@@ -346,7 +356,7 @@ igemm_kernel(const IgemmArgs g)
             // this lane's 16-byte chunk of pixels lies inside one image (the host only picks this
             // mode when the pixels per image are a multiple of the chunk); columns past the end
             // read whatever follows and are masked at the store
-            const int px = col0 + (lane % CPR) * EPC;
+            const int px = col0 + ((lane % CPR) ^ nchw_swz(crow)) * EPC;
             const int img = (g.cols > g.PQ) ? div_any(px, g.PQ) : 0;
             offB[j] = (unsigned)(((img * g.Cin + crow) * g.PQ + (px - img * g.PQ)) * ES);
             bh0[j] = crow;                          // channel row of this lane inside a step
@@ -606,26 +616,39 @@ igemm_kernel(const IgemmArgs g)
                 fb[slot][j] = Frag<FW>::pack(w);
             }
         } else if (BSRC == BSRC_NCHW) {
-            // B tile is [channel][pixel]: gather this lane's 16 bytes of consecutive channels
-            // for its pixel column, one element per LDS read
+            // B tile is [channel][pixel], i.e. reduction-major: the transposing LDS reads of gfx950
+            // hand every lane the 8 bytes of consecutive channels of its pixel column.  Within a group
+            // of 16 lanes, lane t supplies the address of 8 contiguous bytes and lane n receives
+            //   1-byte elements: byte n%8 of the rows supplied by lanes 2i + n/8,   i = 0..7
+            //   2-byte elements: element n%4 of the rows supplied by lanes n/4 + 4i, i = 0..3
+            // so lanes (2i, 2i+1) point at channel row i, pixels 0-7 and 8-15 of the group's 16 pixels
+            // (four lanes per row, four pixels each, for 2-byte elements).
+            constexpr int RPR = (ES == 1) ? 8 : 4;                  // channel rows per read
+            const int t16 = lane & 15;
+            const int trow = (ES == 1) ? (t16 >> 1) : (t16 >> 2);   // channel row this lane points at
+            const int tcol = (ES == 1) ? (t16 & 1) * 8 : (t16 & 3) * 4;
+            const int ncol = ((lane % MF) & ~15) + tcol;            // pixel inside the MFMA tile
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
                 unsigned w[4 * FW];
 #pragma unroll
                 for (int f = 0; f < FW; ++f) {
-                    // first channel row of chunk ch + f
-                    const uint8_t *src = sB + (ch + f) * EPC * (BN * ES) + (b_row + j * MF) * ES;
+                    const int cbyte = (wn * C::WTN + j * MF + ncol) * ES;           // logical byte column of the row
+                    const uint8_t *src = sB + ((ch + f) * EPC + trow) * (BN * ES) +
+                                         ((((cbyte >> 4) ^ nchw_swz(trow)) << 4) | (cbyte & 15));
 #pragma unroll
-                    for (int d = 0; d < 4; ++d) {
+                    for (int h = 0; h < EPC / RPR; ++h) {
+                        typedef __attribute__((address_space(3))) v2i lds_v2i;
+                        typedef __attribute__((address_space(3))) v4s lds_v4s;
+                        v2i r;
                         if (ES == 1) {
-                            unsigned b0 = src[(4 * d + 0) * BN], b1 = src[(4 * d + 1) * BN];
-                            unsigned b2 = src[(4 * d + 2) * BN], b3 = src[(4 * d + 3) * BN];
-                            w[4 * f + d] = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+                            r = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(src + h * RPR * BN * ES));
                         } else {
-                            unsigned h0 = *reinterpret_cast<const uint16_t *>(src + (2 * d + 0) * BN * 2);
-                            unsigned h1 = *reinterpret_cast<const uint16_t *>(src + (2 * d + 1) * BN * 2);
-                            w[4 * f + d] = h0 | (h1 << 16);
+                            v4s q = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s *)(src + h * RPR * BN * ES));
+                            r = __builtin_bit_cast(v2i, q);
                         }
+                        w[4 * f + 2 * h] = (unsigned)r[0];
+                        w[4 * f + 2 * h + 1] = (unsigned)r[1];
                     }
                 }
                 fb[slot][j] = Frag<FW>::pack(w);
