@@ -60,6 +60,7 @@ struct IgemmArgs {
     // (D, T, sd, pd describe the depth axis; conv2d is D = T = 1)
     int D, H, W, CB, P, Q, PQ, T, R, S, sd, sh, sw, pd, ph, pw;
     int Cin;                                        // NCHW-direct kernels: real channel count
+    int row_runs;                                   // tile order: consecutive workgroups of an XCD share a row tile
     int per_img;                                    // NCHW-direct: column tiles never straddle images (each image's
                                                     // pixels are tiled on their own; needed when an image does not
                                                     // hold a whole number of 16-byte pixel chunks)
@@ -295,14 +296,25 @@ igemm_kernel(const IgemmArgs g)
     const int tiles_n = per_img ? tiles_img * div_any(g.cols, g.PQ) : (g.cols + BN - 1) / BN;
     const int ntiles  = tiles_m * tiles_n;
     int bid = blockIdx.x;
-    if ((ntiles & 7) == 0) bid = (bid & 7) * (ntiles >> 3) + (bid >> 3);
-    constexpr int BAND = 8;
-    const int band      = div_any(bid, BAND * tiles_n);
-    const int band_m0   = band * BAND;
-    const int band_rows = (tiles_m - band_m0 < BAND) ? tiles_m - band_m0 : BAND;
-    const int in_band   = bid - band * BAND * tiles_n;
-    const int tn = div_any(in_band, band_rows);
-    const int tm = band_m0 + in_band - tn * band_rows;
+    {   // XCD x = bid % 8 receives workgroups x, x + 8, ...: they become one contiguous run of the tile order
+        const int q8 = ntiles >> 3, r8 = ntiles & 7, x = bid & 7;
+        bid = x * q8 + (x < r8 ? x : r8) + (bid >> 3);
+    }
+    int tm, tn;
+    if (g.row_runs) {
+        // far more A (weight) bytes than B bytes: a run walks the column tiles of one row tile, so each
+        // XCD fetches its own rows of A once and only the small B is fetched by every XCD
+        tm = div_any(bid, tiles_n);
+        tn = bid - tm * tiles_n;
+    } else {
+        constexpr int BAND = 8;
+        const int band      = div_any(bid, BAND * tiles_n);
+        const int band_m0   = band * BAND;
+        const int band_rows = (tiles_m - band_m0 < BAND) ? tiles_m - band_m0 : BAND;
+        const int in_band   = bid - band * BAND * tiles_n;
+        tn = div_any(in_band, band_rows);
+        tm = band_m0 + in_band - tn * band_rows;
+    }
     const int row0 = tm * BM;
     int col0 = tn * BN, col_end = g.cols;           // first column of the tile, end of its column range
     if (per_img) {

@@ -135,6 +135,10 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
     const bool conv = bsrc != BSRC_PLAIN;
     TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, bsrc, allow_split);
     a.ksteps_per_split = ch.ksteps_per_split;
+    // Tile order inside an XCD's run: while the whole B operand is small (<= 8 MiB: every XCD can afford its own
+    // copy in L2) a run walks the column tiles of one row tile, so A (the weights) is fetched once in total; large
+    // problems walk bands of 8 row tiles, which bounds the re-fetching of both operands.
+    a.row_runs = ((long)a.cols * a.kchunks * 16 <= (8L << 20)) ? 1 : 0;
     if (ch.split_k == 1) {
         a.split_stride = 0;
         UNIT_HIP(launch_igemm(dtype, bsrc, ch.tile, a, 1, st));
