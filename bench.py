@@ -459,6 +459,11 @@ def main():
             add("large conv N=32 C=K=256 56x56 3x3, pack_act + conv", dtype, c.macs, c.bytes, event_ms(torch, c.api, 20), c.info)
             del c
             torch.cuda.empty_cache()
+        for dtype in ("i8", "f16"):                # the same kernel on a problem of four workgroup rounds
+            g = GemmCase(torch, unit, wl, 8192, 8192, 8192, dtype)
+            add("gemm 8192^3", dtype, g.macs, g.bytes, event_ms(torch, g.run, 5), g.info)
+            del g
+            torch.cuda.empty_cache()
         for dtype in ("u8i8", "bf16", "fp8"):      # further operand types through the same kernel
             g = GemmCase(torch, unit, wl, 4096, 4096, 4096, dtype)
             add("gemm 4096^3", dtype, g.macs, g.bytes, event_ms(torch, g.run, 30), g.info)
