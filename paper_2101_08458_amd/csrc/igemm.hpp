@@ -236,7 +236,7 @@ struct IgemmCfg {
         IB    = BN / RPI / NW * BMUL,
         LPT   = IA + IB,
         STAGE_BYTES  = (BM + BN * BMUL) * BKB,
-        REDUCE_BYTES = (WGK - 1) * BM * BN * 4,
+        REDUCE_BYTES = (WGK > 1) ? WGK * BM * BN * 4 : 0,
         SMEM_BYTES   = (NST * STAGE_BYTES > REDUCE_BYTES) ? NST * STAGE_BYTES : REDUCE_BYTES,
         FITS  = (SMEM_BYTES <= 160 * 1024) && ((NST - 1) * LPT <= 63),   // LDS capacity, vmcnt range
     };
@@ -786,157 +786,148 @@ igemm_kernel(const IgemmArgs g)
         UNIT_BARRIER();
     }
 
-    // ---- in-group split reduction: waves with wk > 0 park their accumulators in LDS
-    // (lane-contiguous, conflict free), wave slice 0 adds them in fixed order.
+    // ---- in-group split reduction and epilogue.  The unit of work is a GROUP: accumulator elements
+    // 4a..4a+3 of one MFMA tile, which a lane holds for four consecutive rows of its column.  With an
+    // in-group reduction split (WGK > 1) every wave parks all of its groups in LDS (16 bytes per lane,
+    // lane-contiguous, conflict free) and then owns every WGK-th group: it adds the WGK partial sums of
+    // its groups in fixed order and runs the epilogue for them, so the reduction and the epilogue are
+    // shared by all waves of the window instead of falling to one.  Without a split a wave owns the
+    // groups of its own accumulators, one MFMA tile at a time.
+    typedef elem_t v4e __attribute__((ext_vector_type(4)));
+    constexpr int NA = M::NACC, GPT = NA / 4;       // groups per MFMA tile
+    constexpr int NG = TM * TN * GPT;               // groups per wave window
+    static_assert(NG % WGK == 0, "the groups of a window must split evenly over its waves");
+    constexpr int UG = (WGK > 1) ? NG / WGK : GPT;  // groups handled together (their loads are issued first)
+    constexpr int NU = (WGK > 1) ? 1 : TM * TN;     // such units per wave
+    const v4e *red = reinterpret_cast<const v4e *>(smem);
+    const int wmn = wave % (WGM * WGN);
     if (WGK > 1) {
-        elem_t *red = reinterpret_cast<elem_t *>(smem);
-        const int wmn = wave % (WGM * WGN);
-        if (wk > 0) {
+        v4e *park = reinterpret_cast<v4e *>(smem);
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
-                    for (int e = 0; e < M::NACC; ++e)
-                        red[((((wk - 1) * WGM * WGN + wmn) * TM * TN + i * TN + j) * M::NACC + e) * 64 + lane] = acc[i][j][e];
-        }
+                for (int a4 = 0; a4 < GPT; ++a4)
+                    park[((wk * WGM * WGN + wmn) * NG + (i * TN + j) * GPT + a4) * 64 + lane] =
+                        v4e{acc[i][j][4 * a4], acc[i][j][4 * a4 + 1], acc[i][j][4 * a4 + 2], acc[i][j][4 * a4 + 3]};
         __syncthreads();
-        if (wk > 0) return;
-        for (int k2 = 1; k2 < WGK; ++k2)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int e = 0; e < M::NACC; ++e)
-                        acc[i][j][e] += red[((((k2 - 1) * WGM * WGN + wmn) * TM * TN + i * TN + j) * M::NACC + e) * 64 + lane];
     }
 
-    // ---- epilogue
-    if (EPI == EPI_RAW) {
-        // 4-byte stores through a buffer descriptor anchored at the tile's first row;
-        // out-of-tile lanes get an out-of-range offset and are dropped by the hardware.
-        const elem_t *tile_base = reinterpret_cast<const elem_t *>(g.out) + (long)blockIdx.z * g.split_stride +
-                                  (long)row0 * g.row_stride;
-        const __amdgpu_buffer_rsrc_t rsO = make_rsrc(tile_base, UNIT_OOB);   // lanes are masked explicitly
-        // Unsigned-operand correction, added once (by the first reduction slice).  Per row
-        // (DT_U8B) a lane's accumulator elements 4a..4a+3 sit in four consecutive rows: one
-        // 16-byte load each; the vector is allocated in whole 256-byte blocks, rows past the
-        // end read as zero and are never stored.
-        v4i row_fix[TM][M::NACC / 4];
-        if (DT == DT_U8B) {
-            const __amdgpu_buffer_rsrc_t rsF = make_rsrc(g.bias, (unsigned)((g.rows * 4 + 255) & ~255));
+    const elem_t *tile_base = reinterpret_cast<const elem_t *>(g.out) + (long)blockIdx.z * g.split_stride +
+                              (long)row0 * g.row_stride;
+    const __amdgpu_buffer_rsrc_t rsO = make_rsrc(tile_base, UNIT_OOB);        // raw stores; lanes are masked explicitly
+    const __amdgpu_buffer_rsrc_t rsS = make_rsrc(g.scale, (EPI == EPI_REQUANT) ? UNIT_OOB : 0u);
+    // bias: requantise bias, or the unsigned-operand correction of the raw epilogue (added once, by the
+    // first reduction slice; allocated in whole 256-byte blocks for the per-row form)
+    const __amdgpu_buffer_rsrc_t rsBi = make_rsrc(
+        g.bias, !(g.bias && (EPI == EPI_REQUANT || blockIdx.z == 0)) ? 0u
+                : (EPI == EPI_RAW && DT == DT_U8B)                    ? (unsigned)((g.rows * 4 + 255) & ~255) : UNIT_OOB);
+    const __amdgpu_buffer_rsrc_t rsR = make_rsrc(g.residual, g.residual ? UNIT_OOB : 0u);
+    const __amdgpu_buffer_rsrc_t rsP = make_rsrc(g.res_packed, g.res_packed ? UNIT_OOB : 0u);
+    elem_t *out = reinterpret_cast<elem_t *>(g.out);
+
+#pragma clang loop unroll(full)
+    for (int u = 0; u < NU; ++u) {
+        v4e val[UG];
+        int grow[UG], gcol[UG];                     // first row (of four) and column of each group
+        long gcb[UG];                               // offset of (row 0, column) in the NCHW / row-major output
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+        for (int q = 0; q < UG; ++q) {
+            const int gidx = (WGK > 1) ? q * WGK + wk : u * GPT + q;
+            const int a4 = gidx % GPT, ij = gidx / GPT;
+            const int j = ij % TN, i = ij / TN;
+            if (WGK > 1) {
+                v4e v = red[((0 * WGM * WGN + wmn) * NG + gidx) * 64 + lane];
 #pragma unroll
-                for (int a4 = 0; a4 < M::NACC / 4; ++a4) {
-                    const int r = row0 + wm * C::WTM + i * MF + acc_row<MF>(4 * a4, lane);
-                    row_fix[i][a4] = buf_load16(rsF, blockIdx.z == 0 ? (unsigned)r * 4u : UNIT_OOB);
-                }
-        }
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int col = col0 + wn * C::WTN + j * MF + lrow;
-            unsigned cbase;
-            if (CONV) {
-                int n = (g.cols > g.cols_per_img) ? div_any(col, g.cols_per_img) : 0;
-                cbase = (unsigned)((long)n * g.img_stride + (col - n * g.cols_per_img));
+                for (int k2 = 1; k2 < WGK; ++k2) v += red[((k2 * WGM * WGN + wmn) * NG + gidx) * 64 + lane];
+                val[q] = v;
             } else {
-                cbase = (unsigned)col;
+                // (u and q are unrolled constants here, so this indexes registers statically)
+                val[q] = v4e{acc[u / TN][u % TN][4 * q], acc[u / TN][u % TN][4 * q + 1],
+                             acc[u / TN][u % TN][4 * q + 2], acc[u / TN][u % TN][4 * q + 3]};
             }
-            const bool col_ok = col < col_end;
-            elem_t col_fix = 0;
-            if (DT == DT_U8A && col_ok && blockIdx.z == 0) col_fix = (elem_t)g.bias[col];
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-#pragma unroll
-                for (int e = 0; e < M::NACC; ++e) {
-                    const int lr = wm * C::WTM + i * MF + acc_row<MF>(e, lane);
-                    const bool ok = col_ok && lr < rows_here;
-                    const unsigned off = ok ? (cbase + (unsigned)lr * (unsigned)g.row_stride) * 4u : UNIT_OOB;
-                    elem_t val = acc[i][j][e];
-                    if (DT == DT_U8A) val += col_fix;
-                    if (DT == DT_U8B) val += (elem_t)row_fix[i][e >> 2][e & 3];
-                    __builtin_amdgcn_raw_buffer_store_b32(to_bits(val), rsO, off, 0, 0);
-                }
-            }
-        }
-    } else {
-        // Every load of a sub-tile (scale, bias, both residual forms) is issued before its first
-        // store, through buffer descriptors: absent inputs get an empty range and masked lanes an
-        // offset beyond it, both read as zero, so the loads need no branches and wait only once.
-        elem_t *out = reinterpret_cast<elem_t *>(g.out);
-        constexpr int NA = M::NACC;
-        const __amdgpu_buffer_rsrc_t rsS = make_rsrc(g.scale, UNIT_OOB);
-        const __amdgpu_buffer_rsrc_t rsBi = make_rsrc(g.bias, g.bias ? UNIT_OOB : 0u);
-        const __amdgpu_buffer_rsrc_t rsR = make_rsrc(g.residual, g.residual ? UNIT_OOB : 0u);
-        const __amdgpu_buffer_rsrc_t rsP = make_rsrc(g.res_packed, g.res_packed ? UNIT_OOB : 0u);
-        int colv[TN];
-        long cbase[TN];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
+            grow[q] = row0 + wm * C::WTM + i * MF + acc_row<MF>(4 * a4, lane);
             const int col = col0 + wn * C::WTN + j * MF + lrow;
-            colv[j] = col;
+            gcol[q] = col;
             if (CONV) {
-                int n = (g.cols > g.cols_per_img) ? div_any(col, g.cols_per_img) : 0;
-                cbase[j] = (long)n * g.img_stride + (col - n * g.cols_per_img);
+                const int n = (g.cols > g.cols_per_img) ? div_any(col, g.cols_per_img) : 0;
+                gcb[q] = (long)n * g.img_stride + (col - n * g.cols_per_img);
             } else {
-                cbase[j] = col;
+                gcb[q] = col;
             }
         }
+        if (EPI == EPI_RAW) {
+            // 4-byte stores through a buffer descriptor anchored at the tile's first row; out-of-tile
+            // lanes get an out-of-range offset and are dropped by the hardware.  Unsigned operands: per
+            // column (DT_U8A) one correction for the group, per row (DT_U8B) one 16-byte load of four.
+            v4i fix[UG];
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const int rtile = row0 + wm * C::WTM + i * MF;
-            float sc[NA];
-            int bi[NA];
-#pragma unroll
-            for (int e = 0; e < NA; ++e) {
-                const int row = rtile + acc_row<MF>(e, lane);
-                const unsigned off = row < g.rows ? (unsigned)row * 4u : UNIT_OOB;
-                sc[e] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsS, off, 0, 0));
-                bi[e] = (int)__builtin_amdgcn_raw_buffer_load_b32(rsBi, off, 0, 0);
+            for (int q = 0; q < UG; ++q) {
+                if (DT == DT_U8B) {
+                    fix[q] = buf_load16(rsBi, (unsigned)grow[q] * 4u);
+                } else if (DT == DT_U8A) {
+                    const int f = (int)__builtin_amdgcn_raw_buffer_load_b32(rsBi, gcol[q] < col_end ? (unsigned)gcol[q] * 4u : UNIT_OOB, 0, 0);
+                    fix[q] = v4i{f, f, f, f};
+                } else {
+                    fix[q] = v4i{0, 0, 0, 0};
+                }
             }
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int col = colv[j];
-                if (col >= col_end) continue;
-                unsigned add[NA];                   // modular sums: the caller bounds only the total
+            for (int q = 0; q < UG; ++q) {
+                const unsigned cb = (unsigned)gcb[q];
 #pragma unroll
-                for (int e = 0; e < NA; ++e) {
-                    const int row = rtile + acc_row<MF>(e, lane);
-                    const unsigned off = row < g.rows ? (unsigned)(cbase[j] + (long)row * g.row_stride) * 4u : UNIT_OOB;
-                    add[e] = (unsigned)bi[e] + __builtin_amdgcn_raw_buffer_load_b32(rsR, off, 0, 0);
+                for (int b = 0; b < 4; ++b) {
+                    const int lr = grow[q] - row0 + b;
+                    const bool ok = gcol[q] < col_end && lr < rows_here;
+                    const unsigned off = ok ? (cb + (unsigned)lr * (unsigned)g.row_stride) * 4u : UNIT_OOB;
+                    elem_t v = val[q][b];
+                    if (DT == DT_U8A || DT == DT_U8B) v += (elem_t)fix[q][b];
+                    __builtin_amdgcn_raw_buffer_store_b32(to_bits(v), rsO, off, 0, 0);
                 }
-                // accumulator elements 4a..4a+3 of a lane are four consecutive output channels of its
-                // pixel: the packed residual arrives as one 32-bit load, and the int8 results leave as
-                // one 32-bit store into the packed (NHWC) output (padding channels stay zero)
-                unsigned res4[NA / 4];
+            }
+        } else {
+            // Every load of the unit (scale, bias, both residual forms) is issued before its first store,
+            // through buffer descriptors: absent inputs get an empty range and masked lanes an offset
+            // beyond it, both read as zero, so the loads need no branches and the wave waits once.
+            float sc[UG][4];
+            unsigned add[UG][4], res4[UG];          // modular sums: the caller bounds only the total
 #pragma unroll
-                for (int a4 = 0; a4 < NA / 4; ++a4) {
-                    const int rbase = rtile + acc_row<MF>(4 * a4, lane);
-                    res4[a4] = __builtin_amdgcn_raw_buffer_load_b32(
-                        rsP, rbase < g.packed_ld ? (unsigned)((long)col * g.packed_ld + rbase) : UNIT_OOB, 0, 0);
+            for (int q = 0; q < UG; ++q) {
+                const bool col_ok = gcol[q] < col_end;
+#pragma unroll
+                for (int b = 0; b < 4; ++b) {
+                    const int row = grow[q] + b;
+                    const unsigned off = row < g.rows ? (unsigned)row * 4u : UNIT_OOB;
+                    const unsigned roff = (row < g.rows && col_ok) ? (unsigned)(gcb[q] + (long)row * g.row_stride) * 4u : UNIT_OOB;
+                    sc[q][b] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsS, off, 0, 0));
+                    add[q][b] = __builtin_amdgcn_raw_buffer_load_b32(rsBi, off, 0, 0) +
+                                __builtin_amdgcn_raw_buffer_load_b32(rsR, roff, 0, 0);
                 }
+                // the four rows of a group are four consecutive output channels of the lane's pixel: the
+                // packed residual arrives as one 32-bit load, and the int8 results leave as one 32-bit
+                // store into the packed (NHWC) output (padding channels stay zero)
+                res4[q] = __builtin_amdgcn_raw_buffer_load_b32(
+                    rsP, (grow[q] < g.packed_ld && col_ok) ? (unsigned)((long)gcol[q] * g.packed_ld + grow[q]) : UNIT_OOB, 0, 0);
+            }
 #pragma unroll
-                for (int a4 = 0; a4 < NA / 4; ++a4) {
-                    const int rbase = rtile + acc_row<MF>(4 * a4, lane);
-                    unsigned four = 0;
+            for (int q = 0; q < UG; ++q) {
+                if (gcol[q] >= col_end) continue;
+                unsigned four = 0;
 #pragma unroll
-                    for (int b = 0; b < 4; ++b) {
-                        const int e = 4 * a4 + b;
-                        const int row = rbase + b;
-                        if (row >= g.rows) continue;
-                        const long addr = cbase[j] + (long)row * g.row_stride;
-                        const int t = (int)((unsigned)(int)acc[i][j][e] + add[e] +
-                                            (unsigned)((int)(int8_t)(res4[a4] >> (8 * b)) * g.res_mult));
-                        if (g.store_raw) out[addr] = acc[i][j][e];
-                        const int v = requant_elem(t, sc[e], g.relu);
-                        if (g.out_i8) g.out_i8[addr] = (int8_t)v;
-                        four |= ((unsigned)v & 0xffu) << (8 * b);
-                    }
-                    if (g.out_packed && rbase < g.packed_ld)
-                        *reinterpret_cast<unsigned *>(g.out_packed + (long)col * g.packed_ld + rbase) = four;
+                for (int b = 0; b < 4; ++b) {
+                    const int row = grow[q] + b;
+                    if (row >= g.rows) continue;
+                    const long addr = gcb[q] + (long)row * g.row_stride;
+                    const int t = (int)((unsigned)(int)val[q][b] + add[q][b] +
+                                        (unsigned)((int)(int8_t)(res4[q] >> (8 * b)) * g.res_mult));
+                    if (g.store_raw) out[addr] = val[q][b];
+                    const int v = requant_elem(t, sc[q][b], g.relu);
+                    if (g.out_i8) g.out_i8[addr] = (int8_t)v;
+                    four |= ((unsigned)v & 0xffu) << (8 * b);
                 }
+                if (g.out_packed && grow[q] < g.packed_ld)
+                    *reinterpret_cast<unsigned *>(g.out_packed + (long)gcol[q] * g.packed_ld + grow[q]) = four;
             }
         }
     }
