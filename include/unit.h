@@ -124,7 +124,7 @@ int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_inf
  * How unit_conv2d_wpacked_* (and unit_conv2d_*) will read the NCHW activations `x` of this
  * problem when no requantise epilogue is requested (introspection / reports; nothing is launched):
  *   UNIT_INPUT_PACKED          pack_act into the workspace, then the gather kernel
- *   UNIT_INPUT_DIRECT          1x1 stride-1 unpadded conv with aligned channel rows: the main
+ *   UNIT_INPUT_DIRECT          1x1 stride-1 unpadded conv (any batch, any image size): the main
  *                              kernel reads NCHW itself (no pack_act launch)
  *   UNIT_INPUT_DIRECT_SHIFTED  one image, stride 1, output grid equal to the input grid ("same"
  *                              padding, any window), whole reduction steps inside one tap: the main
@@ -204,10 +204,9 @@ int unit_conv2d_packed_f16(const unit_conv2d_desc *d, const void *x_packed, cons
 /*
  * conv2d on plain NCHW activations with pre-packed weights: the per-layer call of an
  * inference loop whose weights were packed once.  Activations are packed into the workspace
- * first, except for 1x1 / stride-1 / unpadded convs without requantise whose channel rows
- * can be streamed as they are (16-byte aligned x; n == 1 and h*w*elem a multiple of 4 bytes,
- * or any n with h*w a multiple of the 16-byte chunk: 16 int8 / 8 fp16 pixels), which read
- * NCHW directly inside the main kernel.  Outputs as in unit_conv2d_i8 / unit_conv2d_f16.
+ * first, except where the main kernel can read NCHW itself (16-byte aligned x, no requantise;
+ * see unit_conv2d_input_mode): 1x1 / stride-1 / unpadded convs of any batch and image size, and
+ * stride-1 "same"-padded convs of one image.  Outputs as in unit_conv2d_i8 / unit_conv2d_f16.
  */
 size_t unit_conv2d_wpacked_workspace(const unit_conv2d_desc *d, int dtype);
 int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const void *w_packed,

@@ -171,16 +171,29 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
 
 // A 1x1, stride-1, unpadded conv can read its NCHW input directly: the
 // channel rows are DMAed as they are and transposed between LDS and the fragments, which
-// saves the separate pack_act launch.  Needs 4-byte aligned channel rows.
+// saves the separate pack_act launch.  The 16-byte global -> LDS loads take any byte offset, so
+// the channel rows need no alignment; with several images whose pixel count is not a whole number
+// of 16-byte chunks the columns are tiled per image (conv_packed sets per_img).
+// Rows that do not start on 4-byte boundaries make some of the 16-byte loads start inside a dword;
+// the range check drops every dword that is not wholly inside the buffer, so the last bytes of the
+// tensor would be lost.  The range is then extended by 3 bytes (slack), which makes the hardware read
+// up to 3 bytes past the tensor (into columns that are never stored).  Memory protection works on
+// pages of at least 4 KiB, so this is done only when those bytes lie on the tensor's last page.
+long nchw_range_slack(const ConvND *d, int dtype, const void *x)
+{
+    const long px = (long)d->d * d->h * d->w, es = elem_size(dtype);
+    if ((px * es) % 4 == 0) return 0;                             // every load starts on a dword: exact range
+    const uintptr_t end = reinterpret_cast<uintptr_t>(x) + (uintptr_t)((long)d->n * d->c * px * es);
+    const unsigned in_page = (unsigned)(end & 4095);
+    return (in_page == 0 || in_page > 4093) ? -1 : 3;             // -1: the slack could cross into another page
+}
+
 bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requant *rq)
 {
-    const long px = (long)d->d * d->h * d->w;      // pixels per image
-    // channel rows must be 4-byte aligned; with several images whose pixel count is not a whole
-    // number of 16-byte chunks the columns are tiled per image (conv_packed sets per_img)
-    const bool rows_ok = (px * elem_size(dtype)) % 4 == 0;
+    if (nchw_range_slack(d, dtype, x) < 0) return false;
     return d->t == 1 && d->r == 1 && d->s == 1 &&
            d->stride_d == 1 && d->stride_h == 1 && d->stride_w == 1 &&
-           d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr && rows_ok && dtype != UNIT_U8I8 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
+           d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr && dtype != UNIT_U8I8 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
 }
 
 // The general direct read (BSRC_NCHWS): one image, stride 1, output grid equal to the input grid
@@ -228,6 +241,11 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
     a.D = d->d;  a.H = d->h;  a.W = d->w;  a.CB = g.cp * es / 16;
     a.P = g.p;  a.Q = g.q;  a.PQ = g.o * g.p * g.q;
     a.b_bytes = nchw_direct ? (long)d->n * d->c * d->d * d->h * d->w * es : (long)d->n * d->d * d->h * d->w * g.cp * es;
+    if (bsrc == BSRC_NCHW) {
+        const long slack = nchw_range_slack(d, dtype, xp);
+        if (slack < 0) return UNIT_EINVAL;          // (callers pick this mode through nchw_direct_ok)
+        a.b_bytes += slack;
+    }
     a.Cin = d->c;
     a.per_img = (bsrc == BSRC_NCHW && d->n > 1 && ((long)d->d * d->h * d->w) % chunk_elems(dtype) != 0) ? 1 : 0;
     a.T = d->t;  a.R = d->r;  a.S = d->s;

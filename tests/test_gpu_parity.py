@@ -202,17 +202,19 @@ def test_conv_i8_small_all_tiles(sh, n):
                 assert same(run_conv_i8(sh, n, x, w), ref), (tile, split)
 
 
-NCHW_DIRECT = [   # 1x1 / stride 1: read straight from NCHW when the channel rows allow it
+NCHW_DIRECT = [   # 1x1 / stride 1: read straight from NCHW, whatever the alignment of the channel rows
     (wl.ConvShape(20, 14, 14, 33, 1, 1, 1, 0), 1), (wl.ConvShape(64, 56, 56, 64, 1, 1, 1, 0), 1),
     (wl.ConvShape(70, 10, 10, 130, 1, 1, 1, 0), 1), (wl.ConvShape(256, 6, 6, 40, 1, 1, 1, 0), 1),
     (wl.ConvShape(3, 18, 18, 5, 1, 1, 1, 0), 1),
-    (wl.ConvShape(130, 7, 7, 64, 1, 1, 1, 0), 1),      # 49 pixels: falls back to pack + gather
+    (wl.ConvShape(130, 7, 7, 64, 1, 1, 1, 0), 1),      # 49 pixels: channel rows at odd byte offsets
+    (wl.ConvShape(37, 3, 5, 20, 1, 1, 1, 0), 1),       # 15 pixels: less than one chunk per row
+    (wl.ConvShape(48, 7, 7, 33, 1, 1, 1, 0), 3),       # several images of 49 pixels: per-image tiles, odd offsets
     (wl.ConvShape(24, 8, 8, 40, 1, 1, 1, 0), 3),       # several images, 64 pixels each: direct
     (wl.ConvShape(72, 12, 4, 96, 1, 1, 1, 0), 5),      # 48 pixels per image: direct, tiles straddle images
     (wl.ConvShape(16, 14, 14, 24, 1, 1, 1, 0), 2),     # 196 pixels per image, n > 1: columns tiled per image
     (wl.ConvShape(40, 6, 6, 24, 1, 1, 1, 0), 5),       # 36 pixels per image: per-image tiles, mostly empty
     (wl.ConvShape(256, 14, 14, 70, 1, 1, 1, 0), 3),    # several reduction steps, per-image tiles
-    (wl.ConvShape(32, 5, 10, 16, 1, 1, 1, 0), 4),      # 50 pixels: int8 rows unaligned (packs), fp16 rows aligned (direct)
+    (wl.ConvShape(32, 5, 10, 16, 1, 1, 1, 0), 4),      # 50 pixels per image
 ]
 
 
