@@ -547,6 +547,58 @@ igemm_kernel(const IgemmArgs g)
         }
     }
 
+    // ---- epilogue bookkeeping.  The unit of work of the epilogue is a GROUP: accumulator elements
+    // 4a..4a+3 of one MFMA tile, which a lane holds for four consecutive rows of its column.  With an
+    // in-group reduction split (WGK > 1) a wave owns every WGK-th group of its window (see the
+    // reduction below), otherwise the groups of its own accumulators, one MFMA tile at a time.
+    constexpr int NA = M::NACC, GPT = NA / 4;       // groups per MFMA tile
+    constexpr int NG = TM * TN * GPT;               // groups per wave window
+    static_assert(NG % WGK == 0, "the groups of a window must split evenly over its waves");
+    constexpr int UG = (WGK > 1) ? NG / WGK : GPT;  // groups handled together (their loads are issued first)
+    constexpr int NU = (WGK > 1) ? 1 : TM * TN;     // such units per wave
+    // first row (of four), column, and offset of (row 0, column) in the output of group q of unit u
+    auto group_at = [&](int u, int q, int &grow, int &gcol, long &gcb) {
+        const int gidx = (WGK > 1) ? q * WGK + wk : u * GPT + q;
+        const int a4 = gidx % GPT, ij = gidx / GPT;
+        const int j = ij % TN, i = ij / TN;
+        grow = row0 + wm * C::WTM + i * MF + acc_row<MF>(4 * a4, lane);
+        gcol = col0 + wn * C::WTN + j * MF + lrow;
+        if (CONV) {
+            const int n = (g.cols > g.cols_per_img) ? div_any(gcol, g.cols_per_img) : 0;
+            gcb = (long)n * g.img_stride + (gcol - n * g.cols_per_img);
+        } else {
+            gcb = gcol;
+        }
+    };
+    // Requantise inputs of one unit (scale, bias, both residual forms), all through buffer descriptors:
+    // absent inputs get an empty range and masked lanes an offset beyond it, both read as zero, so the
+    // loads need no branches and the wave waits once for all of them.
+    auto requant_inputs = [&](int u, float (*sc)[4], unsigned (*add)[4], unsigned *res4) {
+        const __amdgpu_buffer_rsrc_t rsS = make_rsrc(g.scale, UNIT_OOB);
+        const __amdgpu_buffer_rsrc_t rsBi = make_rsrc(g.bias, g.bias ? UNIT_OOB : 0u);
+        const __amdgpu_buffer_rsrc_t rsR = make_rsrc(g.residual, g.residual ? UNIT_OOB : 0u);
+        const __amdgpu_buffer_rsrc_t rsP = make_rsrc(g.res_packed, g.res_packed ? UNIT_OOB : 0u);
+#pragma unroll
+        for (int q = 0; q < UG; ++q) {
+            int grow, gcol;
+            long gcb;
+            group_at(u, q, grow, gcol, gcb);
+            const bool col_ok = gcol < col_end;
+#pragma unroll
+            for (int b = 0; b < 4; ++b) {
+                const int row = grow + b;
+                const unsigned off = row < g.rows ? (unsigned)row * 4u : UNIT_OOB;
+                const unsigned roff = (row < g.rows && col_ok) ? (unsigned)(gcb + (long)row * g.row_stride) * 4u : UNIT_OOB;
+                sc[q][b] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsS, off, 0, 0));
+                add[q][b] = __builtin_amdgcn_raw_buffer_load_b32(rsBi, off, 0, 0) +
+                            __builtin_amdgcn_raw_buffer_load_b32(rsR, roff, 0, 0);
+            }
+            // the four rows of a group are four consecutive output channels of the lane's pixel: the
+            // packed residual arrives as one 32-bit load
+            res4[q] = __builtin_amdgcn_raw_buffer_load_b32(
+                rsP, (grow < g.packed_ld && col_ok) ? (unsigned)((long)gcol * g.packed_ld + grow) : UNIT_OOB, 0, 0);
+        }
+    };
     acc_t acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -786,19 +838,11 @@ igemm_kernel(const IgemmArgs g)
         UNIT_BARRIER();
     }
 
-    // ---- in-group split reduction and epilogue.  The unit of work is a GROUP: accumulator elements
-    // 4a..4a+3 of one MFMA tile, which a lane holds for four consecutive rows of its column.  With an
-    // in-group reduction split (WGK > 1) every wave parks all of its groups in LDS (16 bytes per lane,
-    // lane-contiguous, conflict free) and then owns every WGK-th group: it adds the WGK partial sums of
-    // its groups in fixed order and runs the epilogue for them, so the reduction and the epilogue are
-    // shared by all waves of the window instead of falling to one.  Without a split a wave owns the
-    // groups of its own accumulators, one MFMA tile at a time.
+    // ---- in-group split reduction and epilogue.  With an in-group reduction split every wave parks
+    // all of its groups in LDS (16 bytes per lane, lane-contiguous, conflict free) and then adds the WGK
+    // partial sums of the groups it owns in fixed order and runs the epilogue for them, so the reduction
+    // and the epilogue are shared by all waves of the window instead of falling to one.
     typedef elem_t v4e __attribute__((ext_vector_type(4)));
-    constexpr int NA = M::NACC, GPT = NA / 4;       // groups per MFMA tile
-    constexpr int NG = TM * TN * GPT;               // groups per wave window
-    static_assert(NG % WGK == 0, "the groups of a window must split evenly over its waves");
-    constexpr int UG = (WGK > 1) ? NG / WGK : GPT;  // groups handled together (their loads are issued first)
-    constexpr int NU = (WGK > 1) ? 1 : TM * TN;     // such units per wave
     const v4e *red = reinterpret_cast<const v4e *>(smem);
     const int wmn = wave % (WGM * WGN);
     if (WGK > 1) {
@@ -817,27 +861,22 @@ igemm_kernel(const IgemmArgs g)
     const elem_t *tile_base = reinterpret_cast<const elem_t *>(g.out) + (long)blockIdx.z * g.split_stride +
                               (long)row0 * g.row_stride;
     const __amdgpu_buffer_rsrc_t rsO = make_rsrc(tile_base, UNIT_OOB);        // raw stores; lanes are masked explicitly
-    const __amdgpu_buffer_rsrc_t rsS = make_rsrc(g.scale, (EPI == EPI_REQUANT) ? UNIT_OOB : 0u);
-    // bias: requantise bias, or the unsigned-operand correction of the raw epilogue (added once, by the
-    // first reduction slice; allocated in whole 256-byte blocks for the per-row form)
-    const __amdgpu_buffer_rsrc_t rsBi = make_rsrc(
-        g.bias, !(g.bias && (EPI == EPI_REQUANT || blockIdx.z == 0)) ? 0u
-                : (EPI == EPI_RAW && DT == DT_U8B)                    ? (unsigned)((g.rows * 4 + 255) & ~255) : UNIT_OOB);
-    const __amdgpu_buffer_rsrc_t rsR = make_rsrc(g.residual, g.residual ? UNIT_OOB : 0u);
-    const __amdgpu_buffer_rsrc_t rsP = make_rsrc(g.res_packed, g.res_packed ? UNIT_OOB : 0u);
+    // unsigned-operand correction of the raw epilogue (added once, by the first reduction slice; the
+    // per-row form is allocated in whole 256-byte blocks)
+    const __amdgpu_buffer_rsrc_t rsFix = make_rsrc(
+        g.bias, !(g.bias && blockIdx.z == 0) ? 0u : (DT == DT_U8B) ? (unsigned)((g.rows * 4 + 255) & ~255) : UNIT_OOB);
     elem_t *out = reinterpret_cast<elem_t *>(g.out);
 
 #pragma clang loop unroll(full)
     for (int u = 0; u < NU; ++u) {
         v4e val[UG];
-        int grow[UG], gcol[UG];                     // first row (of four) and column of each group
-        long gcb[UG];                               // offset of (row 0, column) in the NCHW / row-major output
+        int grow[UG], gcol[UG];
+        long gcb[UG];
 #pragma unroll
         for (int q = 0; q < UG; ++q) {
-            const int gidx = (WGK > 1) ? q * WGK + wk : u * GPT + q;
-            const int a4 = gidx % GPT, ij = gidx / GPT;
-            const int j = ij % TN, i = ij / TN;
+            group_at(u, q, grow[q], gcol[q], gcb[q]);
             if (WGK > 1) {
+                const int gidx = q * WGK + wk;
                 v4e v = red[((0 * WGM * WGN + wmn) * NG + gidx) * 64 + lane];
 #pragma unroll
                 for (int k2 = 1; k2 < WGK; ++k2) v += red[((k2 * WGM * WGN + wmn) * NG + gidx) * 64 + lane];
@@ -846,15 +885,6 @@ igemm_kernel(const IgemmArgs g)
                 // (u and q are unrolled constants here, so this indexes registers statically)
                 val[q] = v4e{acc[u / TN][u % TN][4 * q], acc[u / TN][u % TN][4 * q + 1],
                              acc[u / TN][u % TN][4 * q + 2], acc[u / TN][u % TN][4 * q + 3]};
-            }
-            grow[q] = row0 + wm * C::WTM + i * MF + acc_row<MF>(4 * a4, lane);
-            const int col = col0 + wn * C::WTN + j * MF + lrow;
-            gcol[q] = col;
-            if (CONV) {
-                const int n = (g.cols > g.cols_per_img) ? div_any(col, g.cols_per_img) : 0;
-                gcb[q] = (long)n * g.img_stride + (col - n * g.cols_per_img);
-            } else {
-                gcb[q] = col;
             }
         }
         if (EPI == EPI_RAW) {
@@ -865,9 +895,9 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
             for (int q = 0; q < UG; ++q) {
                 if (DT == DT_U8B) {
-                    fix[q] = buf_load16(rsBi, (unsigned)grow[q] * 4u);
+                    fix[q] = buf_load16(rsFix, (unsigned)grow[q] * 4u);
                 } else if (DT == DT_U8A) {
-                    const int f = (int)__builtin_amdgcn_raw_buffer_load_b32(rsBi, gcol[q] < col_end ? (unsigned)gcol[q] * 4u : UNIT_OOB, 0, 0);
+                    const int f = (int)__builtin_amdgcn_raw_buffer_load_b32(rsFix, gcol[q] < col_end ? (unsigned)gcol[q] * 4u : UNIT_OOB, 0, 0);
                     fix[q] = v4i{f, f, f, f};
                 } else {
                     fix[q] = v4i{0, 0, 0, 0};
@@ -887,29 +917,10 @@ igemm_kernel(const IgemmArgs g)
                 }
             }
         } else {
-            // Every load of the unit (scale, bias, both residual forms) is issued before its first store,
-            // through buffer descriptors: absent inputs get an empty range and masked lanes an offset
-            // beyond it, both read as zero, so the loads need no branches and the wave waits once.
+            // every load of the unit is issued before its first store
             float sc[UG][4];
             unsigned add[UG][4], res4[UG];          // modular sums: the caller bounds only the total
-#pragma unroll
-            for (int q = 0; q < UG; ++q) {
-                const bool col_ok = gcol[q] < col_end;
-#pragma unroll
-                for (int b = 0; b < 4; ++b) {
-                    const int row = grow[q] + b;
-                    const unsigned off = row < g.rows ? (unsigned)row * 4u : UNIT_OOB;
-                    const unsigned roff = (row < g.rows && col_ok) ? (unsigned)(gcb[q] + (long)row * g.row_stride) * 4u : UNIT_OOB;
-                    sc[q][b] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsS, off, 0, 0));
-                    add[q][b] = __builtin_amdgcn_raw_buffer_load_b32(rsBi, off, 0, 0) +
-                                __builtin_amdgcn_raw_buffer_load_b32(rsR, roff, 0, 0);
-                }
-                // the four rows of a group are four consecutive output channels of the lane's pixel: the
-                // packed residual arrives as one 32-bit load, and the int8 results leave as one 32-bit
-                // store into the packed (NHWC) output (padding channels stay zero)
-                res4[q] = __builtin_amdgcn_raw_buffer_load_b32(
-                    rsP, (grow[q] < g.packed_ld && col_ok) ? (unsigned)((long)gcol[q] * g.packed_ld + grow[q]) : UNIT_OOB, 0, 0);
-            }
+            requant_inputs(u, sc, add, res4);
 #pragma unroll
             for (int q = 0; q < UG; ++q) {
                 if (gcol[q] >= col_end) continue;
@@ -926,6 +937,8 @@ igemm_kernel(const IgemmArgs g)
                     if (g.out_i8) g.out_i8[addr] = (int8_t)v;
                     four |= ((unsigned)v & 0xffu) << (8 * b);
                 }
+                // the int8 results of a group leave as one 32-bit store into the packed (NHWC) output
+                // (padding channels stay zero)
                 if (g.out_packed && grow[q] < g.packed_ld)
                     *reinterpret_cast<unsigned *>(g.out_packed + (long)gcol[q] * g.packed_ld + grow[q]) = four;
             }
