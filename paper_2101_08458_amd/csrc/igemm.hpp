@@ -44,10 +44,10 @@ enum { EPI_RAW = 0, EPI_REQUANT = 1 };
 // transposed on the way from LDS into the fragments).  BSRC_NCHWS is the general form of the
 // direct read for one image and stride 1 with "same" padding: output pixel m of the flattened
 // image needs input pixel m + delta(tap) of every channel, so the B tile of a step is a window of
-// each channel row shifted by the tap's delta.  The window is fetched from the enclosing 16-byte
-// grid of the tensor (so rows need no alignment), held at twice the tile width, and the byte
-// shift (0..15, per channel row) is applied when the fragments are gathered; pixels whose tap
-// falls into the padding are masked there.
+// each channel row shifted by the tap's delta.  The 16-byte loads start at the window's exact byte (any
+// offset), so the tile lands in LDS as in the 1x1 mode and is read the same way; pixels whose tap
+// falls into the padding are masked after the read, and the two chunks that straddle the tensor's
+// start and end are patched from a copy of its first and last 16 bytes.
 enum { BSRC_PLAIN = 0, BSRC_GATHER = 1, BSRC_NCHW = 2, BSRC_NCHWS = 3 };
 
 struct IgemmArgs {
@@ -221,7 +221,6 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t r, uint8_t *lds, un
 template <int DT, int BM, int BN, int BKB, int WGM, int WGN, int WGK, int MF, int NST, int BSRC = BSRC_PLAIN>
 struct IgemmCfg {
     enum {
-        BMUL  = (BSRC == BSRC_NCHWS) ? 2 : 1,      // the shifted direct read holds B at twice the tile width
         NW    = WGM * WGN * WGK,                   // waves per workgroup
         NT    = NW * 64,
         NCH   = BKB / 16,                          // 16-byte chunks per row per step
@@ -233,11 +232,13 @@ struct IgemmCfg {
         CPL   = KSUBB / 16,                        // 16-byte chunks per MFMA along k
         RPI   = 1024 / BKB,                        // tile rows filled by one wave-level DMA
         IA    = BM / RPI / NW,                     // DMA instructions per wave per step, A tile
-        IB    = BN / RPI / NW * BMUL,
+        IB    = BN / RPI / NW,
         LPT   = IA + IB,
-        STAGE_BYTES  = (BM + BN * BMUL) * BKB,
+        STAGE_BYTES  = (BM + BN) * BKB,
+        EDGE_BYTES   = (BSRC == BSRC_NCHWS) ? 1024 : 0,    // shifted direct read: first and last 16 bytes of the tensor
+        RING_BYTES   = NST * STAGE_BYTES + EDGE_BYTES,
         REDUCE_BYTES = (WGK > 1) ? WGK * BM * BN * 4 : 0,
-        SMEM_BYTES   = (NST * STAGE_BYTES > REDUCE_BYTES) ? NST * STAGE_BYTES : REDUCE_BYTES,
+        SMEM_BYTES   = (RING_BYTES > REDUCE_BYTES) ? RING_BYTES : REDUCE_BYTES,
         FITS  = (SMEM_BYTES <= 160 * 1024) && ((NST - 1) * LPT <= 63),   // LDS capacity, vmcnt range
     };
     static_assert(BM % (WGM * MF) == 0 && BN % (WGN * MF) == 0, "wave tiles must be whole MFMA tiles");
@@ -273,10 +274,6 @@ igemm_kernel(const IgemmArgs g)
     constexpr int SWZ_ROWS = (ES == 1) ? 8 : 4;                             // rows one transposing read touches
     constexpr int SWZ_MOD  = (CPR / SWZ_UNIT < SWZ_ROWS) ? CPR / SWZ_UNIT : SWZ_ROWS;
     auto nchw_swz = [&](int r) { return SWZ_MOD > 1 ? SWZ_UNIT * ((r / SWZ_DIV) % SWZ_MOD) : 0; };
-    constexpr int PITCH = 2 * BN * ES;              // shifted mode: bytes per channel row of the B tile
-    constexpr int CPR2 = PITCH / 16;                // shifted mode: chunks per channel row
-    constexpr int CRPI2 = (CPR2 >= 64) ? 1 : 64 / CPR2;
-    static_assert(BSRC != BSRC_NCHWS || CPR2 <= 64, "a channel row must fit one DMA instruction");
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 
@@ -356,11 +353,12 @@ igemm_kernel(const IgemmArgs g)
         int r = (j * NW + wave) * RPI + lr_blk;
         bool valid = r < cols_here;
         if (BSRC == BSRC_NCHWS) {
-            // lane -> (channel row inside the step, 16-byte chunk of that row's window)
-            const int crow = (j * NW + wave) * CRPI2 + lane / CPR2;
+            // lane -> (channel row inside the DMA block, 16-byte chunk of that row's window of pixels);
+            // bd0 = byte offset of the chunk from the first byte the step needs of its first channel row
+            const int crow = (j * NW + wave) * CRPI + lane / CPR;
             bh0[j] = crow;
-            bd0[j] = crow * g.PQ * ES;              // byte offset of the channel row inside the step's block
-            bw0[j] = (lane % CPR2) * 16;
+            bd0[j] = (crow * g.PQ + ((lane % CPR) ^ nchw_swz(crow)) * EPC) * ES;
+            bw0[j] = 0;
             offB[j] = 0;
         } else if (BSRC == BSRC_NCHW) {
             // lane -> (channel row inside the DMA block, 16-byte chunk of pixels)
@@ -456,15 +454,18 @@ igemm_kernel(const IgemmArgs g)
             dma16(rsA, dst + j * NW * 1024, kok ? offA[j] + kbyte : UNIT_OOB);
         dst += BM * BKB;
         if (BSRC == BSRC_NCHWS) {
-            // first byte this step needs of channel row 0 of its block: pixel col0 + delta of
-            // channel it_cb*EPC (negative above the image: those pixels are masked at the read)
+            // first byte this step needs of channel row 0 of its block: pixel col0 + delta of channel
+            // it_cb*EPC.  The loads start at any byte, so every channel row lands with its window of
+            // pixels at the tile's own columns.  A chunk that is not wholly inside the tensor comes back
+            // as zeros: the few real pixels it holds (first and last channel only) are patched at the read
             const int delta = (it_r - g.ph) * g.W + (it_s - g.pw);
             const int base = (it_cb * EPC * g.PQ + col0 + delta) * ES;
             const bool step_ok = (kc - cT) < kend;
 #pragma unroll
             for (int j = 0; j < IB; ++j) {
-                const int off = ((base + bd0[j]) & ~15) + bw0[j];   // enclosing 16-byte grid of the tensor
-                dma16(rsB, dst + j * NW * 1024, (step_ok && off >= 0) ? (unsigned)off : UNIT_OOB);
+                const int off = base + bd0[j];
+                const bool ok = step_ok && off >= 0 && off + 16 <= (int)g.b_bytes;
+                dma16(rsB, dst + j * NW * 1024, ok ? (unsigned)off : UNIT_OOB);
             }
             next_tap(it_r, it_s, it_cb);
         } else if (BSRC == BSRC_NCHW) {
@@ -636,50 +637,7 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
             for (int i = 0; i < TM; ++i) fa[slot][i] ^= (int)0x80808080;
         }
-        if (BSRC == BSRC_NCHWS) {
-            // B tile is [channel][window of 2*BN pixels]; element (channel row, tile column c)
-            // sits at row*PITCH + c*ES + (byte shift of that row's window inside the 16-byte grid)
-            const int delta = (rt_r - g.ph) * g.W + (rt_s - g.pw);
-            // byte shift of channel row `row` of a chunk: the chunk's first row starts a whole
-            // number of 16-byte units after the step's first row (16 elements * pixels per row),
-            // so the shift depends on the row inside the chunk only and is wave-uniform
-            const int cbase = (col0 + delta) * ES;
-            const int pqes = g.PQ * ES;
-            const int dr = rt_r - g.ph, dc = rt_s - g.pw;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                unsigned w[4 * FW];
-#pragma unroll
-                for (int f = 0; f < FW; ++f) {
-                    const uint8_t *src = sB + (ch + f) * EPC * PITCH + (b_row + j * MF) * ES;
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        if (ES == 1) {
-                            unsigned b[4];
-#pragma unroll
-                            for (int e = 0; e < 4; ++e) {
-                                const int row = 4 * d + e;
-                                b[e] = src[row * PITCH + ((cbase + row * pqes) & 15)];
-                            }
-                            w[4 * f + d] = b[0] | (b[1] << 8) | (b[2] << 16) | (b[3] << 24);
-                        } else {
-                            unsigned h[2];
-#pragma unroll
-                            for (int e = 0; e < 2; ++e) {
-                                const int row = 2 * d + e;
-                                h[e] = *reinterpret_cast<const uint16_t *>(src + row * PITCH + ((cbase + row * pqes) & 15));
-                            }
-                            w[4 * f + d] = h[0] | (h[1] << 16);
-                        }
-                    }
-                }
-                // taps that fall into the padding (or columns past the image) contribute zero
-                const bool inside = (unsigned)(sp[j] + dr) < (unsigned)g.H && (unsigned)(sq[j] + dc) < (unsigned)g.W;
-#pragma unroll
-                for (int t = 0; t < 4 * FW; ++t) w[t] = inside ? w[t] : 0u;
-                fb[slot][j] = Frag<FW>::pack(w);
-            }
-        } else if (BSRC == BSRC_NCHW) {
+        if (BSRC == BSRC_NCHW || BSRC == BSRC_NCHWS) {
             // B tile is [channel][pixel], i.e. reduction-major: the transposing LDS reads of gfx950
             // hand every lane the 8 bytes of consecutive channels of its pixel column.  Within a group
             // of 16 lanes, lane t supplies the address of 8 contiguous bytes and lane n receives
@@ -715,6 +673,36 @@ igemm_kernel(const IgemmArgs g)
                         w[4 * f + 2 * h + 1] = (unsigned)r[1];
                     }
                 }
+                if (BSRC == BSRC_NCHWS) {
+                    // shifted read: channel row c of the step holds pixels col0 + delta .. of its channel,
+                    // delta = the tap's offset in the flattened image
+                    const int dr = rt_r - g.ph, dc = rt_s - g.pw;
+                    const int wstart = col0 + dr * g.W + dc;            // pixel index of tile column 0
+                    const int m = wn * C::WTN + j * MF + lrow;          // this lane's tile column
+                    const int pix = wstart + m, cstart = wstart + (m & ~(EPC - 1));
+                    const uint8_t *edge = smem + NST * C::STAGE_BYTES;
+                    constexpr unsigned EMASK = (ES == 1) ? 0xffu : 0xffffu;
+                    // The chunk that straddles the start of the tensor was not loaded: its pixels of the
+                    // first channel come from the tensor's first 16 bytes (kept at edge[0..15]) ...
+                    if (sub == 0 && wk == 0 && rt_cb == 0 && wstart < 0) {
+                        const bool fix = lchunk == 0 && cstart < 0 && pix >= 0;
+                        const uint8_t *src = edge + (fix ? pix * ES : 0);
+                        const unsigned v = (ES == 1) ? *src : *reinterpret_cast<const uint16_t *>(src);
+                        if (fix) w[0] = (w[0] & ~EMASK) | v;
+                    }
+                    // ... and likewise the chunk that straddles its end, for the last channel (edge[16..31])
+                    if (sub == NS - 1 && wk == WGK - 1 && rt_cb + NCH >= g.CB && wstart + BN > g.PQ) {
+                        const bool fix = lchunk == C::CPL - FW && cstart + EPC > g.PQ && pix < g.PQ;
+                        const uint8_t *src = edge + 16 + (fix ? (pix - (g.PQ - EPC)) * ES : 0);
+                        const unsigned v = (ES == 1) ? *src : *reinterpret_cast<const uint16_t *>(src);
+                        constexpr int SH = 32 - 8 * ES;
+                        if (fix) w[4 * FW - 1] = (w[4 * FW - 1] & ~(EMASK << SH)) | (v << SH);
+                    }
+                    // taps that fall into the padding (or columns past the image) contribute zero
+                    const bool inside = (unsigned)(sp[j] + dr) < (unsigned)g.H && (unsigned)(sq[j] + dc) < (unsigned)g.W;
+#pragma unroll
+                    for (int t = 0; t < 4 * FW; ++t) w[t] = inside ? w[t] : 0u;
+                }
                 fb[slot][j] = Frag<FW>::pack(w);
             }
         } else {
@@ -730,6 +718,9 @@ igemm_kernel(const IgemmArgs g)
 
     if (ks_begin < ks_end) {
         constexpr int AHEAD = WHOLE ? NST - 1 : NST;            // tiles in flight after the prologue
+        if (BSRC == BSRC_NCHWS && wave == 0)                    // first and last 16 bytes of the tensor (see read_frags)
+            dma16(rsB, smem + NST * C::STAGE_BYTES,
+                  lane == 0 ? 0u : lane == 1 ? (unsigned)(g.b_bytes - 16) : UNIT_OOB);
 #pragma unroll
         for (int t = 0; t < AHEAD; ++t) issue_tile(t);          // (zeros past the slice end)
         UNIT_WAIT_VM_LGKM0((AHEAD - 1) * C::LPT);               // own part of tile 0 has landed

@@ -69,21 +69,16 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
     // main-loop step of a small tile costs ~0.2 us of DMA latency, while the extra reduce
     // launch costs ~3 us, so it pays from about 24 steps on (slices of ~6 steps).
     int split = 1;
-    if (bsrc == BSRC_NCHWS) {
-        // the shifted direct read moves twice the B bytes per step and gathers them bytewise
-        // (~0.4 us per step of a small tile), so splitting pays from about 12 steps on; slices
-        // of ~3 steps measured best on the 14x14 and 7x7 layers
-        if (ksteps >= 12 && nt <= CUS / 2) {
-            split = ksteps / 3;
-            if (split > 6) split = 6;
-            int cap = (int)(2 * CUS / nt);
-            if (split > cap) split = cap;
-        }
-    } else if (ksteps >= 24 && nt <= CUS / 2) {
+    if (ksteps >= 24 && nt <= CUS / 2) {
         split = ksteps / 6;
         int cap = (int)(2 * CUS / nt);
         if (split > cap) split = cap;
         if (split < 1) split = 1;
+    } else if (bsrc == BSRC_NCHWS && ksteps >= 12 && nt <= CUS / 4) {
+        // the shifted direct read has no pack launch in front of it to hide under, and its steps are a
+        // little longer (unaligned 16-byte loads): with a quarter of the chip or less busy, slices of
+        // about 4 steps measured best (the 14x14 layers)
+        split = ksteps / 4;
     }
     int fs = env_int("UNIT_SPLITK", -1);
     if (fs >= 1) split = fs;

@@ -204,9 +204,13 @@ bool nchw_shift_ok(const ConvND *d, int dtype, const ConvGeom &g, const void *x,
     if (d->stride_h != 1 || d->stride_w != 1) return false;
     if (2 * d->pad_h != d->r - 1 || 2 * d->pad_w != d->s - 1) return false;
     if (reinterpret_cast<uintptr_t>(x) & 15) return false;
+    // only the first and the last channel may have needed pixels in a 16-byte chunk that crosses the
+    // tensor's start or end (the kernel patches exactly those): true once an image holds a chunk more
+    // than the largest tap offset
+    const long px = (long)d->h * d->w;
+    if (px < (long)d->pad_h * d->w + d->pad_w + chunk_elems(dtype)) return false;
+    if ((long)d->c * px * elem_size(dtype) >= (1L << 31)) return false;       // byte offsets are 32-bit
     TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_NCHWS);
-    const TileCfg &t = g_tiles[ch.tile];
-    if ((long)(t.bm + 2 * t.bn) * t.bkb * t.nst > 160 * 1024) return false;   // twice-wide B tile exceeds the LDS
     return ((long)d->c * elem_size(dtype)) % g_tiles[ch.tile].bkb == 0;
 }
 

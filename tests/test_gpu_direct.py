@@ -33,6 +33,9 @@ CASES = [
     (wl.ConvShape(64, 12, 12, 64, 3, 3, 1, 1), PACKED, SHIFTED),       # 64 channels: one fp16 step, half an int8 step
     (wl.ConvShape(128, 56, 56, 32, 3, 3, 1, 1), SHIFTED, SHIFTED),     # many column tiles
     (wl.ConvShape(128, 12, 12, 16, 3, 3, 1, 1), SHIFTED, SHIFTED),     # 16 output channels: the narrow tile
+    (wl.ConvShape(128, 4, 4, 32, 3, 3, 1, 1), PACKED, SHIFTED),        # 16 pixels: too few for 16 one-byte elements per chunk
+    (wl.ConvShape(128, 5, 5, 48, 3, 3, 1, 1), SHIFTED, SHIFTED),       # smallest image the one-byte types take
+    (wl.ConvShape(128, 7, 7, 48, 5, 5, 1, 2), SHIFTED, SHIFTED),       # largest tap offsets relative to the image
 ]
 
 
@@ -60,8 +63,6 @@ def test_shifted_direct_i8(case):
                                         ws_bytes(unit.unit_conv2d_wpacked_workspace(d, unit.UNIT_I8)))
             torch.cuda.synchronize()
         assert same(host(y), ref, f"tile {tile} split {split} mode {mode}")
-    with forced(tile=0):
-        assert unit.unit_conv2d_input_mode(d, unit.UNIT_I8, xd) != SHIFTED      # no kernel for the largest tile
 
 
 @pytest.mark.parametrize("case", range(len(CASES)))
@@ -103,7 +104,7 @@ def test_shifted_direct_f16_bf16_fp8(case):
 def test_shifted_direct_border_taps_exact():
     """All-ones image and filters: every output equals the number of taps inside the image times
     the channel count, so a wrong border mask or a wrong window shift shows as a wrong count."""
-    for h, w, r, pad in [(14, 14, 3, 1), (7, 9, 3, 1), (6, 5, 5, 2), (5, 7, 7, 3)]:
+    for h, w, r, pad in [(14, 14, 3, 1), (7, 9, 3, 1), (6, 5, 5, 2), (8, 7, 7, 3)]:
         sh = wl.ConvShape(128, h, w, 32, r, r, 1, pad)
         d = _desc(sh)
         x = np.ones((1, 128, h, w), np.int8)
@@ -134,11 +135,12 @@ def test_modes_that_must_not_use_the_shifted_read():
 
 
 def test_shifted_direct_odd_geometries():
-    """Windows with different extents per axis, single-row and single-pixel images."""
+    """Windows with different extents per axis, narrow images, and images too small for the shifted read
+    (fewer pixels than the largest tap offset plus one 16-byte chunk), which must fall back to packing."""
     geoms = [   # (c, h, w, k, r, s, pad_h, pad_w)
         (128, 6, 9, 24, 1, 3, 0, 1), (128, 9, 6, 24, 3, 1, 1, 0), (128, 1, 17, 40, 3, 3, 1, 1),
         (128, 13, 1, 40, 3, 3, 1, 1), (256, 1, 1, 64, 3, 3, 1, 1), (128, 2, 2, 33, 5, 5, 2, 2),
-        (128, 3, 40, 16, 3, 7, 1, 3),
+        (128, 3, 40, 16, 3, 7, 1, 3), (128, 2, 19, 40, 3, 3, 1, 1), (128, 17, 2, 40, 3, 3, 1, 1),
     ]
     for i, (c, h, w, k, r, s, ph, pw) in enumerate(geoms):
         d = unit.conv_desc(1, c, h, w, k, r, s, (1, 1), (ph, pw))
@@ -152,7 +154,7 @@ def test_shifted_direct_odd_geometries():
                 mode = unit.unit_conv2d_input_mode(d, unit.UNIT_I8, xd)
                 announce("shifted odd geometry", (c, h, w, k, r, s, ph, pw), "tile", tile, "mode", mode)
                 if tile is None and k > 16:
-                    assert mode == SHIFTED
+                    assert mode == (SHIFTED if h * w >= ph * w + pw + 16 else PACKED)
                 y = torch.full(ref.shape, -7, dtype=torch.int32, device="cuda:0")
                 unit.unit_conv2d_i8(d, xd, dev(wt), y, None, None, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_I8)))
                 torch.cuda.synchronize()
