@@ -126,8 +126,9 @@ int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_inf
  *   UNIT_INPUT_PACKED          pack_act into the workspace, then the gather kernel
  *   UNIT_INPUT_DIRECT          1x1 stride-1 unpadded conv (any batch, any image size): the main
  *                              kernel reads NCHW itself (no pack_act launch)
- *   UNIT_INPUT_DIRECT_SHIFTED  one image, stride 1, output grid equal to the input grid ("same"
- *                              padding, any window), whole reduction steps inside one tap: the main
+ *   UNIT_INPUT_DIRECT_SHIFTED  stride 1, output grid equal to the input grid ("same" padding, any
+ *                              window), whole reduction steps inside one tap, and a layer small
+ *                              enough to be launch-bound (one image, or a few small ones): the main
  *                              kernel reads per-tap shifted windows of the NCHW channel rows, any
  *                              row alignment (no pack_act launch)
  * Returns the mode (>= 0) or a negative unit_status.
@@ -206,7 +207,8 @@ int unit_conv2d_packed_f16(const unit_conv2d_desc *d, const void *x_packed, cons
  * inference loop whose weights were packed once.  Activations are packed into the workspace
  * first, except where the main kernel can read NCHW itself (16-byte aligned x, no requantise;
  * see unit_conv2d_input_mode): 1x1 / stride-1 / unpadded convs of any batch and image size, and
- * stride-1 "same"-padded convs of one image.  Outputs as in unit_conv2d_i8 / unit_conv2d_f16.
+ * small stride-1 "same"-padded convs (one image, or a few small ones).  Outputs as in unit_conv2d_i8 /
+ * unit_conv2d_f16.
  */
 size_t unit_conv2d_wpacked_workspace(const unit_conv2d_desc *d, int dtype);
 int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const void *w_packed,

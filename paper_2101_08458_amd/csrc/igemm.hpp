@@ -289,7 +289,7 @@ igemm_kernel(const IgemmArgs g)
     // order in bands of 8 row-tiles so the tiles resident together share A and B rows.
     const int tiles_m = (g.rows + BM - 1) / BM;
     const int tiles_img = (g.PQ + BN - 1) / BN;     // per-image tiling only
-    const bool per_img = (BSRC == BSRC_NCHW) && g.per_img;
+    const bool per_img = (BSRC == BSRC_NCHW || BSRC == BSRC_NCHWS) && g.per_img;
     const int tiles_n = per_img ? tiles_img * div_any(g.cols, g.PQ) : (g.cols + BN - 1) / BN;
     const int ntiles  = tiles_m * tiles_n;
     int bid = blockIdx.x;
@@ -355,9 +355,12 @@ igemm_kernel(const IgemmArgs g)
         if (BSRC == BSRC_NCHWS) {
             // lane -> (channel row inside the DMA block, 16-byte chunk of that row's window of pixels);
             // bd0 = byte offset of the chunk from the first byte the step needs of its first channel row
+            // (a chunk of pixels lies inside one image, as in the 1x1 mode)
             const int crow = (j * NW + wave) * CRPI + lane / CPR;
+            const int px = col0 + ((lane % CPR) ^ nchw_swz(crow)) * EPC;
+            const int img = (g.cols > g.PQ) ? div_any(px, g.PQ) : 0;
             bh0[j] = crow;
-            bd0[j] = (crow * g.PQ + ((lane % CPR) ^ nchw_swz(crow)) * EPC) * ES;
+            bd0[j] = ((img * g.Cin + crow) * g.PQ + (px - img * g.PQ)) * ES;
             bw0[j] = 0;
             offB[j] = 0;
         } else if (BSRC == BSRC_NCHW) {
@@ -459,7 +462,7 @@ igemm_kernel(const IgemmArgs g)
             // pixels at the tile's own columns.  A chunk that is not wholly inside the tensor comes back
             // as zeros: the few real pixels it holds (first and last channel only) are patched at the read
             const int delta = (it_r - g.ph) * g.W + (it_s - g.pw);
-            const int base = (it_cb * EPC * g.PQ + col0 + delta) * ES;
+            const int base = (it_cb * EPC * g.PQ + delta) * ES;
             const bool step_ok = (kc - cT) < kend;
 #pragma unroll
             for (int j = 0; j < IB; ++j) {
@@ -542,9 +545,10 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = col0 + b_row + j * MF;
-            const int p = div_any(col, g.W);
-            sp[j] = (col < g.cols) ? p : -0x100000;
-            sq[j] = col - p * g.W;
+            const int pin = (g.cols > g.PQ) ? col - div_any(col, g.PQ) * g.PQ : col;    // pixel inside its image
+            const int p = div_any(pin, g.W);
+            sp[j] = (col < col_end) ? p : -0x100000;
+            sq[j] = pin - p * g.W;
         }
     }
 
@@ -675,9 +679,10 @@ igemm_kernel(const IgemmArgs g)
                 }
                 if (BSRC == BSRC_NCHWS) {
                     // shifted read: channel row c of the step holds pixels col0 + delta .. of its channel,
-                    // delta = the tap's offset in the flattened image
+                    // delta = the tap's offset in the flattened image.  The tensor's start can only be
+                    // straddled in the first image, where columns are pixel indices; its end in the last
                     const int dr = rt_r - g.ph, dc = rt_s - g.pw;
-                    const int wstart = col0 + dr * g.W + dc;            // pixel index of tile column 0
+                    const int wstart = col0 + dr * g.W + dc;            // pixel index of tile column 0 (first image)
                     const int m = wn * C::WTN + j * MF + lrow;          // this lane's tile column
                     const int pix = wstart + m, cstart = wstart + (m & ~(EPC - 1));
                     const uint8_t *edge = smem + NST * C::STAGE_BYTES;
@@ -691,9 +696,11 @@ igemm_kernel(const IgemmArgs g)
                         if (fix) w[0] = (w[0] & ~EMASK) | v;
                     }
                     // ... and likewise the chunk that straddles its end, for the last channel (edge[16..31])
-                    if (sub == NS - 1 && wk == WGK - 1 && rt_cb + NCH >= g.CB && wstart + BN > g.PQ) {
-                        const bool fix = lchunk == C::CPL - FW && cstart + EPC > g.PQ && pix < g.PQ;
-                        const uint8_t *src = edge + 16 + (fix ? (pix - (g.PQ - EPC)) * ES : 0);
+                    const int last0 = g.cols - g.PQ;                    // first column of the last image
+                    if (sub == NS - 1 && wk == WGK - 1 && rt_cb + NCH >= g.CB && wstart - last0 + BN > g.PQ) {
+                        const int pixl = pix - last0, cstartl = cstart - last0;
+                        const bool fix = lchunk == C::CPL - FW && cstartl + EPC > g.PQ && pixl < g.PQ;
+                        const uint8_t *src = edge + 16 + (fix ? (pixl - (g.PQ - EPC)) * ES : 0);
                         const unsigned v = (ES == 1) ? *src : *reinterpret_cast<const uint16_t *>(src);
                         constexpr int SH = 32 - 8 * ES;
                         if (fix) w[4 * FW - 1] = (w[4 * FW - 1] & ~(EMASK << SH)) | (v << SH);

@@ -196,11 +196,11 @@ bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requan
            d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr && dtype != UNIT_U8I8 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
 }
 
-// The general direct read (BSRC_NCHWS): one image, stride 1, output grid equal to the input grid
+// The general direct read (BSRC_NCHWS): stride 1, output grid equal to the input grid
 // ("same" padding), whole steps inside one tap, and a tile shape that has a kernel in this mode.
 bool nchw_shift_ok(const ConvND *d, int dtype, const ConvGeom &g, const void *x, const unit_requant *rq)
 {
-    if (rq || dtype == UNIT_U8I8 || d->n != 1 || d->d != 1 || d->t != 1) return false;
+    if (rq || dtype == UNIT_U8I8 || d->d != 1 || d->t != 1) return false;
     if (d->stride_h != 1 || d->stride_w != 1) return false;
     if (2 * d->pad_h != d->r - 1 || 2 * d->pad_w != d->s - 1) return false;
     if (reinterpret_cast<uintptr_t>(x) & 15) return false;
@@ -209,9 +209,17 @@ bool nchw_shift_ok(const ConvND *d, int dtype, const ConvGeom &g, const void *x,
     // than the largest tap offset
     const long px = (long)d->h * d->w;
     if (px < (long)d->pad_h * d->w + d->pad_w + chunk_elems(dtype)) return false;
-    if ((long)d->c * px * elem_size(dtype) >= (1L << 31)) return false;       // byte offsets are 32-bit
+    if ((long)d->n * d->c * px * elem_size(dtype) >= (1L << 31)) return false;    // byte offsets are 32-bit
+    // The unaligned loads and the border masks make a step of this mode a little dearer than a gather step; what it
+    // saves is the pack_act launch.  That pays while the layer is launch-bound (one image, a few small ones);
+    // measured on the 3x3 layers of the ResNet-50 set, fp16: at batch 16 packing first is 5-25 % faster.
+    if ((long)g.rows * g.cols * g.kchunks * 16 > (256L << 20)) return false;
     TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_NCHWS);
-    return ((long)d->c * elem_size(dtype)) % g_tiles[ch.tile].bkb == 0;
+    const TileCfg &t = g_tiles[ch.tile];
+    // several images whose pixels are not whole 16-byte chunks are tiled one image at a time: not worth it
+    // when the tiles of an image would be more than half empty
+    if (d->n > 1 && px % chunk_elems(dtype) != 0 && (px + t.bn - 1) / t.bn * t.bn > 2 * px) return false;
+    return ((long)d->c * elem_size(dtype)) % t.bkb == 0;
 }
 
 // `xp` is the packed activation tensor, or (direct modes) the caller's NCHW tensor itself.
@@ -251,7 +259,7 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
         a.b_bytes += slack;
     }
     a.Cin = d->c;
-    a.per_img = (bsrc == BSRC_NCHW && d->n > 1 && ((long)d->d * d->h * d->w) % chunk_elems(dtype) != 0) ? 1 : 0;
+    a.per_img = (nchw_direct && d->n > 1 && ((long)d->d * d->h * d->w) % chunk_elems(dtype) != 0) ? 1 : 0;
     a.T = d->t;  a.R = d->r;  a.S = d->s;
     a.sd = d->stride_d;  a.sh = d->stride_h;  a.sw = d->stride_w;  a.pd = d->pad_d;  a.ph = d->pad_h;  a.pw = d->pad_w;
     a.out = y_raw;  a.row_stride = a.PQ;  a.img_stride = (long)d->k * a.PQ;  a.cols_per_img = a.PQ;

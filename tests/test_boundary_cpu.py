@@ -127,13 +127,18 @@ def test_input_mode_decisions_are_host_logic(lib):
     # 49-byte rows: some loads start inside a dword, so the buffer range gets 3 bytes of slack -- only
     # where those bytes lie on the tensor's own last page (16*512*49 bytes are 98 whole pages)
     assert mode(16, 512, 7, 7, 2048, 1, 1, 1, 0) == P             # tensor ends on a page boundary
+    assert mode(2, 512, 7, 7, 2048, 1, 1, 1, 0, ptr=x + 3072) == S           # same for a small batch (ends at x + 53248): the
+                                                                  # shifted read needs no slack and takes it
     assert mode(16, 512, 7, 7, 2048, 1, 1, 1, 0, ptr=x + 512) == D   # same tensor, 512 bytes further on
     assert mode(1, 512, 7, 7, 2048, 1, 1, 1, 0) == D              # 49-byte rows: no alignment needed
     assert mode(1, 256, 14, 14, 256, 3, 3, 1, 1) == S             # 3x3, same padding
     assert mode(1, 128, 11, 10, 33, 5, 5, 1, 2) == S
     assert mode(1, 64, 56, 56, 64, 3, 3, 1, 1) == P               # 64 int8 channels: half a step
     assert mode(1, 64, 56, 56, 64, 3, 3, 1, 1, dtype=unit.UNIT_F16) == S
-    assert mode(2, 256, 14, 14, 256, 3, 3, 1, 1) == P             # more than one image
+    assert mode(2, 256, 14, 14, 256, 3, 3, 1, 1) == S             # batches: columns tiled per image (196 = 12.25 chunks)
+    assert mode(2, 128, 28, 28, 128, 3, 3, 1, 1) == S             # batches: whole chunks per image
+    assert mode(16, 128, 28, 28, 128, 3, 3, 1, 1) == P            # large batches: packing first is cheaper than unaligned loads
+    assert mode(64, 128, 5, 5, 512, 3, 3, 1, 1) == P              # 25-pixel images would leave 64-wide tiles mostly empty
     assert mode(1, 256, 14, 14, 256, 3, 3, 2, 1) == P             # stride 2
     assert mode(1, 256, 14, 14, 256, 3, 3, 1, 0) == P             # output grid smaller than the input
     assert mode(1, 256, 14, 14, 256, 3, 3, 1, 1, dtype=unit.UNIT_U8I8) == P

@@ -1,4 +1,4 @@
-"""GPU parity for the shifted direct read of NCHW activations (one image, stride 1, "same"
+"""GPU parity for the shifted direct read of NCHW activations (stride 1, "same"
 padding): the main kernel fetches per-tap shifted windows of the channel rows instead of
 running pack_act first.  Every case is compared with the oracle on every tile shape that has
 a kernel in this mode and with a forced split; the input mode the library reports is checked
@@ -101,6 +101,65 @@ def test_shifted_direct_f16_bf16_fp8(case):
                 assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), (name, tile, split)
 
 
+BATCHES = [   # (n, shape): images of whole 16-byte chunks (tiles span images) and others (tiled per image)
+    (3, wl.ConvShape(128, 8, 8, 40, 3, 3, 1, 1)),       # 64 pixels: a 256-wide tile holds four images
+    (2, wl.ConvShape(128, 12, 12, 33, 3, 3, 1, 1)),     # 144 pixels: whole chunks for one-byte elements too
+    (3, wl.ConvShape(128, 14, 14, 48, 3, 3, 1, 1)),     # 196 pixels: per image for every type
+    (5, wl.ConvShape(128, 9, 7, 24, 5, 3, 1, (2, 1))),  # 63 pixels, different window extents
+    (2, wl.ConvShape(256, 28, 28, 32, 3, 3, 1, 1)),
+]
+
+
+@pytest.mark.parametrize("case", range(len(BATCHES)))
+def test_shifted_direct_batches(case):
+    """Several images: every image's border taps are masked on its own, the windows of an image's first
+    channel reach back into the previous image (masked), and only the first image's first channel and the
+    last image's last channel can touch the tensor's ends."""
+    n, sh = BATCHES[case]
+    pad = sh.pad if isinstance(sh.pad, tuple) else (sh.pad, sh.pad)
+    d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, (1, 1), pad)
+    g = wl.rng(66, case)
+    x = wl.int8_activations(g, (n, sh.c, sh.h, sh.w))
+    w = wl.int8_weights(g, (sh.k, sh.c, sh.r, sh.s))
+    ref = oracle.conv2d_i8(x, w, (1, 1), pad)
+    xd, wd = dev(x), dev(w)
+    for tile, split in [(None, None)] + [(t, 1) for t in ALL_TILES] + [(3, 2), (4, 3)]:
+        with forced(tile=tile, split=split):
+            mode = unit.unit_conv2d_input_mode(d, unit.UNIT_I8, xd)
+            announce("shifted batch i8", n, tuple(sh), "tile", tile, "split", split, "mode", mode)
+            if tile is None:
+                assert mode == SHIFTED
+            y = torch.full(ref.shape, -7, dtype=torch.int32, device="cuda:0")
+            unit.unit_conv2d_i8(d, xd, wd, y, None, None, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_I8)))
+            torch.cuda.synchronize()
+        assert same(host(y), ref, f"batch case {case} tile {tile} split {split} mode {mode}")
+    kred = sh.c * sh.r * sh.s
+    for name, ut, gen, orc, fn in [
+        ("f16", unit.UNIT_F16, wl.conv_inputs_f16, lambda a, b: (oracle.conv2d_f16(a, b, (1, 1), pad),) +
+         oracle.conv2d_f16_f64(a, b, (1, 1), pad), unit.unit_conv2d_f16),
+        ("fp8", unit.UNIT_FP8, wl.conv_inputs_fp8, lambda a, b: oracle.conv2d_fp8(a, b, (1, 1), pad), unit.unit_conv2d_fp8),
+    ]:
+        xf, wf = gen(wl.ConvShape(sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, 1, 0), n, 67, case)
+        reff, truth, mag = orc(xf, wf)
+        xfd, wfd = dev(xf), dev(wf)
+        for tile in (None, 1, 3, 4):
+            with forced(tile=tile):
+                mode = unit.unit_conv2d_input_mode(d, ut, xfd)
+                announce("shifted batch", name, n, tuple(sh), "tile", tile, "mode", mode)
+                if tile is None:
+                    assert mode == SHIFTED
+                y = torch.empty(reff.shape, dtype=torch.float32, device="cuda:0")
+                fn(d, xfd, wfd, y, ws_bytes(unit.unit_conv2d_workspace(d, ut)))
+                torch.cuda.synchronize()
+            got = host(y)
+            if name == "fp8":
+                assert fp8_rel_err(got, reff) <= 1e-3, (name, tile)
+                assert np.all(np.abs(got - truth) <= fp8_bound(kred, mag)), (name, tile)
+            else:
+                assert f16_rel_err(got, reff, kred) <= 1e-3, (name, tile)
+                assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), (name, tile)
+
+
 def test_shifted_direct_border_taps_exact():
     """All-ones image and filters: every output equals the number of taps inside the image times
     the channel count, so a wrong border mask or a wrong window shift shows as a wrong count."""
@@ -124,7 +183,7 @@ def test_shifted_direct_border_taps_exact():
 def test_modes_that_must_not_use_the_shifted_read():
     xd = ws_bytes(1 << 20)
     mode = lambda d, ut=unit.UNIT_I8, x=xd: unit.unit_conv2d_input_mode(d, ut, x)
-    assert mode(unit.conv_desc(2, 128, 14, 14, 64, 3, 3, 1, 1)) == PACKED          # two images
+    assert mode(unit.conv_desc(64, 128, 5, 5, 512, 3, 3, 1, 1)) == PACKED          # small images, one mostly empty 64-wide tile each
     assert mode(unit.conv_desc(1, 128, 14, 14, 64, 3, 3, 2, 1)) == PACKED          # stride 2
     assert mode(unit.conv_desc(1, 128, 14, 14, 64, 3, 3, 1, 0)) == PACKED          # output grid smaller than input
     assert mode(unit.conv_desc(1, 120, 14, 14, 64, 3, 3, 1, 1)) == PACKED          # channels not a whole step
