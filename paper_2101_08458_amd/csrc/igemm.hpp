@@ -61,6 +61,8 @@ struct IgemmArgs {
     int D, H, W, CB, P, Q, PQ, T, R, S, sd, sh, sw, pd, ph, pw;
     int Cin;                                        // NCHW-direct kernels: real channel count
     int row_runs;                                   // tile order: consecutive workgroups of an XCD share a row tile
+    int edge;                                       // NCHW-direct 1x1: rows are not dword-aligned, so the 16-byte chunk
+                                                    // that crosses the tensor's end is not loaded but patched (see read_frags)
     int per_img;                                    // NCHW-direct: column tiles never straddle images (each image's
                                                     // pixels are tiled on their own; needed when an image does not
                                                     // hold a whole number of 16-byte pixel chunks)
@@ -211,6 +213,27 @@ __device__ __forceinline__ void dma16(__amdgpu_buffer_rsrc_t r, uint8_t *lds, un
 {
     __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void *)lds, 16, off, 0, 0, 0);
 }
+// Transposing LDS reads (ds_read_b64_tr_b8 / _b16) as inline assembly.  Through the compiler's builtins every such
+// read is preceded by s_waitcnt vmcnt(0): the compiler cannot tell which LDS bytes the global -> LDS loads in flight
+// will write, so it waits for all of them, which takes the load pipeline down to one tile in flight.  The kernel
+// orders tiles and reads itself (stage ring, barriers, explicit vmcnt waits), so it issues these reads unseen by
+// that analysis.  The compiler then does not wait for their results either: the kernel waits itself (an s_waitcnt
+// the compiler sees, so that its own bookkeeping of the ordinary LDS reads stays exact) and then passes every such
+// fragment through lds_tr_done(), an empty statement with the fragment as in/out operand, so that no use of it can
+// be scheduled above the wait.
+template <int ES, int OFF> __device__ __forceinline__ v2i lds_tr(unsigned lds_addr)
+{
+    v2i r;
+    if (ES == 1) asm volatile("ds_read_b64_tr_b8 %0, %1 offset:%2" : "=v"(r) : "v"(lds_addr), "n"(OFF) : "memory");
+    else         asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(lds_addr), "n"(OFF) : "memory");
+    return r;
+}
+template <typename F> __device__ __forceinline__ void lds_tr_done(F &frag)
+{
+    asm volatile("" : "+v"(frag));
+}
+// s_waitcnt lgkmcnt(0) only
+#define UNIT_WAIT_LGKM0() __builtin_amdgcn_s_waitcnt((0xF | (0x3 << 14) | (0x7 << 4)))
 // s_waitcnt vmcnt(N) lgkmcnt(0)  (expcnt left alone); N <= 63
 #define UNIT_WAIT_VM_LGKM0(N) __builtin_amdgcn_s_waitcnt((((N) & 0xF) | (((N) >> 4) << 14) | (0x7 << 4)))
 // s_waitcnt vmcnt(N) only (lgkmcnt and expcnt left alone)
@@ -235,7 +258,7 @@ struct IgemmCfg {
         IB    = BN / RPI / NW,
         LPT   = IA + IB,
         STAGE_BYTES  = (BM + BN) * BKB,
-        EDGE_BYTES   = (BSRC == BSRC_NCHWS) ? 1024 : 0,    // shifted direct read: first and last 16 bytes of the tensor
+        EDGE_BYTES   = (BSRC == BSRC_NCHWS || BSRC == BSRC_NCHW) ? 1024 : 0,   // direct reads: first and last 16 bytes of the tensor
         RING_BYTES   = NST * STAGE_BYTES + EDGE_BYTES,
         REDUCE_BYTES = (WGK > 1) ? WGK * BM * BN * 4 : 0,
         SMEM_BYTES   = (RING_BYTES > REDUCE_BYTES) ? RING_BYTES : REDUCE_BYTES,
@@ -439,6 +462,11 @@ igemm_kernel(const IgemmArgs g)
         it_r = rt_r = tap / g.S;
         it_s = rt_s = tap - it_r * g.S;
     }
+    // (the divisions above leave their results in vector registers; the tap walk is scalar work)
+    it_r = rt_r = __builtin_amdgcn_readfirstlane(it_r);
+    it_s = rt_s = __builtin_amdgcn_readfirstlane(it_s);
+    it_cb = rt_cb = __builtin_amdgcn_readfirstlane(it_cb);
+    if (BSRC == BSRC_NCHW) rt_cb = ks_begin * NCH;  // 1x1 mode: first reduction chunk of the step being read
     auto next_tap = [&](int &tr, int &ts, int &tcb) {
         tcb += NCH;
         if (tcb >= g.CB) {
@@ -476,10 +504,13 @@ igemm_kernel(const IgemmArgs g)
             // count or past the slice end come back as zeros
             const int chan0 = (kc - cT) * EPC;
             const int chan_end = (kend * EPC < g.Cin) ? kend * EPC : g.Cin;
+            // (g.edge: a chunk that is not wholly inside the tensor is not loaded: see read_frags)
+            const unsigned lim = g.edge ? (unsigned)g.b_bytes : 0xffffffffu;
 #pragma unroll
             for (int j = 0; j < IB; ++j) {
-                bool ok = chan0 + bh0[j] < chan_end;
-                dma16(rsB, dst + j * NW * 1024, ok ? offB[j] + (unsigned)(chan0 * g.PQ * ES) : UNIT_OOB);
+                const unsigned off = offB[j] + (unsigned)(chan0 * g.PQ * ES);
+                const bool ok = chan0 + bh0[j] < chan_end && off + 16u <= lim;
+                dma16(rsB, dst + j * NW * 1024, ok ? off : UNIT_OOB);
             }
         } else if (BSRC == BSRC_GATHER && uni_tap) {
             const bool step_ok = (kc - cT) < kend;
@@ -630,6 +661,33 @@ igemm_kernel(const IgemmArgs g)
     constexpr bool WHOLE = (TM * TN <= 4) && NST >= 3;      // (the register-prefetch schedule needs three LDS stages)
     constexpr int NSLOT = WHOLE ? 2 * NS : 2;
     frag_t fa[NSLOT][TM], fb[NSLOT][TN];
+    // Shifted direct read: what remains to be done to the B fragments of a slot when they are used (border mask,
+    // edge elements).  It is applied then and not at the read, so that nothing waits for the LDS data early.
+    bool b_in[NSLOT][TN], b_fs[NSLOT][TN], b_fe[NSLOT][TN];
+    unsigned b_vs[NSLOT][TN], b_ve[NSLOT][TN];
+    auto finish_frags = [&](int slot) {
+        if (BSRC != BSRC_NCHW && BSRC != BSRC_NCHWS) return;
+        UNIT_WAIT_LGKM0();                                      // (the transposing reads: see lds_tr)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) lds_tr_done(fb[slot][j]);
+        constexpr bool TAPS = (BSRC == BSRC_NCHWS);
+        if (!TAPS && !g.edge) return;
+        constexpr unsigned EMASK = (ES == 1) ? 0xffu : 0xffffu;
+        constexpr int SH = 32 - 8 * ES;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            frag_t f = fb[slot][j];
+            // (selects, no branches: the MFMA schedule wants one basic block per step)
+            if (TAPS) f[0] = b_fs[slot][j] ? (int)(((unsigned)f[0] & ~EMASK) | b_vs[slot][j]) : f[0];
+            f[4 * FW - 1] = b_fe[slot][j] ? (int)(((unsigned)f[4 * FW - 1] & ~(EMASK << SH)) | (b_ve[slot][j] << SH))
+                                          : f[4 * FW - 1];
+            if (TAPS) {
+#pragma unroll
+                for (int t = 0; t < 4 * FW; ++t) f[t] = b_in[slot][j] ? f[t] : 0;
+            }
+            fb[slot][j] = f;
+        }
+    };
     auto read_frags = [&](int stage, int sub, int slot) {
         const uint8_t *sA = smem + stage * C::STAGE_BYTES;
         const uint8_t *sB = sA + BM * BKB;
@@ -662,53 +720,48 @@ igemm_kernel(const IgemmArgs g)
                     const int cbyte = (wn * C::WTN + j * MF + ncol) * ES;           // logical byte column of the row
                     const uint8_t *src = sB + ((ch + f) * EPC + trow) * (BN * ES) +
                                          ((((cbyte >> 4) ^ nchw_swz(trow)) << 4) | (cbyte & 15));
-#pragma unroll
-                    for (int h = 0; h < EPC / RPR; ++h) {
-                        typedef __attribute__((address_space(3))) v2i lds_v2i;
-                        typedef __attribute__((address_space(3))) v4s lds_v4s;
-                        v2i r;
-                        if (ES == 1) {
-                            r = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(src + h * RPR * BN * ES));
-                        } else {
-                            v4s q = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s *)(src + h * RPR * BN * ES));
-                            r = __builtin_bit_cast(v2i, q);
-                        }
-                        w[4 * f + 2 * h] = (unsigned)r[0];
-                        w[4 * f + 2 * h + 1] = (unsigned)r[1];
-                    }
+                    static_assert(EPC / RPR == 2, "two transposing reads per 16-byte fragment chunk");
+                    const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) const uint8_t *)src;
+                    const v2i r0 = lds_tr<ES, 0>(lds_addr), r1 = lds_tr<ES, RPR * BN * ES>(lds_addr);
+                    w[4 * f + 0] = (unsigned)r0[0];
+                    w[4 * f + 1] = (unsigned)r0[1];
+                    w[4 * f + 2] = (unsigned)r1[0];
+                    w[4 * f + 3] = (unsigned)r1[1];
                 }
-                if (BSRC == BSRC_NCHWS) {
+                {
                     // shifted read: channel row c of the step holds pixels col0 + delta .. of its channel,
-                    // delta = the tap's offset in the flattened image.  The tensor's start can only be
-                    // straddled in the first image, where columns are pixel indices; its end in the last
-                    const int dr = rt_r - g.ph, dc = rt_s - g.pw;
+                    // delta = the tap's offset in the flattened image (0 in the 1x1 mode).  The tensor's start can
+                    // only be straddled in the first image, where columns are pixel indices; its end in the last
+                    constexpr bool TAPS = (BSRC == BSRC_NCHWS);
+                    const int dr = TAPS ? rt_r - g.ph : 0, dc = TAPS ? rt_s - g.pw : 0;
                     const int wstart = col0 + dr * g.W + dc;            // pixel index of tile column 0 (first image)
                     const int m = wn * C::WTN + j * MF + lrow;          // this lane's tile column
                     const int pix = wstart + m, cstart = wstart + (m & ~(EPC - 1));
                     const uint8_t *edge = smem + NST * C::STAGE_BYTES;
-                    constexpr unsigned EMASK = (ES == 1) ? 0xffu : 0xffffu;
                     // The chunk that straddles the start of the tensor was not loaded: its pixels of the
                     // first channel come from the tensor's first 16 bytes (kept at edge[0..15]) ...
-                    if (sub == 0 && wk == 0 && rt_cb == 0 && wstart < 0) {
+                    b_fs[slot][j] = b_fe[slot][j] = false;
+                    b_vs[slot][j] = b_ve[slot][j] = 0;
+                    // (both cases are rare and wave-uniform: a scalar branch keeps them out of the other steps)
+                    if (TAPS && sub == 0 && wk == 0 && rt_cb == 0 && wstart < 0) {
                         const bool fix = lchunk == 0 && cstart < 0 && pix >= 0;
                         const uint8_t *src = edge + (fix ? pix * ES : 0);
-                        const unsigned v = (ES == 1) ? *src : *reinterpret_cast<const uint16_t *>(src);
-                        if (fix) w[0] = (w[0] & ~EMASK) | v;
+                        b_vs[slot][j] = (ES == 1) ? *src : *reinterpret_cast<const uint16_t *>(src);
+                        b_fs[slot][j] = fix;
                     }
                     // ... and likewise the chunk that straddles its end, for the last channel (edge[16..31])
                     const int last0 = g.cols - g.PQ;                    // first column of the last image
-                    if (sub == NS - 1 && wk == WGK - 1 && rt_cb + NCH >= g.CB && wstart - last0 + BN > g.PQ) {
+                    const bool last_step = TAPS ? rt_cb + NCH >= g.CB : (g.edge && rt_cb + NCH >= g.kchunks);
+                    if (sub == NS - 1 && wk == WGK - 1 && last_step && wstart - last0 + BN > g.PQ) {
                         const int pixl = pix - last0, cstartl = cstart - last0;
                         const bool fix = lchunk == C::CPL - FW && cstartl + EPC > g.PQ && pixl < g.PQ;
                         const uint8_t *src = edge + 16 + (fix ? (pixl - (g.PQ - EPC)) * ES : 0);
-                        const unsigned v = (ES == 1) ? *src : *reinterpret_cast<const uint16_t *>(src);
-                        constexpr int SH = 32 - 8 * ES;
-                        if (fix) w[4 * FW - 1] = (w[4 * FW - 1] & ~(EMASK << SH)) | (v << SH);
+                        b_ve[slot][j] = (ES == 1) ? *src : *reinterpret_cast<const uint16_t *>(src);
+                        b_fe[slot][j] = fix;
                     }
                     // taps that fall into the padding (or columns past the image) contribute zero
-                    const bool inside = (unsigned)(sp[j] + dr) < (unsigned)g.H && (unsigned)(sq[j] + dc) < (unsigned)g.W;
-#pragma unroll
-                    for (int t = 0; t < 4 * FW; ++t) w[t] = inside ? w[t] : 0u;
+                    if (TAPS)
+                        b_in[slot][j] = (unsigned)(sp[j] + dr) < (unsigned)g.H && (unsigned)(sq[j] + dc) < (unsigned)g.W;
                 }
                 fb[slot][j] = Frag<FW>::pack(w);
             }
@@ -725,7 +778,7 @@ igemm_kernel(const IgemmArgs g)
 
     if (ks_begin < ks_end) {
         constexpr int AHEAD = WHOLE ? NST - 1 : NST;            // tiles in flight after the prologue
-        if (BSRC == BSRC_NCHWS && wave == 0)                    // first and last 16 bytes of the tensor (see read_frags)
+        if ((BSRC == BSRC_NCHWS || (BSRC == BSRC_NCHW && g.edge)) && wave == 0)   // first and last 16 bytes of the tensor (see read_frags)
             dma16(rsB, smem + NST * C::STAGE_BYTES,
                   lane == 0 ? 0u : lane == 1 ? (unsigned)(g.b_bytes - 16) : UNIT_OOB);
 #pragma unroll
@@ -742,8 +795,11 @@ igemm_kernel(const IgemmArgs g)
                 const int prev_stage = (stage == 0) ? NST - 1 : stage - 1;
                 UNIT_WAIT_VM((NST >= 3 ? NST - 3 : 0) * C::LPT);   // own part of the next tile has landed
                 UNIT_BARRIER();
+#pragma unroll
+                for (int s2 = 0; s2 < NS; ++s2) finish_frags(SET * NS + s2);   // (read one step ago)
                 __builtin_amdgcn_sched_barrier(0);
                 if (BSRC == BSRC_NCHWS) next_tap(rt_r, rt_s, rt_cb);
+                if (BSRC == BSRC_NCHW) rt_cb += NCH;
 #pragma unroll
                 for (int s2 = 0; s2 < NS; ++s2) read_frags(next_stage, s2, (SET ^ 1) * NS + s2);
                 issue_tile(prev_stage);                          // tile ks+NST-1 into the stage read one step ago
@@ -787,6 +843,7 @@ igemm_kernel(const IgemmArgs g)
                     UNIT_WAIT_VM_LGKM0((NST - 2) * C::LPT);     // next tile landed, my reads of this one done
                     UNIT_BARRIER();
                 }
+                finish_frags(slot);
                 __builtin_amdgcn_sched_barrier(0);
                 // One scheduling region: the MFMAs of this sub-step plus the memory
                 // instructions that must be in flight before the next one -- the fragment
@@ -797,6 +854,7 @@ igemm_kernel(const IgemmArgs g)
                     read_frags(stage, s2 + 1, slot ^ 1);
                 } else {
                     if (BSRC == BSRC_NCHWS) next_tap(rt_r, rt_s, rt_cb);
+                    if (BSRC == BSRC_NCHW) rt_cb += NCH;
                     read_frags(next_stage, 0, slot ^ 1);
                     issue_tile(stage);                           // tile ks+NST into the stage just freed
                 }
@@ -828,6 +886,13 @@ igemm_kernel(const IgemmArgs g)
                 for (int i = 0; i < TM; ++i) fa[0][i] = fa[1][i];
 #pragma unroll
                 for (int j = 0; j < TN; ++j) fb[0][j] = fb[1][j];
+                if (BSRC == BSRC_NCHWS || BSRC == BSRC_NCHW) {
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) {
+                        b_in[0][j] = b_in[1][j];  b_fs[0][j] = b_fs[1][j];  b_fe[0][j] = b_fe[1][j];
+                        b_vs[0][j] = b_vs[1][j];  b_ve[0][j] = b_ve[1][j];
+                    }
+                }
             }
             stage = next_stage;
         }

@@ -174,23 +174,25 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
 // saves the separate pack_act launch.  The 16-byte global -> LDS loads take any byte offset, so
 // the channel rows need no alignment; with several images whose pixel count is not a whole number
 // of 16-byte chunks the columns are tiled per image (conv_packed sets per_img).
-// Rows that do not start on 4-byte boundaries make some of the 16-byte loads start inside a dword;
-// the range check drops every dword that is not wholly inside the buffer, so the last bytes of the
-// tensor would be lost.  The range is then extended by 3 bytes (slack), which makes the hardware read
-// up to 3 bytes past the tensor (into columns that are never stored).  Memory protection works on
-// pages of at least 4 KiB, so this is done only when those bytes lie on the tensor's last page.
-long nchw_range_slack(const ConvND *d, int dtype, const void *x)
+// The range check of those loads works per dword (a dword that is not wholly inside the buffer reads as
+// zero), so with rows that do not start on 4-byte boundaries the chunk that crosses the tensor's end would
+// lose valid bytes.  The kernel then does not load that chunk at all and takes its pixels (last channel only)
+// from a copy of the tensor's last 16 bytes (IgemmArgs::edge); that needs whole steps of channels and an
+// image of at least one chunk.
+bool nchw_rows_unaligned(const ConvND *d, int dtype)
 {
-    const long px = (long)d->d * d->h * d->w, es = elem_size(dtype);
-    if ((px * es) % 4 == 0) return 0;                             // every load starts on a dword: exact range
-    const uintptr_t end = reinterpret_cast<uintptr_t>(x) + (uintptr_t)((long)d->n * d->c * px * es);
-    const unsigned in_page = (unsigned)(end & 4095);
-    return (in_page == 0 || in_page > 4093) ? -1 : 3;             // -1: the slack could cross into another page
+    return ((long)d->d * d->h * d->w * elem_size(dtype)) % 4 != 0;
 }
 
 bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requant *rq)
 {
-    if (nchw_range_slack(d, dtype, x) < 0) return false;
+    if (nchw_rows_unaligned(d, dtype)) {
+        ConvGeom g;
+        if (conv_geom(d, dtype, &g) != UNIT_OK) return false;
+        TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_NCHW);
+        if (((long)d->c * elem_size(dtype)) % g_tiles[ch.tile].bkb != 0) return false;
+        if ((long)d->d * d->h * d->w < chunk_elems(dtype)) return false;
+    }
     return d->t == 1 && d->r == 1 && d->s == 1 &&
            d->stride_d == 1 && d->stride_h == 1 && d->stride_w == 1 &&
            d->pad_d == 0 && d->pad_h == 0 && d->pad_w == 0 && rq == nullptr && dtype != UNIT_U8I8 && (reinterpret_cast<uintptr_t>(x) & 15) == 0;
@@ -253,12 +255,8 @@ int conv_packed(const ConvND *d, int dtype, const void *xp, const void *wp,
     a.D = d->d;  a.H = d->h;  a.W = d->w;  a.CB = g.cp * es / 16;
     a.P = g.p;  a.Q = g.q;  a.PQ = g.o * g.p * g.q;
     a.b_bytes = nchw_direct ? (long)d->n * d->c * d->d * d->h * d->w * es : (long)d->n * d->d * d->h * d->w * g.cp * es;
-    if (bsrc == BSRC_NCHW) {
-        const long slack = nchw_range_slack(d, dtype, xp);
-        if (slack < 0) return UNIT_EINVAL;          // (callers pick this mode through nchw_direct_ok)
-        a.b_bytes += slack;
-    }
     a.Cin = d->c;
+    a.edge = (bsrc == BSRC_NCHW && nchw_rows_unaligned(d, dtype)) ? 1 : 0;
     a.per_img = (nchw_direct && d->n > 1 && ((long)d->d * d->h * d->w) % chunk_elems(dtype) != 0) ? 1 : 0;
     a.T = d->t;  a.R = d->r;  a.S = d->s;
     a.sd = d->stride_d;  a.sh = d->stride_h;  a.sw = d->stride_w;  a.pd = d->pad_d;  a.ph = d->pad_h;  a.pw = d->pad_w;

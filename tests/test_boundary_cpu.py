@@ -124,13 +124,15 @@ def test_input_mode_decisions_are_host_logic(lib):
     assert mode(1, 64, 56, 56, 256, 1, 1, 1, 0) == D              # aligned 1x1
     assert mode(16, 64, 56, 56, 256, 1, 1, 1, 0, dtype=unit.UNIT_F16) == D   # batches: whole chunks per image
     assert mode(16, 256, 14, 14, 1024, 1, 1, 1, 0, dtype=unit.UNIT_F16) == D  # batches: columns tiled per image
-    # 49-byte rows: some loads start inside a dword, so the buffer range gets 3 bytes of slack -- only
-    # where those bytes lie on the tensor's own last page (16*512*49 bytes are 98 whole pages)
-    assert mode(16, 512, 7, 7, 2048, 1, 1, 1, 0) == P             # tensor ends on a page boundary
-    assert mode(2, 512, 7, 7, 2048, 1, 1, 1, 0, ptr=x + 3072) == S           # same for a small batch (ends at x + 53248): the
-                                                                  # shifted read needs no slack and takes it
-    assert mode(16, 512, 7, 7, 2048, 1, 1, 1, 0, ptr=x + 512) == D   # same tensor, 512 bytes further on
-    assert mode(1, 512, 7, 7, 2048, 1, 1, 1, 0) == D              # 49-byte rows: no alignment needed
+    # 49-byte rows: some loads start inside a dword, whose range check would lose the tensor's last bytes; the
+    # kernel patches them from a copy of the last 16 bytes, wherever the tensor lies (whole steps of channels only)
+    assert mode(16, 512, 7, 7, 2048, 1, 1, 1, 0) == D
+    assert mode(16, 512, 7, 7, 2048, 1, 1, 1, 0, ptr=x + 512) == D
+    assert mode(1, 512, 7, 7, 2048, 1, 1, 1, 0) == D
+    assert mode(1, 512, 7, 7, 2048, 1, 1, 1, 0, dtype=unit.UNIT_F16) == D     # 98-byte rows
+    assert mode(1, 520, 7, 7, 2048, 1, 1, 1, 0) == P              # unaligned rows and a partial last step of channels
+    assert mode(1, 520, 6, 6, 2048, 1, 1, 1, 0) == D              # 36-byte rows: dword-aligned, any channel count
+    assert mode(1, 512, 3, 5, 2048, 1, 1, 1, 0) == P              # 15 pixels: less than one chunk of one-byte elements
     assert mode(1, 256, 14, 14, 256, 3, 3, 1, 1) == S             # 3x3, same padding
     assert mode(1, 128, 11, 10, 33, 5, 5, 1, 2) == S
     assert mode(1, 64, 56, 56, 64, 3, 3, 1, 1) == P               # 64 int8 channels: half a step

@@ -28,8 +28,9 @@ CASES = [
     (wl.ConvShape(128, 7, 7, 130, 3, 3, 1, 1), SHIFTED, SHIFTED),      # 49-pixel rows, tiles wider than the image
     (wl.ConvShape(128, 9, 13, 40, 3, 3, 1, 1), SHIFTED, SHIFTED),      # odd sizes: every byte shift occurs
     (wl.ConvShape(128, 11, 10, 33, 5, 5, 1, 2), SHIFTED, SHIFTED),     # wider window
-    (wl.ConvShape(512, 7, 7, 64, 1, 1, 1, 0), DIRECT, DIRECT),         # 1x1 whose rows are not 4-byte aligned: plain direct read
-    (wl.ConvShape(384, 5, 3, 48, 1, 1, 1, 0), DIRECT, DIRECT),         # 15-pixel image
+    (wl.ConvShape(512, 7, 7, 64, 1, 1, 1, 0), DIRECT, DIRECT),         # 1x1 whose rows are not 4-byte aligned: end chunk patched
+    (wl.ConvShape(384, 5, 3, 48, 1, 1, 1, 0), PACKED, DIRECT),         # 15-pixel image: less than a chunk of one-byte elements
+    (wl.ConvShape(256, 6, 6, 48, 1, 1, 1, 0), DIRECT, DIRECT),         # 1x1 with dword-aligned rows: the plain direct read
     (wl.ConvShape(64, 12, 12, 64, 3, 3, 1, 1), PACKED, SHIFTED),       # 64 channels: one fp16 step, half an int8 step
     (wl.ConvShape(128, 56, 56, 32, 3, 3, 1, 1), SHIFTED, SHIFTED),     # many column tiles
     (wl.ConvShape(128, 12, 12, 16, 3, 3, 1, 1), SHIFTED, SHIFTED),     # 16 output channels: the narrow tile

@@ -215,6 +215,12 @@ NCHW_DIRECT = [   # 1x1 / stride 1: read straight from NCHW, whatever the alignm
     (wl.ConvShape(40, 6, 6, 24, 1, 1, 1, 0), 5),       # 36 pixels per image: per-image tiles, mostly empty
     (wl.ConvShape(256, 14, 14, 70, 1, 1, 1, 0), 3),    # several reduction steps, per-image tiles
     (wl.ConvShape(32, 5, 10, 16, 1, 1, 1, 0), 4),      # 50 pixels per image
+    # rows that are not dword-aligned with whole steps of channels: read directly, the chunk that crosses the
+    # tensor's end is patched (one-byte types need 128 channels per step, two-byte types 64; the 256-byte-step
+    # tile twice as many)
+    (wl.ConvShape(128, 7, 7, 40, 1, 1, 1, 0), 1), (wl.ConvShape(256, 5, 5, 33, 1, 1, 1, 0), 3),
+    (wl.ConvShape(128, 3, 11, 24, 1, 1, 1, 0), 2), (wl.ConvShape(64, 7, 7, 40, 1, 1, 1, 0), 1),
+    (wl.ConvShape(512, 9, 9, 72, 1, 1, 1, 0), 2), (wl.ConvShape(256, 7, 7, 16, 1, 1, 1, 0), 1),
 ]
 
 
