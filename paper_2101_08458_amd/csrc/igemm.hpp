@@ -789,10 +789,15 @@ igemm_kernel(const IgemmArgs g)
         if (WHOLE) {
 #pragma unroll
             for (int s2 = 0; s2 < NS; ++s2) read_frags(0, s2, s2);
-            auto whole_step = [&](auto set_c) {
+            // The step loop is unrolled over the fragment sets and the stage ring (four steps), so that set and
+            // stages are constants: LDS addresses fold into the instructions' offsets and the ring arithmetic
+            // disappears.  These loops run one wave per SIMD and are bound by instruction issue.
+            static_assert(!WHOLE || NST == 4, "the unrolled step loop walks a ring of four stages");
+            auto whole_step = [&](auto set_c, auto stage_c) {
                 constexpr int SET = decltype(set_c)::value;
-                const int next_stage = (stage + 1 == NST) ? 0 : stage + 1;
-                const int prev_stage = (stage == 0) ? NST - 1 : stage - 1;
+                constexpr int STG = decltype(stage_c)::value;
+                constexpr int next_stage = (STG + 1) % NST;
+                constexpr int prev_stage = (STG + NST - 1) % NST;
                 UNIT_WAIT_VM((NST >= 3 ? NST - 3 : 0) * C::LPT);   // own part of the next tile has landed
                 UNIT_BARRIER();
 #pragma unroll
@@ -823,12 +828,15 @@ igemm_kernel(const IgemmArgs g)
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                stage = next_stage;
             };
             for (int ks = ks_begin;;) {
-                whole_step(IntC<0>{});
+                whole_step(IntC<0>{}, IntC<0>{});
                 if (++ks >= ks_end) break;
-                whole_step(IntC<1>{});
+                whole_step(IntC<1>{}, IntC<1>{});
+                if (++ks >= ks_end) break;
+                whole_step(IntC<0>{}, IntC<2>{});
+                if (++ks >= ks_end) break;
+                whole_step(IntC<1>{}, IntC<3>{});
                 if (++ks >= ks_end) break;
             }
         } else {
