@@ -48,7 +48,9 @@ enum { EPI_RAW = 0, EPI_REQUANT = 1 };
 // offset), so the tile lands in LDS as in the 1x1 mode and is read the same way; pixels whose tap
 // falls into the padding are masked after the read, and the two chunks that straddle the tensor's
 // start and end are patched from a copy of its first and last 16 bytes.
-enum { BSRC_PLAIN = 0, BSRC_GATHER = 1, BSRC_NCHW = 2, BSRC_NCHWS = 3 };
+// BSRC_GATHERU is the gather for layers whose pixels hold a whole number of steps of channel chunks: every lane
+// of a step then works on the same tap and the tap walk is scalar (the launcher picks it; callers say BSRC_GATHER).
+enum { BSRC_PLAIN = 0, BSRC_GATHER = 1, BSRC_NCHW = 2, BSRC_NCHWS = 3, BSRC_GATHERU = 4 };
 
 struct IgemmArgs {
     // operands (byte pointers; every row starts 16-byte aligned, reduction zero padded to 16 B)
@@ -302,7 +304,11 @@ igemm_kernel(const IgemmArgs g)
 
     const int tid  = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps LDS addresses scalar
+    int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: keeps LDS addresses scalar
+    // (opaque from here on: otherwise the compiler re-derives it, and everything computed from it, from the
+    // thread id inside the step loop for the code after the loop -- half a dozen instructions per step)
+    asm volatile("" : "+s"(wave_s));
+    const int wave = wave_s;
     const int wk   = wave / (WGM * WGN);
     const int wm   = (wave % (WGM * WGN)) / WGN;
     const int wn   = wave % WGN;
@@ -397,7 +403,7 @@ igemm_kernel(const IgemmArgs g)
             offB[j] = (unsigned)(((img * g.Cin + crow) * g.PQ + (px - img * g.PQ)) * ES);
             bh0[j] = crow;                          // channel row of this lane inside a step
             bd0[j] = bw0[j] = 0;
-        } else if (BSRC == BSRC_GATHER) {
+        } else if (BSRC == BSRC_GATHER || BSRC == BSRC_GATHERU) {
             int cc = valid ? col0 + r : 0;
             // (integer divisions are ~40 instructions each: skip the ones whose result is known)
             int n = 0, opq = cc;
@@ -420,8 +426,8 @@ igemm_kernel(const IgemmArgs g)
     // conv: reduction chunk kc -> (r, s, channel chunk cb), advanced incrementally per step
     int kc = ks_begin * NCH + cT;
     int ct = 0, cr = 0, cs = 0, ccb = 0;
-    const bool uni_tap = (BSRC == BSRC_GATHER) && (g.CB % NCH == 0);
-    if (BSRC == BSRC_GATHER && !uni_tap) {
+    constexpr bool uni_tap = (BSRC == BSRC_GATHERU);
+    if (BSRC == BSRC_GATHER) {
         int trs = kc / g.CB;
         ccb = kc - trs * g.CB;
         ct = trs / (g.R * g.S);
@@ -512,7 +518,7 @@ igemm_kernel(const IgemmArgs g)
                 const bool ok = chan0 + bh0[j] < chan_end && off + 16u <= lim;
                 dma16(rsB, dst + j * NW * 1024, ok ? off : UNIT_OOB);
             }
-        } else if (BSRC == BSRC_GATHER && uni_tap) {
+        } else if (BSRC == BSRC_GATHERU) {
             const bool step_ok = (kc - cT) < kend;
 #pragma unroll
             for (int j = 0; j < IB; ++j) {
@@ -829,16 +835,18 @@ igemm_kernel(const IgemmArgs g)
                 }
                 __builtin_amdgcn_sched_barrier(0);
             };
-            for (int ks = ks_begin;;) {
+            // (whole rounds of the ring in a loop with a single exit, then the remaining steps: a loop with an
+            // exit after every step makes the compiler carry an exit flag and placeholder copies through each step)
+            int steps_left = ks_end - ks_begin;
+            for (; steps_left >= 4; steps_left -= 4) {
                 whole_step(IntC<0>{}, IntC<0>{});
-                if (++ks >= ks_end) break;
                 whole_step(IntC<1>{}, IntC<1>{});
-                if (++ks >= ks_end) break;
                 whole_step(IntC<0>{}, IntC<2>{});
-                if (++ks >= ks_end) break;
                 whole_step(IntC<1>{}, IntC<3>{});
-                if (++ks >= ks_end) break;
             }
+            if (steps_left >= 1) whole_step(IntC<0>{}, IntC<0>{});
+            if (steps_left >= 2) whole_step(IntC<1>{}, IntC<1>{});
+            if (steps_left >= 3) whole_step(IntC<0>{}, IntC<2>{});
         } else {
         read_frags(0, 0, 0);
         for (int ks = ks_begin; ks < ks_end; ++ks) {
