@@ -50,7 +50,8 @@ enum { EPI_RAW = 0, EPI_REQUANT = 1 };
 // start and end are patched from a copy of its first and last 16 bytes.
 // BSRC_GATHERU is the gather for layers whose pixels hold a whole number of steps of channel chunks: every lane
 // of a step then works on the same tap and the tap walk is scalar (the launcher picks it; callers say BSRC_GATHER).
-enum { BSRC_PLAIN = 0, BSRC_GATHER = 1, BSRC_NCHW = 2, BSRC_NCHWS = 3, BSRC_GATHERU = 4 };
+// BSRC_NCHWE is the 1x1 direct read for rows that are not dword-aligned (IgemmArgs::edge; picked by the launcher).
+enum { BSRC_PLAIN = 0, BSRC_GATHER = 1, BSRC_NCHW = 2, BSRC_NCHWS = 3, BSRC_GATHERU = 4, BSRC_NCHWE = 5 };
 
 struct IgemmArgs {
     // operands (byte pointers; every row starts 16-byte aligned, reduction zero padded to 16 B)
@@ -260,7 +261,7 @@ struct IgemmCfg {
         IB    = BN / RPI / NW,
         LPT   = IA + IB,
         STAGE_BYTES  = (BM + BN) * BKB,
-        EDGE_BYTES   = (BSRC == BSRC_NCHWS || BSRC == BSRC_NCHW) ? 1024 : 0,   // direct reads: first and last 16 bytes of the tensor
+        EDGE_BYTES   = (BSRC == BSRC_NCHWS || BSRC == BSRC_NCHWE) ? 1024 : 0,   // direct reads: first and last 16 bytes of the tensor
         RING_BYTES   = NST * STAGE_BYTES + EDGE_BYTES,
         REDUCE_BYTES = (WGK > 1) ? WGK * BM * BN * 4 : 0,
         SMEM_BYTES   = (RING_BYTES > REDUCE_BYTES) ? RING_BYTES : REDUCE_BYTES,
@@ -318,7 +319,9 @@ igemm_kernel(const IgemmArgs g)
     // order in bands of 8 row-tiles so the tiles resident together share A and B rows.
     const int tiles_m = (g.rows + BM - 1) / BM;
     const int tiles_img = (g.PQ + BN - 1) / BN;     // per-image tiling only
-    const bool per_img = (BSRC == BSRC_NCHW || BSRC == BSRC_NCHWS) && g.per_img;
+    constexpr bool NCHW1 = (BSRC == BSRC_NCHW || BSRC == BSRC_NCHWE);     // 1x1 direct read, without / with edge patch
+    constexpr bool EDGE1 = (BSRC == BSRC_NCHWE);
+    const bool per_img = (NCHW1 || BSRC == BSRC_NCHWS) && g.per_img;
     const int tiles_n = per_img ? tiles_img * div_any(g.cols, g.PQ) : (g.cols + BN - 1) / BN;
     const int ntiles  = tiles_m * tiles_n;
     int bid = blockIdx.x;
@@ -392,7 +395,7 @@ igemm_kernel(const IgemmArgs g)
             bd0[j] = ((img * g.Cin + crow) * g.PQ + (px - img * g.PQ)) * ES;
             bw0[j] = 0;
             offB[j] = 0;
-        } else if (BSRC == BSRC_NCHW) {
+        } else if (NCHW1) {
             // lane -> (channel row inside the DMA block, 16-byte chunk of pixels)
             const int crow = (j * NW + wave) * CRPI + lane / CPR;
             // this lane's 16-byte chunk of pixels lies inside one image (the host only picks this
@@ -472,7 +475,7 @@ igemm_kernel(const IgemmArgs g)
     it_r = rt_r = __builtin_amdgcn_readfirstlane(it_r);
     it_s = rt_s = __builtin_amdgcn_readfirstlane(it_s);
     it_cb = rt_cb = __builtin_amdgcn_readfirstlane(it_cb);
-    if (BSRC == BSRC_NCHW) rt_cb = ks_begin * NCH;  // 1x1 mode: first reduction chunk of the step being read
+    if (EDGE1) rt_cb = ks_begin * NCH;  // 1x1 mode: first reduction chunk of the step being read
     auto next_tap = [&](int &tr, int &ts, int &tcb) {
         tcb += NCH;
         if (tcb >= g.CB) {
@@ -505,13 +508,13 @@ igemm_kernel(const IgemmArgs g)
                 dma16(rsB, dst + j * NW * 1024, ok ? (unsigned)off : UNIT_OOB);
             }
             next_tap(it_r, it_s, it_cb);
-        } else if (BSRC == BSRC_NCHW) {
+        } else if (NCHW1) {
             // channel rows of this step: chan0 .. chan0 + BKB/ES; rows past the real channel
             // count or past the slice end come back as zeros
             const int chan0 = (kc - cT) * EPC;
             const int chan_end = (kend * EPC < g.Cin) ? kend * EPC : g.Cin;
-            // (g.edge: a chunk that is not wholly inside the tensor is not loaded: see read_frags)
-            const unsigned lim = g.edge ? (unsigned)g.b_bytes : 0xffffffffu;
+            // (edge variant: a chunk that is not wholly inside the tensor is not loaded: see read_frags)
+            const unsigned lim = EDGE1 ? (unsigned)g.b_bytes : 0xffffffffu;
 #pragma unroll
             for (int j = 0; j < IB; ++j) {
                 const unsigned off = offB[j] + (unsigned)(chan0 * g.PQ * ES);
@@ -672,12 +675,12 @@ igemm_kernel(const IgemmArgs g)
     bool b_in[NSLOT][TN], b_fs[NSLOT][TN], b_fe[NSLOT][TN];
     unsigned b_vs[NSLOT][TN], b_ve[NSLOT][TN];
     auto finish_frags = [&](int slot) {
-        if (BSRC != BSRC_NCHW && BSRC != BSRC_NCHWS) return;
+        if (!NCHW1 && BSRC != BSRC_NCHWS) return;
         UNIT_WAIT_LGKM0();                                      // (the transposing reads: see lds_tr)
 #pragma unroll
         for (int j = 0; j < TN; ++j) lds_tr_done(fb[slot][j]);
         constexpr bool TAPS = (BSRC == BSRC_NCHWS);
-        if (!TAPS && !g.edge) return;
+        if (!TAPS && !EDGE1) return;
         constexpr unsigned EMASK = (ES == 1) ? 0xffu : 0xffffu;
         constexpr int SH = 32 - 8 * ES;
 #pragma unroll
@@ -705,7 +708,7 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
             for (int i = 0; i < TM; ++i) fa[slot][i] ^= (int)0x80808080;
         }
-        if (BSRC == BSRC_NCHW || BSRC == BSRC_NCHWS) {
+        if (NCHW1 || BSRC == BSRC_NCHWS) {
             // B tile is [channel][pixel], i.e. reduction-major: the transposing LDS reads of gfx950
             // hand every lane the 8 bytes of consecutive channels of its pixel column.  Within a group
             // of 16 lanes, lane t supplies the address of 8 contiguous bytes and lane n receives
@@ -734,7 +737,7 @@ igemm_kernel(const IgemmArgs g)
                     w[4 * f + 2] = (unsigned)r1[0];
                     w[4 * f + 3] = (unsigned)r1[1];
                 }
-                {
+                if (BSRC == BSRC_NCHWS || EDGE1) {
                     // shifted read: channel row c of the step holds pixels col0 + delta .. of its channel,
                     // delta = the tap's offset in the flattened image (0 in the 1x1 mode).  The tensor's start can
                     // only be straddled in the first image, where columns are pixel indices; its end in the last
@@ -757,7 +760,7 @@ igemm_kernel(const IgemmArgs g)
                     }
                     // ... and likewise the chunk that straddles its end, for the last channel (edge[16..31])
                     const int last0 = g.cols - g.PQ;                    // first column of the last image
-                    const bool last_step = TAPS ? rt_cb + NCH >= g.CB : (g.edge && rt_cb + NCH >= g.kchunks);
+                    const bool last_step = TAPS ? rt_cb + NCH >= g.CB : rt_cb + NCH >= g.kchunks;
                     if (sub == NS - 1 && wk == WGK - 1 && last_step && wstart - last0 + BN > g.PQ) {
                         const int pixl = pix - last0, cstartl = cstart - last0;
                         const bool fix = lchunk == C::CPL - FW && cstartl + EPC > g.PQ && pixl < g.PQ;
@@ -784,7 +787,7 @@ igemm_kernel(const IgemmArgs g)
 
     if (ks_begin < ks_end) {
         constexpr int AHEAD = WHOLE ? NST - 1 : NST;            // tiles in flight after the prologue
-        if ((BSRC == BSRC_NCHWS || (BSRC == BSRC_NCHW && g.edge)) && wave == 0)   // first and last 16 bytes of the tensor (see read_frags)
+        if ((BSRC == BSRC_NCHWS || EDGE1) && wave == 0)   // first and last 16 bytes of the tensor (see read_frags)
             dma16(rsB, smem + NST * C::STAGE_BYTES,
                   lane == 0 ? 0u : lane == 1 ? (unsigned)(g.b_bytes - 16) : UNIT_OOB);
 #pragma unroll
@@ -810,7 +813,7 @@ igemm_kernel(const IgemmArgs g)
                 for (int s2 = 0; s2 < NS; ++s2) finish_frags(SET * NS + s2);   // (read one step ago)
                 __builtin_amdgcn_sched_barrier(0);
                 if (BSRC == BSRC_NCHWS) next_tap(rt_r, rt_s, rt_cb);
-                if (BSRC == BSRC_NCHW) rt_cb += NCH;
+                if (EDGE1) rt_cb += NCH;
 #pragma unroll
                 for (int s2 = 0; s2 < NS; ++s2) read_frags(next_stage, s2, (SET ^ 1) * NS + s2);
                 issue_tile(prev_stage);                          // tile ks+NST-1 into the stage read one step ago
@@ -870,7 +873,7 @@ igemm_kernel(const IgemmArgs g)
                     read_frags(stage, s2 + 1, slot ^ 1);
                 } else {
                     if (BSRC == BSRC_NCHWS) next_tap(rt_r, rt_s, rt_cb);
-                    if (BSRC == BSRC_NCHW) rt_cb += NCH;
+                    if (EDGE1) rt_cb += NCH;
                     read_frags(next_stage, 0, slot ^ 1);
                     issue_tile(stage);                           // tile ks+NST into the stage just freed
                 }
@@ -902,7 +905,7 @@ igemm_kernel(const IgemmArgs g)
                 for (int i = 0; i < TM; ++i) fa[0][i] = fa[1][i];
 #pragma unroll
                 for (int j = 0; j < TN; ++j) fb[0][j] = fb[1][j];
-                if (BSRC == BSRC_NCHWS || BSRC == BSRC_NCHW) {
+                if (BSRC == BSRC_NCHWS || EDGE1) {
 #pragma unroll
                     for (int j = 0; j < TN; ++j) {
                         b_in[0][j] = b_in[1][j];  b_fs[0][j] = b_fs[1][j];  b_fe[0][j] = b_fe[1][j];
