@@ -52,10 +52,15 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
         if (tile < 0 && rows <= 64 && (long)cdiv(cols, 256) >= CUS * 3 / 4)
             tile = (kchunks >= 32) ? 6 : 1;
         // small problems are launch- and latency-bound: measured over the ResNet-50 batch-1
-        // layers, 64x64 (2x2x2 waves) wins once it yields ~100 workgroups, 32x32 below that
+        // layers, 64x64 (2x2x2 waves) wins once it yields ~160 workgroups, 32x32 below that (at ~100 the
+        // 32x32 tile's ~400 workgroups fill the chip and finish 0.2-0.4 us earlier, unless the reduction is
+        // deep: there the 64x64 tile's fewer bytes per MAC count for more)
         // (a 64x64 tile with 256-byte steps in two stages is 4-18 % faster on deep reductions when a layer
         // is timed alone, but slower inside a sequence of layers, where every launch starts on cold caches)
-        if (tile < 0) tile = ((long)cdiv(rows, 64) * cdiv(cols, 64) >= 96) ? 3 : 4;
+        if (tile < 0) {
+            const long n64 = (long)cdiv(rows, 64) * cdiv(cols, 64);
+            tile = (n64 >= 160 || (n64 >= 96 && kchunks > 32)) ? 3 : 4;
+        }
     }
     int forced = env_int("UNIT_TILE", -1);
     if (forced >= 0 && forced < NUM_TILES) tile = forced;
