@@ -53,6 +53,10 @@ enum { EPI_RAW = 0, EPI_REQUANT = 1 };
 // BSRC_NCHWE is the 1x1 direct read for rows that are not dword-aligned (IgemmArgs::edge; picked by the launcher).
 enum { BSRC_PLAIN = 0, BSRC_GATHER = 1, BSRC_NCHW = 2, BSRC_NCHWS = 3, BSRC_GATHERU = 4, BSRC_NCHWE = 5 };
 
+// Divisor with its reciprocal for the kernels' integer divisions: m = floor(2^32 / d) (0xffffffff for d = 1).
+// The host fills these in; a division is then a multiply-high and one correction (see divu).
+struct DivU { unsigned d, m; };
+
 struct IgemmArgs {
     // operands (byte pointers; every row starts 16-byte aligned, reduction zero padded to 16 B)
     const uint8_t *A;  long lda;  int rows;        // lda in bytes
@@ -81,6 +85,11 @@ struct IgemmArgs {
     int8_t *out_i8;                                 // same indexing as out, or NULL
     int8_t *out_packed;  int packed_ld;             // [col][packed_ld] int8, or NULL
     int store_raw;                                  // also store raw accumulators to out
+    // divisors of the index arithmetic (unused ones hold d = 1)
+    DivU dv_pq, dv_ppq, dv_q, dv_w;                 // PQ (output pixels per image), P*Q, Q, W
+    DivU dv_cpi;                                    // cols_per_img
+    DivU dv_tiles_n, dv_band, dv_tiles_img;         // column tiles, 8 * column tiles, column tiles per image (per_img)
+    int nimg;                                       // cols / PQ (images)
 };
 
 // One element of the requantise rule.  v_cvt_f32_i32 and v_rndne_f32 both round to
@@ -154,6 +163,13 @@ __device__ __forceinline__ int div_small(int a, int b)
     return q;
 }
 __device__ __forceinline__ int div_any(int a, int b) { return (a < (1 << 22)) ? div_small(a, b) : a / b; }
+// n / x.d for any 0 <= n < 2^31: the truncated reciprocal makes the multiply-high at most one too small
+__device__ __forceinline__ int divu(int n, DivU x)
+{
+    const unsigned q = __umulhi((unsigned)n, x.m);
+    const unsigned r = (unsigned)n - q * x.d;
+    return (int)(q + (r >= x.d ? 1u : 0u));
+}
 
 template <int V> struct IntC { static constexpr int value = V; };
 
@@ -322,7 +338,7 @@ igemm_kernel(const IgemmArgs g)
     constexpr bool NCHW1 = (BSRC == BSRC_NCHW || BSRC == BSRC_NCHWE);     // 1x1 direct read, without / with edge patch
     constexpr bool EDGE1 = (BSRC == BSRC_NCHWE);
     const bool per_img = (NCHW1 || BSRC == BSRC_NCHWS) && g.per_img;
-    const int tiles_n = per_img ? tiles_img * div_any(g.cols, g.PQ) : (g.cols + BN - 1) / BN;
+    const int tiles_n = per_img ? tiles_img * g.nimg : (g.cols + BN - 1) / BN;
     const int ntiles  = tiles_m * tiles_n;
     int bid = blockIdx.x;
     {   // XCD x = bid % 8 receives workgroups x, x + 8, ...: they become one contiguous run of the tile order
@@ -333,11 +349,11 @@ igemm_kernel(const IgemmArgs g)
     if (g.row_runs) {
         // far more A (weight) bytes than B bytes: a run walks the column tiles of one row tile, so each
         // XCD fetches its own rows of A once and only the small B is fetched by every XCD
-        tm = div_any(bid, tiles_n);
+        tm = divu(bid, g.dv_tiles_n);
         tn = bid - tm * tiles_n;
     } else {
         constexpr int BAND = 8;
-        const int band      = div_any(bid, BAND * tiles_n);
+        const int band      = divu(bid, g.dv_band);
         const int band_m0   = band * BAND;
         const int band_rows = (tiles_m - band_m0 < BAND) ? tiles_m - band_m0 : BAND;
         const int in_band   = bid - band * BAND * tiles_n;
@@ -347,7 +363,7 @@ igemm_kernel(const IgemmArgs g)
     const int row0 = tm * BM;
     int col0 = tn * BN, col_end = g.cols;           // first column of the tile, end of its column range
     if (per_img) {
-        const int img = div_any(tn, tiles_img);
+        const int img = divu(tn, g.dv_tiles_img);
         col0 = img * g.PQ + (tn - img * tiles_img) * BN;
         col_end = (img + 1) * g.PQ;
     }
@@ -390,7 +406,7 @@ igemm_kernel(const IgemmArgs g)
             // (a chunk of pixels lies inside one image, as in the 1x1 mode)
             const int crow = (j * NW + wave) * CRPI + lane / CPR;
             const int px = col0 + ((lane % CPR) ^ nchw_swz(crow)) * EPC;
-            const int img = (g.cols > g.PQ) ? div_any(px, g.PQ) : 0;
+            const int img = (g.cols > g.PQ) ? divu(px, g.dv_pq) : 0;
             bh0[j] = crow;
             bd0[j] = ((img * g.Cin + crow) * g.PQ + (px - img * g.PQ)) * ES;
             bw0[j] = 0;
@@ -402,7 +418,7 @@ igemm_kernel(const IgemmArgs g)
             // mode when the pixels per image are a multiple of the chunk); columns past the end
             // read whatever follows and are masked at the store
             const int px = col0 + ((lane % CPR) ^ nchw_swz(crow)) * EPC;
-            const int img = (g.cols > g.PQ) ? div_any(px, g.PQ) : 0;
+            const int img = (g.cols > g.PQ) ? divu(px, g.dv_pq) : 0;
             offB[j] = (unsigned)(((img * g.Cin + crow) * g.PQ + (px - img * g.PQ)) * ES);
             bh0[j] = crow;                          // channel row of this lane inside a step
             bd0[j] = bw0[j] = 0;
@@ -410,10 +426,10 @@ igemm_kernel(const IgemmArgs g)
             int cc = valid ? col0 + r : 0;
             // (integer divisions are ~40 instructions each: skip the ones whose result is known)
             int n = 0, opq = cc;
-            if (g.cols > g.PQ) { n = div_any(cc, g.PQ); opq = cc - n * g.PQ; }   // more than one image
+            if (g.cols > g.PQ) { n = divu(cc, g.dv_pq); opq = cc - n * g.PQ; }   // more than one image
             int o = 0, pq = opq;
-            if (g.PQ > g.P * g.Q) { o = div_any(opq, g.P * g.Q); pq = opq - o * (g.P * g.Q); }   // output depth > 1
-            int p = div_any(pq, g.Q), q = pq - p * g.Q;
+            if (g.PQ > g.P * g.Q) { o = divu(opq, g.dv_ppq); pq = opq - o * (g.P * g.Q); }   // output depth > 1
+            int p = divu(pq, g.dv_q), q = pq - p * g.Q;
             // an invalid column gets a row far outside the image: its bounds test always fails
             const int bd = o * g.sd - g.pd, bh = p * g.sh - g.ph, bw = q * g.sw - g.pw;
             bd0[j] = bd;
@@ -585,8 +601,8 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = col0 + b_row + j * MF;
-            const int pin = (g.cols > g.PQ) ? col - div_any(col, g.PQ) * g.PQ : col;    // pixel inside its image
-            const int p = div_any(pin, g.W);
+            const int pin = (g.cols > g.PQ) ? col - divu(col, g.dv_pq) * g.PQ : col;    // pixel inside its image
+            const int p = divu(pin, g.dv_w);
             sp[j] = (col < col_end) ? p : -0x100000;
             sq[j] = pin - p * g.W;
         }
@@ -609,7 +625,7 @@ igemm_kernel(const IgemmArgs g)
         grow = row0 + wm * C::WTM + i * MF + acc_row<MF>(4 * a4, lane);
         gcol = col0 + wn * C::WTN + j * MF + lrow;
         if (CONV) {
-            const int n = (g.cols > g.cols_per_img) ? div_any(gcol, g.cols_per_img) : 0;
+            const int n = (g.cols > g.cols_per_img) ? divu(gcol, g.dv_cpi) : 0;
             gcb = (long)n * g.img_stride + (gcol - n * g.cols_per_img);
         } else {
             gcb = gcol;

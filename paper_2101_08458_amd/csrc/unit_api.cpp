@@ -128,6 +128,15 @@ void fill_tile_info(const TileChoice &ch, int dtype, unit_tile_info *out)
     out->mfma = c.mf;     out->split_k = ch.split_k;  out->workgroups = ch.workgroups;
 }
 
+// divisor + truncated reciprocal for the kernels' divisions (IgemmArgs::dv_*)
+static DivU make_div(long d)
+{
+    DivU x;
+    x.d = d > 1 ? (unsigned)d : 1u;
+    x.m = d > 1 ? (unsigned)((1ULL << 32) / (unsigned long long)d) : 0xffffffffu;
+    return x;
+}
+
 // Runs the main kernel (+ the split reduce when the selector splits across workgroups).
 int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
               void *ws, size_t ws_bytes, hipStream_t st, bool allow_split = true)
@@ -139,6 +148,21 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
     // copy in L2) a run walks the column tiles of one row tile, so A (the weights) is fetched once in total; large
     // problems walk bands of 8 row tiles, which bounds the re-fetching of both operands.
     a.row_runs = ((long)a.cols * a.kchunks * 16 <= (8L << 20)) ? 1 : 0;
+    {   // divisors of the index arithmetic (the tile coordinates depend on the tile chosen here)
+        const TileCfg &t = g_tiles[ch.tile];
+        const long pq = a.PQ > 0 ? a.PQ : 1;
+        const long tiles_img = (pq + t.bn - 1) / t.bn;
+        a.nimg = (int)(a.cols / pq);
+        const long tiles_n = (conv && a.per_img) ? tiles_img * a.nimg : ((long)a.cols + t.bn - 1) / t.bn;
+        a.dv_tiles_n = make_div(tiles_n);
+        a.dv_band = make_div(8 * tiles_n);
+        a.dv_tiles_img = make_div(tiles_img);
+        a.dv_pq = make_div(a.PQ);
+        a.dv_ppq = make_div((long)a.P * a.Q);
+        a.dv_q = make_div(a.Q);
+        a.dv_w = make_div(a.W);
+        a.dv_cpi = make_div(a.cols_per_img);
+    }
     if (ch.split_k == 1) {
         a.split_stride = 0;
         UNIT_HIP(launch_igemm(dtype, bsrc, ch.tile, a, 1, st));
