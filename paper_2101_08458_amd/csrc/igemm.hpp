@@ -686,15 +686,35 @@ igemm_kernel(const IgemmArgs g)
     constexpr bool WHOLE = (TM * TN <= 4) && NST >= 3;      // (the register-prefetch schedule needs three LDS stages)
     constexpr int NSLOT = WHOLE ? 2 * NS : 2;
     frag_t fa[NSLOT][TM], fb[NSLOT][TN];
+    // The direct modes issue their transposing reads as inline assembly (see lds_tr), except in the kernels with the
+    // highest register pressure (32-byte fragments on the large wave tiles): a fragment the compiler spilled or
+    // moved between such a read and the kernel's own wait would be saved before it has arrived, so those keep the
+    // builtins and the compiler's conservative waits.
+    constexpr bool ASM_TR = !(FW == 2 && TM * TN >= 8);
+    // Results of those reads stay in the 8-byte pieces the instructions return until the kernel has waited for them
+    // (finish_frags): only then are they assembled into fragments, so that no register copy the compiler may need
+    // for the assembly can run ahead of the data.
+    v2i fbr[NSLOT][TN][2 * FW];
     // Shifted direct read: what remains to be done to the B fragments of a slot when they are used (border mask,
     // edge elements).  It is applied then and not at the read, so that nothing waits for the LDS data early.
     bool b_in[NSLOT][TN], b_fs[NSLOT][TN], b_fe[NSLOT][TN];
     unsigned b_vs[NSLOT][TN], b_ve[NSLOT][TN];
     auto finish_frags = [&](int slot) {
         if (!NCHW1 && BSRC != BSRC_NCHWS) return;
-        UNIT_WAIT_LGKM0();                                      // (the transposing reads: see lds_tr)
+        if (ASM_TR) {
+            UNIT_WAIT_LGKM0();                                  // (the transposing reads: see lds_tr)
 #pragma unroll
-        for (int j = 0; j < TN; ++j) lds_tr_done(fb[slot][j]);
+            for (int j = 0; j < TN; ++j) {
+                unsigned w[4 * FW];
+#pragma unroll
+                for (int h = 0; h < 2 * FW; ++h) {
+                    lds_tr_done(fbr[slot][j][h]);
+                    w[2 * h] = (unsigned)fbr[slot][j][h][0];
+                    w[2 * h + 1] = (unsigned)fbr[slot][j][h][1];
+                }
+                fb[slot][j] = Frag<FW>::pack(w);
+            }
+        }
         constexpr bool TAPS = (BSRC == BSRC_NCHWS);
         if (!TAPS && !EDGE1) return;
         constexpr unsigned EMASK = (ES == 1) ? 0xffu : 0xffffu;
@@ -746,8 +766,23 @@ igemm_kernel(const IgemmArgs g)
                     const uint8_t *src = sB + ((ch + f) * EPC + trow) * (BN * ES) +
                                          ((((cbyte >> 4) ^ nchw_swz(trow)) << 4) | (cbyte & 15));
                     static_assert(EPC / RPR == 2, "two transposing reads per 16-byte fragment chunk");
-                    const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) const uint8_t *)src;
-                    const v2i r0 = lds_tr<ES, 0>(lds_addr), r1 = lds_tr<ES, RPR * BN * ES>(lds_addr);
+                    v2i r0, r1;
+                    if (ASM_TR) {
+                        const unsigned lds_addr = (unsigned)(size_t)(__attribute__((address_space(3))) const uint8_t *)src;
+                        fbr[slot][j][2 * f] = lds_tr<ES, 0>(lds_addr);
+                        fbr[slot][j][2 * f + 1] = lds_tr<ES, RPR * BN * ES>(lds_addr);
+                        continue;
+                    } else {
+                        typedef __attribute__((address_space(3))) v2i lds_v2i;
+                        typedef __attribute__((address_space(3))) v4s lds_v4s;
+                        if (ES == 1) {
+                            r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)src);
+                            r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(src + RPR * BN * ES));
+                        } else {
+                            r0 = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s *)src));
+                            r1 = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s *)(src + RPR * BN * ES)));
+                        }
+                    }
                     w[4 * f + 0] = (unsigned)r0[0];
                     w[4 * f + 1] = (unsigned)r0[1];
                     w[4 * f + 2] = (unsigned)r1[0];
@@ -788,7 +823,7 @@ igemm_kernel(const IgemmArgs g)
                     if (TAPS)
                         b_in[slot][j] = (unsigned)(sp[j] + dr) < (unsigned)g.H && (unsigned)(sq[j] + dc) < (unsigned)g.W;
                 }
-                fb[slot][j] = Frag<FW>::pack(w);
+                if (!ASM_TR) fb[slot][j] = Frag<FW>::pack(w);   // (otherwise assembled in finish_frags)
             }
         } else {
 #pragma unroll
@@ -917,6 +952,16 @@ igemm_kernel(const IgemmArgs g)
                 __builtin_amdgcn_sched_barrier(0);
             }
             if (NS & 1) {                            // odd sub-step count: next tile's first fragments sit in slot 1
+                if (ASM_TR && (NCHW1 || BSRC == BSRC_NCHWS)) {   // (their transposing reads must have landed before they are copied)
+                    UNIT_WAIT_LGKM0();
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+#pragma unroll
+                        for (int h = 0; h < 2 * FW; ++h) {
+                            lds_tr_done(fbr[1][j][h]);
+                            fbr[0][j][h] = fbr[1][j][h];
+                        }
+                }
 #pragma unroll
                 for (int i = 0; i < TM; ++i) fa[0][i] = fa[1][i];
 #pragma unroll
