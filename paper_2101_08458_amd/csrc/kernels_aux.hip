@@ -60,6 +60,70 @@ pack_act_kernel(const T *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW
     }
 }
 
+// The same transpose with the two mechanisms of the main kernel's direct 1x1 read: the 64-channel x TP-pixel tile
+// comes into LDS with 16-byte global -> LDS loads (any byte offset; a row of pixels per channel, chunks XOR-swizzled
+// by row), and gfx950's transposing LDS reads hand every lane the 16 bytes of consecutive channels of its pixel, i.e.
+// one chunk of the packed tensor (see read_frags in igemm.hpp for the lane layout).  Lanes 16g..16g+15 of a wave hold
+// chunk g of 16 consecutive pixels, so a wave's store covers whole 64-byte runs of the packed rows.  ES = element
+// bytes; TP is chosen so that a channel row of the tile is a whole 128-byte line.  Needs rows that start on dword boundaries (the range check of those loads works per dword) and a tensor
+// below 2 GiB; the byte-wise kernel above takes the rest.
+template <int ES, int TP>
+__global__ void __launch_bounds__(256)
+pack_act_tr_kernel(const uint8_t *__restrict__ x, uint8_t *__restrict__ xp, int C, int HW, int cp, unsigned x_bytes)
+{
+    constexpr int TC = 64;                        // channels per tile (TP pixels)
+    constexpr int EPC = 16 / ES;                  // elements per 16-byte chunk
+    constexpr int CPR = TP * ES / 16;             // chunks per channel row of the tile
+    constexpr int CRPI = 64 / CPR;                // channel rows per wave-level load
+    constexpr int NI = TC / CRPI / 4;             // loads per wave
+    constexpr int RPR = (ES == 1) ? 8 : 4;        // channel rows per transposing read
+    constexpr int SWZ_UNIT = (ES == 1) ? 2 : 4, SWZ_DIV = (16 / CPR > 1) ? 16 / CPR : 1;
+    constexpr int SWZ_MOD = (CPR / SWZ_UNIT < RPR) ? CPR / SWZ_UNIT : RPR;
+    static_assert(SWZ_DIV * SWZ_MOD == RPR, "the swizzle must repeat with the rows of one transposing read");
+    auto swz = [](int r) { return SWZ_MOD > 1 ? SWZ_UNIT * ((r / SWZ_DIV) % SWZ_MOD) : 0; };
+    __shared__ __attribute__((aligned(16))) uint8_t tile[TC * TP * ES];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int hw0 = blockIdx.x * TP, c0 = blockIdx.y * TC, n = blockIdx.z;
+    const __amdgpu_buffer_rsrc_t rs = make_rsrc(x, x_bytes);
+#pragma unroll
+    for (int j = 0; j < NI; ++j) {
+        const int crow = (j * 4 + wave) * CRPI + lane / CPR;
+        const int px = hw0 + ((lane % CPR) ^ swz(crow)) * EPC;
+        const int c = c0 + crow;
+        // (channels past C read as zeros: the padding of the packed rows; pixels past the image are never stored)
+        const unsigned off = c < C ? (unsigned)((((long)n * C + c) * HW + px) * ES) : UNIT_OOB;
+        dma16(rs, tile + (j * 4 + wave) * 1024, off);
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    const int t16 = lane & 15;
+    const int trow = (ES == 1) ? (t16 >> 1) : (t16 >> 2);      // channel row this lane points at
+    const int tcol = (ES == 1) ? (t16 & 1) * 8 : (t16 & 3) * 4;
+#pragma unroll
+    for (int pg = wave; pg < TP / 16; pg += 4) {               // groups of 16 pixels of the tile, dealt to the waves
+    const int cbyte = (pg * 16 + tcol) * ES;
+    const int px = hw0 + pg * 16 + t16;
+#pragma unroll
+    for (int it = 0; it < TC / EPC / 4; ++it) {
+        const int cc = it * 4 + (lane >> 4);                   // chunk of the tile's channels
+        const uint8_t *src = tile + (cc * EPC + trow) * (TP * ES) + ((((cbyte >> 4) ^ swz(trow)) << 4) | (cbyte & 15));
+        typedef __attribute__((address_space(3))) v2i lds_v2i;
+        typedef __attribute__((address_space(3))) v4s lds_v4s;
+        v2i r0, r1;
+        if (ES == 1) {
+            r0 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)src);
+            r1 = __builtin_amdgcn_ds_read_tr8_b64_v2i32((lds_v2i *)(src + RPR * TP * ES));
+        } else {
+            r0 = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s *)src));
+            r1 = __builtin_bit_cast(v2i, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_v4s *)(src + RPR * TP * ES)));
+        }
+        if (px < HW && c0 + cc * EPC < cp)
+            *reinterpret_cast<v4i *>(xp + (((long)n * HW + px) * cp + c0 + cc * EPC) * ES) = v4i{r0[0], r0[1], r1[0], r1[1]};
+    }
+    }
+}
+
 // Images whose channels fit one 16-byte chunk (network inputs): one thread per pixel reads its
 // CL >= C channel values (coalesced along the pixels; channels past C re-read channel 0 and are
 // zeroed) and writes the pixel's chunk.  The tiled transpose above would spend a 64-channel tile
@@ -113,6 +177,16 @@ hipError_t launch_pack_act_sub(int dtype, int n, int c, int h, int w, int sh, in
     if (c <= chunk && n <= 65535) {
         if (dtype == DT_I8) launch_pack_small((const int8_t *)x, (uint8_t *)xp, n, c, hw, hw_in, Q, srow, scol, st);
         else                launch_pack_small((const uint16_t *)x, (uint8_t *)xp, n, c, hw, hw_in, Q, srow, scol, st);
+        return hipGetLastError();
+    }
+    const int es = (dtype == DT_I8) ? 1 : 2;
+    const long x_bytes = (long)n * c * hw_in * es;
+    if (!sub && ((long)hw * es) % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 15) == 0 && x_bytes < (1L << 31)) {
+        const int cp = (c + chunk - 1) / chunk * chunk;
+        const int tp = 128 / es;                   // tile pixels: one 128-byte line per channel row
+        dim3 grid((hw + tp - 1) / tp, (cp + 63) / 64, n);
+        if (es == 1) hipLaunchKernelGGL((pack_act_tr_kernel<1, 128>), grid, dim3(256), 0, st, (const uint8_t *)x, (uint8_t *)xp, c, hw, cp, (unsigned)x_bytes);
+        else         hipLaunchKernelGGL((pack_act_tr_kernel<2, 64>), grid, dim3(256), 0, st, (const uint8_t *)x, (uint8_t *)xp, c, hw, cp, (unsigned)x_bytes);
         return hipGetLastError();
     }
     if (dtype == DT_I8) {   // callers pass the storage type: one- or two-byte elements
