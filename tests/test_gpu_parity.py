@@ -456,6 +456,31 @@ def test_requant_epilogue_extreme_accumulators():
     assert same(host(y8), exp)
 
 
+PACK_SHAPES = [   # (n, c, h, w): both pack kernels (rows of pixels on dword boundaries or not), ragged tiles
+    (3, 70, 12, 12), (1, 64, 56, 56), (2, 130, 8, 10), (1, 33, 7, 7), (2, 20, 5, 13), (1, 200, 16, 9),
+    (4, 17, 4, 4), (1, 96, 3, 44), (2, 64, 1, 128), (1, 257, 2, 2),
+]
+
+
+@pytest.mark.parametrize("n,c,h,w_", PACK_SHAPES)
+def test_pack_act_layout(n, c, h, w_):
+    """pack_act is a pure permutation with zero fill: xp[n][h*w][cp], cp = channels padded to a 16-byte chunk;
+    element (n, c, h, w) lands at xp[n][h*W + w][c].  Checked for one- and two-byte elements."""
+    g = wl.rng(58, n * 1000 + c)
+    for name, ut, dt, chunk, fn in [("i8", unit.UNIT_I8, np.int8, 16, unit.unit_pack_act_i8),
+                                    ("f16", unit.UNIT_F16, np.uint16, 8, unit.unit_pack_act_f16)]:
+        x = g.integers(0, 256 if dt == np.int8 else 65536, size=(n, c, h, w_)).astype(np.uint16 if dt == np.uint16 else np.uint8)
+        x = x.view(np.int8) if dt == np.int8 else x
+        cp = (c + chunk - 1) // chunk * chunk
+        xp = torch.full((int(unit.unit_packed_act_bytes(n, c, h, w_, ut)),), 0x5a, dtype=torch.uint8, device="cuda:0")
+        announce("pack_act layout", name, n, c, h, w_)
+        fn(n, c, h, w_, dev(x.view(np.int16) if dt == np.uint16 else x), xp)
+        torch.cuda.synchronize()
+        raw = host(xp)[: n * h * w_ * cp * x.itemsize].view(x.dtype).reshape(n, h, w_, cp)
+        assert same(raw[..., :c].transpose(0, 3, 1, 2), x), name
+        assert np.all(raw[..., c:] == 0), name
+
+
 def test_pack_roundtrip_and_glue_ops():
     g = wl.rng(52)
     n, c, h, w_ = 2, 37, 13, 11
