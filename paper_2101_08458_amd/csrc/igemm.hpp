@@ -492,13 +492,7 @@ igemm_kernel(const IgemmArgs g)
     it_s = rt_s = __builtin_amdgcn_readfirstlane(it_s);
     it_cb = rt_cb = __builtin_amdgcn_readfirstlane(it_cb);
     if (EDGE1) rt_cb = ks_begin * NCH;  // 1x1 mode: first reduction chunk of the step being read
-    auto next_tap = [&](int &tr, int &ts, int &tcb) {
-        tcb += NCH;
-        if (tcb >= g.CB) {
-            tcb = 0;
-            if (++ts == g.S) { ts = 0; ++tr; }
-        }
-    };
+    int it_base = ((it_r - g.ph) * g.W + (it_s - g.pw)) * ES, it_cbo = it_cb * EPC * ES * g.PQ;
 
     // issues the DMA of the next tile (the one whose chunk for this thread is kc) into `stage`
     auto issue_tile = [&](int stage) {
@@ -514,8 +508,8 @@ igemm_kernel(const IgemmArgs g)
             // it_cb*EPC.  The loads start at any byte, so every channel row lands with its window of
             // pixels at the tile's own columns.  A chunk that is not wholly inside the tensor comes back
             // as zeros: the few real pixels it holds (first and last channel only) are patched at the read
-            const int delta = (it_r - g.ph) * g.W + (it_s - g.pw);
-            const int base = (it_cb * EPC * g.PQ + delta) * ES;
+            // (it_base: byte offset of the tap, recomputed when the tap changes; it_cbo: of the channel block)
+            const int base = it_base + it_cbo;
             const bool step_ok = (kc - cT) < kend;
 #pragma unroll
             for (int j = 0; j < IB; ++j) {
@@ -523,7 +517,14 @@ igemm_kernel(const IgemmArgs g)
                 const bool ok = step_ok && off >= 0 && off + 16 <= (int)g.b_bytes;
                 dma16(rsB, dst + j * NW * 1024, ok ? (unsigned)off : UNIT_OOB);
             }
-            next_tap(it_r, it_s, it_cb);
+            it_cb += NCH;
+            it_cbo += NCH * EPC * ES * g.PQ;
+            if (it_cb >= g.CB) {
+                it_cb = 0;
+                it_cbo = 0;
+                if (++it_s == g.S) { it_s = 0; ++it_r; }
+                it_base = ((it_r - g.ph) * g.W + (it_s - g.pw)) * ES;
+            }
         } else if (NCHW1) {
             // channel rows of this step: chan0 .. chan0 + BKB/ES; rows past the real channel
             // count or past the slice end come back as zeros
@@ -607,6 +608,29 @@ igemm_kernel(const IgemmArgs g)
             sq[j] = pin - p * g.W;
         }
     }
+    // Shifted direct read, per tap of the step being read (recomputed only when the tap changes; these loops are
+    // bound by instruction issue): pixel index of tile column 0 in the first image, whether this wave may have to
+    // patch the chunk that straddles the tensor's start / end, and the border mask of this lane's pixels.
+    int r_wstart = 0;
+    bool r_ns = false, r_ne = false, r_in[TN];
+    auto reader_tap = [&]() {
+        const int dr = rt_r - g.ph, dc = rt_s - g.pw;
+        r_wstart = col0 + dr * g.W + dc;
+        r_ns = wk == 0 && r_wstart < 0;
+        r_ne = wk == WGK - 1 && r_wstart - (g.cols - g.PQ) + BN > g.PQ;
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            r_in[j] = (unsigned)(sp[j] + dr) < (unsigned)g.H && (unsigned)(sq[j] + dc) < (unsigned)g.W;
+    };
+    if (BSRC == BSRC_NCHWS) reader_tap();
+    auto advance_reader = [&]() {
+        rt_cb += NCH;
+        if (rt_cb >= g.CB) {
+            rt_cb = 0;
+            if (++rt_s == g.S) { rt_s = 0; ++rt_r; }
+            reader_tap();
+        }
+    };
 
     // ---- epilogue bookkeeping.  The unit of work of the epilogue is a GROUP: accumulator elements
     // 4a..4a+3 of one MFMA tile, which a lane holds for four consecutive rows of its column.  With an
@@ -793,8 +817,7 @@ igemm_kernel(const IgemmArgs g)
                     // delta = the tap's offset in the flattened image (0 in the 1x1 mode).  The tensor's start can
                     // only be straddled in the first image, where columns are pixel indices; its end in the last
                     constexpr bool TAPS = (BSRC == BSRC_NCHWS);
-                    const int dr = TAPS ? rt_r - g.ph : 0, dc = TAPS ? rt_s - g.pw : 0;
-                    const int wstart = col0 + dr * g.W + dc;            // pixel index of tile column 0 (first image)
+                    const int wstart = TAPS ? r_wstart : col0;          // pixel index of tile column 0 (first image)
                     const int m = wn * C::WTN + j * MF + lrow;          // this lane's tile column
                     const int pix = wstart + m, cstart = wstart + (m & ~(EPC - 1));
                     const uint8_t *edge = smem + NST * C::STAGE_BYTES;
@@ -803,7 +826,7 @@ igemm_kernel(const IgemmArgs g)
                     b_fs[slot][j] = b_fe[slot][j] = false;
                     b_vs[slot][j] = b_ve[slot][j] = 0;
                     // (both cases are rare and wave-uniform: a scalar branch keeps them out of the other steps)
-                    if (TAPS && sub == 0 && wk == 0 && rt_cb == 0 && wstart < 0) {
+                    if (TAPS && sub == 0 && r_ns && rt_cb == 0) {
                         const bool fix = lchunk == 0 && cstart < 0 && pix >= 0;
                         const uint8_t *src = edge + (fix ? pix * ES : 0);
                         b_vs[slot][j] = (ES == 1) ? *src : *reinterpret_cast<const uint16_t *>(src);
@@ -811,8 +834,9 @@ igemm_kernel(const IgemmArgs g)
                     }
                     // ... and likewise the chunk that straddles its end, for the last channel (edge[16..31])
                     const int last0 = g.cols - g.PQ;                    // first column of the last image
-                    const bool last_step = TAPS ? rt_cb + NCH >= g.CB : rt_cb + NCH >= g.kchunks;
-                    if (sub == NS - 1 && wk == WGK - 1 && last_step && wstart - last0 + BN > g.PQ) {
+                    const bool near_end = TAPS ? (r_ne && rt_cb + NCH >= g.CB)
+                                               : (wk == WGK - 1 && rt_cb + NCH >= g.kchunks && wstart - last0 + BN > g.PQ);
+                    if (sub == NS - 1 && near_end) {
                         const int pixl = pix - last0, cstartl = cstart - last0;
                         const bool fix = lchunk == C::CPL - FW && cstartl + EPC > g.PQ && pixl < g.PQ;
                         const uint8_t *src = edge + 16 + (fix ? (pixl - (g.PQ - EPC)) * ES : 0);
@@ -820,8 +844,7 @@ igemm_kernel(const IgemmArgs g)
                         b_fe[slot][j] = fix;
                     }
                     // taps that fall into the padding (or columns past the image) contribute zero
-                    if (TAPS)
-                        b_in[slot][j] = (unsigned)(sp[j] + dr) < (unsigned)g.H && (unsigned)(sq[j] + dc) < (unsigned)g.W;
+                    if (TAPS) b_in[slot][j] = r_in[j];
                 }
                 if (!ASM_TR) fb[slot][j] = Frag<FW>::pack(w);   // (otherwise assembled in finish_frags)
             }
@@ -863,7 +886,7 @@ igemm_kernel(const IgemmArgs g)
 #pragma unroll
                 for (int s2 = 0; s2 < NS; ++s2) finish_frags(SET * NS + s2);   // (read one step ago)
                 __builtin_amdgcn_sched_barrier(0);
-                if (BSRC == BSRC_NCHWS) next_tap(rt_r, rt_s, rt_cb);
+                if (BSRC == BSRC_NCHWS) advance_reader();
                 if (EDGE1) rt_cb += NCH;
 #pragma unroll
                 for (int s2 = 0; s2 < NS; ++s2) read_frags(next_stage, s2, (SET ^ 1) * NS + s2);
@@ -923,7 +946,7 @@ igemm_kernel(const IgemmArgs g)
                 if (!last) {
                     read_frags(stage, s2 + 1, slot ^ 1);
                 } else {
-                    if (BSRC == BSRC_NCHWS) next_tap(rt_r, rt_s, rt_cb);
+                    if (BSRC == BSRC_NCHWS) advance_reader();
                     if (EDGE1) rt_cb += NCH;
                     read_frags(next_stage, 0, slot ^ 1);
                     issue_tile(stage);                           // tile ks+NST into the stage just freed
