@@ -40,9 +40,9 @@ typedef __bf16   v8bf __attribute__((ext_vector_type(8)));
 enum { DT_I8 = 0, DT_F16 = 1, DT_BF16 = 2, DT_U8A = 3, DT_U8B = 4, DT_FP8 = 5 };
 enum { EPI_RAW = 0, EPI_REQUANT = 1 };
 // where the B operand (columns) comes from: a plain matrix, the packed-NHWC conv gather, or
-// an NCHW tensor read directly (1x1 stride-1 convs of one image: channel rows of pixels,
+// an NCHW tensor read directly (1x1 stride-1 unpadded convs: channel rows of pixels,
 // transposed on the way from LDS into the fragments).  BSRC_NCHWS is the general form of the
-// direct read for one image and stride 1 with "same" padding: output pixel m of the flattened
+// direct read for stride 1 with "same" padding: output pixel m of the flattened
 // image needs input pixel m + delta(tap) of every channel, so the B tile of a step is a window of
 // each channel row shifted by the tap's delta.  The 16-byte loads start at the window's exact byte (any
 // offset), so the tile lands in LDS as in the 1x1 mode and is read the same way; pixels whose tap
