@@ -253,6 +253,27 @@ def test_conv_wpacked_nchw_direct(sh, n):
         assert np.all(np.abs(got - truth) <= 2 * sh.c * 2.0 ** -24 * mag + 1e-30), (tile, split)
 
 
+def test_conv_i8_more_than_four_million_columns():
+    """Column indices beyond 2^22: the kernels' index divisions (pixel -> image / row / column, tile coordinates)
+    must be exact over the whole 31-bit range, not only where a float reciprocal would do.  Two images of
+    1450 x 1450 pixels give 4 205 000 output columns; a 1x1 conv reads them directly from NCHW, a 3x3 conv goes
+    through pack_act and the gather."""
+    g = wl.rng(59)
+    n, c, h = 2, 16, 1450
+    x = wl.int8_activations(g, (n, c, h, h))
+    xd = dev(x)
+    for k, r, pad in [(24, 1, 0), (8, 3, 1)]:
+        w = wl.int8_weights(g, (k, c, r, r))
+        ref = oracle.conv2d_i8(x, w, (1, 1), (pad, pad))
+        d = unit.conv_desc(n, c, h, h, k, r, r, 1, pad)
+        y = torch.full(ref.shape, -7, dtype=torch.int32, device="cuda:0")
+        announce("conv_i8 4.2M columns", k, r)
+        unit.unit_conv2d_i8(d, xd, dev(w), y, None, None, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_I8)))
+        torch.cuda.synchronize()
+        assert same(host(y), ref, f"k {k} window {r}")
+        del y
+
+
 def test_conv_i8_asymmetric_geometry():
     """Different stride / pad / window per axis (the C ABI carries them separately)."""
     g = wl.rng(31)
