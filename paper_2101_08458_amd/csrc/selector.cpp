@@ -27,7 +27,7 @@ static int env_int(const char *name, int dflt)
 
 static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
-TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split)
+TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split, int cb)
 {
     (void)dtype;
     const int CUS = 256;
@@ -62,6 +62,8 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
             tile = (n64 >= 160 || (n64 >= 96 && kchunks > 32)) ? 3 : 4;
         }
     }
+    // shifted direct read of 64-byte pixels (64 int8 or 32 fp16 channels): the small tile with 64-byte steps
+    if (bsrc == BSRC_NCHWS && tile == 4 && cb > 0 && cb % 8 != 0 && cb % 4 == 0) tile = 9;
     int forced = env_int("UNIT_TILE", -1);
     if (forced >= 0 && forced < NUM_TILES) tile = forced;
 

@@ -142,7 +142,7 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
               void *ws, size_t ws_bytes, hipStream_t st, bool allow_split = true)
 {
     const bool conv = bsrc != BSRC_PLAIN;
-    TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, bsrc, allow_split);
+    TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, bsrc, allow_split, conv ? a.CB : 0);
     a.ksteps_per_split = ch.ksteps_per_split;
     // Tile order inside an XCD's run: while the whole B operand is small (<= 8 MiB: every XCD can afford its own
     // copy in L2) a run walks the column tiles of one row tile, so A (the weights) is fetched once in total; large
@@ -240,7 +240,7 @@ bool nchw_shift_ok(const ConvND *d, int dtype, const ConvGeom &g, const void *x,
     // saves is the pack_act launch.  That pays while the layer is launch-bound (one image, a few small ones);
     // measured on the 3x3 layers of the ResNet-50 set, fp16: at batch 16 packing first is 5-25 % faster.
     if ((long)g.rows * g.cols * g.kchunks * 16 > (256L << 20)) return false;
-    TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_NCHWS);
+    TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_NCHWS, true, g.cp * elem_size(dtype) / 16);
     const TileCfg &t = g_tiles[ch.tile];
     // several images whose pixels are not whole 16-byte chunks are tiled one image at a time: not worth it
     // when the tiles of an image would be more than half empty
@@ -316,7 +316,7 @@ size_t conv_fix_bytes(const ConvND *d, int dtype)
 
 size_t conv_split_bytes(const ConvGeom &g, int dtype, int bsrc)
 {
-    TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, bsrc);
+    TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, bsrc, true, g.cp * elem_size(dtype) / 16);
     return ch.split_k > 1 ? align256((size_t)ch.split_k * ((g.out_elems + 3) & ~3L) * 4) : 0;
 }
 // what a caller who does not know the input mode yet must provide

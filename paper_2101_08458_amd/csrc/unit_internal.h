@@ -17,7 +17,7 @@ struct TileCfg {
     int mf;                   // MFMA edge
     int nst;                  // LDS stages
 };
-enum { NUM_TILES = 9 };
+enum { NUM_TILES = 10 };
 extern const TileCfg g_tiles[NUM_TILES];
 extern const TileCfg g_tiles_fp8[NUM_TILES];   // same tiles, wave grids of the fp8 kernels
 
@@ -30,7 +30,8 @@ struct TileChoice {
 
 // selector.cpp (pure host arithmetic)
 // bsrc: where the B operand comes from (BSRC_*); the tile depends on the shape only, the split also on bsrc
-TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split = true);
+// cb: 16-byte channel chunks per pixel (BSRC_NCHWS only: its steps must divide them), 0 = not applicable
+TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split = true, int cb = 0);
 
 // launchers (kernels_*.hip).  All return hipError_t from the launch.
 hipError_t launch_igemm(int dtype, int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);

@@ -13,7 +13,7 @@ from gpu_util import announce, dev, host, forced, f16_rel_err, fp8_rel_err, fp8_
 
 pytestmark = pytest.mark.gpu
 
-ALL_TILES = [0, 1, 2, 3, 4, 5, 6, 7, 8]
+ALL_TILES = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9]
 SHIFTED, DIRECT, PACKED = unit.UNIT_INPUT_DIRECT_SHIFTED, unit.UNIT_INPUT_DIRECT, unit.UNIT_INPUT_PACKED
 
 
@@ -31,7 +31,8 @@ CASES = [
     (wl.ConvShape(512, 7, 7, 64, 1, 1, 1, 0), DIRECT, DIRECT),         # 1x1 whose rows are not 4-byte aligned: end chunk patched
     (wl.ConvShape(384, 5, 3, 48, 1, 1, 1, 0), PACKED, DIRECT),         # 15-pixel image: less than a chunk of one-byte elements
     (wl.ConvShape(256, 6, 6, 48, 1, 1, 1, 0), DIRECT, DIRECT),         # 1x1 with dword-aligned rows: the plain direct read
-    (wl.ConvShape(64, 12, 12, 64, 3, 3, 1, 1), PACKED, SHIFTED),       # 64 channels: one fp16 step, half an int8 step
+    (wl.ConvShape(64, 12, 12, 64, 3, 3, 1, 1), SHIFTED, SHIFTED),      # 64 channels: one fp16 step; int8 takes the tile with 64-byte steps
+    (wl.ConvShape(32, 12, 12, 64, 3, 3, 1, 1), PACKED, SHIFTED),       # 32 channels: 64 bytes of fp16, too few of int8
     (wl.ConvShape(128, 56, 56, 32, 3, 3, 1, 1), SHIFTED, SHIFTED),     # many column tiles
     (wl.ConvShape(128, 12, 12, 16, 3, 3, 1, 1), SHIFTED, SHIFTED),     # 16 output channels: the narrow tile
     (wl.ConvShape(128, 4, 4, 32, 3, 3, 1, 1), PACKED, SHIFTED),        # 16 pixels: too few for 16 one-byte elements per chunk
