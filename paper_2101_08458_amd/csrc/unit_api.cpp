@@ -554,7 +554,7 @@ int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out
     int rc = conv_geom(&nd, dtype, &g);
     if (rc != UNIT_OK) return rc;
     if (!out) return UNIT_EINVAL;
-    fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_GATHER), dtype, out);
+    fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_GATHER, true, g.cp * elem_size(dtype) / 16), dtype, out);
     return UNIT_OK;
 }
 
