@@ -65,7 +65,11 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
     // 64-byte pixels (64 int8 or 32 fp16 channels): the small tile with 64-byte steps.  The shifted direct read
     // needs it (its steps must stay inside one tap); the gather gets one tap per step with it, i.e. the scalar
     // tap walk instead of the per-lane one (config 1, 64 -> 64 channels 3x3 at 56x56: 3.9 -> 3.5 us)
-    if ((bsrc == BSRC_NCHWS || bsrc == BSRC_GATHER) && tile == 4 && cb > 0 && cb % 8 != 0 && cb % 4 == 0) tile = 9;
+    // (for the gather only while the reduction is at most 2 KiB: beyond that twice the steps cost more than the
+    // per-lane tap walk; Table I layers, both types)
+    if (tile == 4 && cb > 0 && cb % 8 != 0 && cb % 4 == 0 &&
+        (bsrc == BSRC_NCHWS || (bsrc == BSRC_GATHER && kchunks <= 128)))
+        tile = 9;
     int forced = env_int("UNIT_TILE", -1);
     if (forced >= 0 && forced < NUM_TILES) tile = forced;
 
