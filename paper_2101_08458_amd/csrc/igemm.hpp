@@ -90,6 +90,10 @@ struct IgemmArgs {
     DivU dv_cpi;                                    // cols_per_img
     DivU dv_tiles_n, dv_band, dv_tiles_img;         // column tiles, 8 * column tiles, column tiles per image (per_img)
     int nimg;                                       // cols / PQ (images)
+    // (appended: the order of the fields above decides how the compiler groups the argument loads of every kernel's
+    // prologue; inserting these three in front of dv_tiles_n, or sorting all fields by use into 64-byte lines, cost
+    // 3-4 % of the batch-1 step each time it was tried)
+    DivU dv_cb, dv_s, dv_r;                         // CB, S, R (the per-lane tap walk of the gather)
 };
 
 // One element of the requantise rule.  v_cvt_f32_i32 and v_rndne_f32 both round to
@@ -447,12 +451,12 @@ igemm_kernel(const IgemmArgs g)
     int ct = 0, cr = 0, cs = 0, ccb = 0;
     constexpr bool uni_tap = (BSRC == BSRC_GATHERU);
     if (BSRC == BSRC_GATHER) {
-        int trs = kc / g.CB;
+        int trs = divu(kc, g.dv_cb);
         ccb = kc - trs * g.CB;
-        ct = trs / (g.R * g.S);
-        int rs = trs - ct * (g.R * g.S);
-        cr = rs / g.S;
-        cs = rs - cr * g.S;
+        int tr = divu(trs, g.dv_s);                 // tap rows from the start (over all planes)
+        cs = trs - tr * g.S;
+        ct = divu(tr, g.dv_r);
+        cr = tr - ct * g.R;
     }
 
     // Gather fast path: when the channel chunks of a pixel are a whole number of steps
@@ -570,16 +574,19 @@ igemm_kernel(const IgemmArgs g)
                                 ((unsigned)w < (unsigned)g.W);
                 dma16(rsB, dst + j * NW * 1024, ok ? offB[j] + tap : UNIT_OOB);
             }
+            // whole taps to move on by (several when a pixel holds fewer chunks than a step), then whole tap rows
+            // and planes: three divisions by reciprocal multiplies, no branches (per-lane loops here cost the
+            // network stems a fifth of their step)
             ccb += NCH;
-            if (ccb >= g.CB) {                       // whole taps to move on by (several when a pixel
-                const int adv = div_small(ccb, g.CB);  // holds fewer chunks than a step)
-                ccb -= adv * g.CB;
-                cs += adv;
-                while (cs >= g.S) {
-                    cs -= g.S;
-                    if (++cr == g.R) { cr = 0; ++ct; }
-                }
-            }
+            const int adv = divu(ccb, g.dv_cb);
+            ccb -= adv * g.CB;
+            cs += adv;
+            const int qs = divu(cs, g.dv_s);
+            cs -= qs * g.S;
+            cr += qs;
+            const int qr = divu(cr, g.dv_r);
+            cr -= qr * g.R;
+            ct += qr;
         } else {
 #pragma unroll
             for (int j = 0; j < IB; ++j)

@@ -162,6 +162,9 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
         a.dv_q = make_div(a.Q);
         a.dv_w = make_div(a.W);
         a.dv_cpi = make_div(a.cols_per_img);
+        a.dv_cb = make_div(a.CB);
+        a.dv_s = make_div(a.S);
+        a.dv_r = make_div(a.R);
     }
     if (ch.split_k == 1) {
         a.split_stride = 0;
