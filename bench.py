@@ -404,10 +404,13 @@ def main():
             t_pack += mult * tp
             byts += mult * c.bytes
             t_api += mult * ta
+            mode = unit.unit_conv2d_input_mode(c.d, c.ut, c.x)
+            # api_us: the call the step makes (tile as chosen for its input mode); conv_us / pack_us: the
+            # packed-path kernels of the same layer timed on their own
             per_layer.append({"shape": list(sh), "x": mult, "api_us": round(ta * 1e3, 2),
                               "conv_us": round(tc * 1e3, 2), "pack_us": round(tp * 1e3, 2),
-                              "tile": tile_str(c.info),
-                              "input": ("packed", "direct", "direct-shifted")[unit.unit_conv2d_input_mode(c.d, c.ut, c.x)]})
+                              "tile": tile_str(unit.unit_select_conv2d_input(c.d, c.ut, mode)),
+                              "input": ("packed", "direct", "direct-shifted")[mode]})
         return ms, ms_eager, macs, t_conv, t_pack, byts, per_layer, t_api
 
     wlname = args.workload

@@ -119,6 +119,11 @@ size_t unit_matmul_workspace(int32_t m, int32_t n, int32_t k, int64_t lda, int64
  * fused spatial dims, split reduction).  conv: rows = k, cols = n*p*q, kbytes = r*s*cp. */
 int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out);
 int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_info *out);
+/* unit_select_conv2d reports the choice for packed activations (unit_conv2d_packed_*, or a wpacked
+ * call that packs first).  The direct input modes may take another tile or grid split (their steps
+ * cost differently): this variant reports the choice for the given unit_input_mode, whether or not
+ * the problem qualifies for it (ask unit_conv2d_input_mode).  UNIT_EINVAL for an unknown mode. */
+int unit_select_conv2d_input(const unit_conv2d_desc *d, int dtype, int input_mode, unit_tile_info *out);
 
 /*
  * How unit_conv2d_wpacked_* (and unit_conv2d_*) will read the NCHW activations `x` of this

@@ -561,6 +561,18 @@ int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out
     return UNIT_OK;
 }
 
+int unit_select_conv2d_input(const unit_conv2d_desc *d, int dtype, int input_mode, unit_tile_info *out)
+{
+    ConvGeom g;
+    ConvND nd(d);
+    int rc = conv_geom(&nd, dtype, &g);
+    if (rc != UNIT_OK) return rc;
+    if (!out || input_mode < UNIT_INPUT_PACKED || input_mode > UNIT_INPUT_DIRECT_SHIFTED) return UNIT_EINVAL;
+    const int bsrc = input_mode == UNIT_INPUT_DIRECT ? BSRC_NCHW : input_mode == UNIT_INPUT_DIRECT_SHIFTED ? BSRC_NCHWS : BSRC_GATHER;
+    fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, bsrc, true, g.cp * elem_size(dtype) / 16), dtype, out);
+    return UNIT_OK;
+}
+
 int unit_conv2d_input_mode(const unit_conv2d_desc *d, int dtype, const void *x)
 {
     ConvGeom g;

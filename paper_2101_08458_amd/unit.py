@@ -66,7 +66,7 @@ _lib = None
 EXPORTS = [
     "unit_version", "unit_status_str", "unit_last_hip_error", "unit_conv2d_out_dims",
     "unit_packed_act_bytes", "unit_packed_weights_bytes", "unit_conv2d_workspace",
-    "unit_conv2d_packed_workspace", "unit_matmul_workspace", "unit_select_conv2d",
+    "unit_conv2d_packed_workspace", "unit_matmul_workspace", "unit_select_conv2d", "unit_select_conv2d_input",
     "unit_select_matmul", "unit_conv2d_i8", "unit_conv2d_f16", "unit_matmul_i8", "unit_matmul_f16",
     "unit_pack_act_i8", "unit_pack_act_f16", "unit_pack_weights_i8", "unit_pack_weights_f16",
     "unit_unpack_act_i8", "unit_conv2d_packed_i8", "unit_conv2d_packed_f16",
@@ -106,6 +106,7 @@ def load():
         "unit_conv2d_packed_workspace": (sz, [dp, ctypes.c_int]),
         "unit_matmul_workspace": (sz, [i32, i32, i32, i64, i64, ctypes.c_int]),
         "unit_select_conv2d": (ctypes.c_int, [dp, ctypes.c_int, tp]),
+        "unit_select_conv2d_input": (ctypes.c_int, [dp, ctypes.c_int, ctypes.c_int, tp]),
         "unit_select_matmul": (ctypes.c_int, [i32, i32, i32, ctypes.c_int, tp]),
         "unit_conv2d_i8": (ctypes.c_int, [dp, vp, vp, vp, rp, vp, vp, sz, vp]),
         "unit_conv2d_f16": (ctypes.c_int, [dp, vp, vp, vp, vp, sz, vp]),
@@ -228,6 +229,13 @@ def unit_matmul_workspace(m, n, k, lda, ldb, dtype):
 def unit_select_conv2d(d, dtype):
     info = unit_tile_info()
     _check(load().unit_select_conv2d(ctypes.byref(d), dtype, ctypes.byref(info)), "unit_select_conv2d")
+    return info
+
+
+def unit_select_conv2d_input(d, dtype, input_mode):
+    info = unit_tile_info()
+    _check(load().unit_select_conv2d_input(ctypes.byref(d), dtype, input_mode, ctypes.byref(info)),
+           "unit_select_conv2d_input")
     return info
 
 

@@ -51,6 +51,19 @@ def test_selector_answers(lib):
     info = unit.unit_select_conv2d(d, unit.UNIT_I8)
     assert info.split_k > 1 and info.workgroups >= 128
     assert unit.unit_conv2d_packed_workspace(d, unit.UNIT_I8) >= info.split_k * 512 * 49 * 4
+    # per input mode: the packed answer is unit_select_conv2d's; the shifted direct read splits a
+    # 14x14 layer of 18 steps that the packed path leaves whole; an unknown mode is an error
+    d = unit.conv_desc(1, 256, 14, 14, 256, 3, 3, 1, 1)
+    packed = unit.unit_select_conv2d(d, unit.UNIT_I8)
+    same = unit.unit_select_conv2d_input(d, unit.UNIT_I8, unit.UNIT_INPUT_PACKED)
+    assert (same.block_m, same.block_n, same.split_k, same.workgroups) == \
+           (packed.block_m, packed.block_n, packed.split_k, packed.workgroups)
+    shifted = unit.unit_select_conv2d_input(d, unit.UNIT_I8, unit.UNIT_INPUT_DIRECT_SHIFTED)
+    assert packed.split_k == 1 and shifted.split_k > 1
+    assert shifted.workgroups == packed.workgroups // packed.split_k * shifted.split_k
+    info = unit.unit_tile_info()
+    assert lib.unit_select_conv2d_input(ctypes.byref(d), unit.UNIT_I8, 3, ctypes.byref(info)) == unit.UNIT_EINVAL
+    assert lib.unit_select_conv2d_input(ctypes.byref(d), unit.UNIT_I8, 0, None) == unit.UNIT_EINVAL
 
 
 def test_error_paths_return_before_launch(lib):
