@@ -41,8 +41,6 @@ def parse():
                              "large_conv_f16", "resnet50_f16_b16", "table1_ablation", "conv3d_resnet18"])
     ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--vendor-context", action="store_true",
-                    help="also time the ROCm libraries PyTorch ships with (hipBLASLt / MIOpen) on the large shapes: context, not a target")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (counter calibration for profiles)")
     return ap.parse_args()
@@ -226,31 +224,6 @@ def cpu_baseline(wl, budget_s=12.0):
                                         f"batch 1, {macs / 1e9:.2f} GMAC in {secs:.2f} s, OpenMP direct loops"}
 
 
-def vendor_context(torch):
-    """What the vendor libraries reachable through PyTorch do on the same box with random operands
-    (hipBLASLt matmul with fp16 / int32 outputs, MIOpen NHWC conv with fp16 output).  Context for the
-    MFMA fractions only: different output types, not a comparison system of the paper."""
-    res = []
-    M = 4096
-    a = torch.randn(M, M, device="cuda:0", dtype=torch.float16)
-    b = torch.randn(M, M, device="cuda:0", dtype=torch.float16)
-    t = event_ms(torch, lambda: torch.matmul(a, b.t()), 20)
-    res.append({"op": "torch.matmul fp16 4096^3 (fp16 out)", "us": round(t * 1e3, 1), "TFLOPS": round(2.0 * M ** 3 / t / 1e9, 1)})
-    ai = torch.randint(-128, 127, (M, M), device="cuda:0", dtype=torch.int8)
-    bi = torch.randint(-128, 127, (M, M), device="cuda:0", dtype=torch.int8)
-    try:
-        t = event_ms(torch, lambda: torch._int_mm(ai, bi.t()), 20)
-        res.append({"op": "torch._int_mm int8 4096^3 (int32 out)", "us": round(t * 1e3, 1), "TOPS": round(2.0 * M ** 3 / t / 1e9, 1)})
-    except Exception as e:                                   # not every build exposes it
-        res.append({"op": "torch._int_mm", "error": str(e)[:80]})
-    x = torch.randn(32, 256, 56, 56, device="cuda:0", dtype=torch.float16).contiguous(memory_format=torch.channels_last)
-    w = torch.randn(256, 256, 3, 3, device="cuda:0", dtype=torch.float16).contiguous(memory_format=torch.channels_last)
-    t = event_ms(torch, lambda: torch.nn.functional.conv2d(x, w, padding=1), 10)
-    res.append({"op": "torch conv2d fp16 NHWC N=32 C=K=256 56x56 3x3 (fp16 out)", "us": round(t * 1e3, 1),
-                "TFLOPS": round(2.0 * 32 * 256 * 56 * 56 * 256 * 9 / t / 1e9, 1)})
-    return res
-
-
 def conv3d_resnet18(torch, unit, wl, out):
     """The paper's conv3d experiment (Section VI-C): every 2-D convolution of a ResNet-18-shaped
     network lifted to 3-D.  The paper does not give the depth; here every layer gets an input depth
@@ -307,8 +280,7 @@ def table1_ablation(torch, unit, wl, out):
     tile with the best grid split; +Tune = best tile and split of the sweep; selector = what
     the library's rule picks.  Fused H*W (the paper's FuseDim) is inherent in the implicit
     GEMM and cannot be switched off."""
-    os.environ.pop("UNIT_TILE", None)
-    os.environ.pop("UNIT_SPLITK", None)
+    unit.unit_debug_force_tile(-1, -1)
     splits = [1, 2, 3, 4, 6, 8, 12]
     rows = []
     for dtype in ("f16", "i8"):
@@ -316,7 +288,7 @@ def table1_ablation(torch, unit, wl, out):
             c = ConvCase(torch, unit, wl, sh, 1, dtype, 6, idx)
 
             def timed(tile, split):
-                os.environ["UNIT_TILE"], os.environ["UNIT_SPLITK"] = str(tile), str(split)
+                unit.unit_debug_force_tile(tile, split)
                 try:
                     if unit.unit_select_conv2d(c.d, c.ut).split_k != split:
                         return None
@@ -325,8 +297,7 @@ def table1_ablation(torch, unit, wl, out):
                         c.ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")
                     return event_ms(torch, c.conv, 20) * 1e3
                 finally:
-                    os.environ.pop("UNIT_TILE", None)
-                    os.environ.pop("UNIT_SPLITK", None)
+                    unit.unit_debug_force_tile(-1, -1)
 
             generic = timed(3, 1)
             splitk = min(t for t in (timed(3, s) for s in splits) if t is not None)
@@ -519,8 +490,6 @@ def main():
             del net
         out["others"] = others
 
-    if args.vendor_context:
-        out["vendor_context"] = vendor_context(torch)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

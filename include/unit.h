@@ -18,6 +18,10 @@
  *   - Return value: UNIT_OK (0) or a negative unit_status.  Argument errors are
  *     detected on the host before anything is launched.
  *   - Concurrent calls are safe if their outputs and workspaces do not overlap.
+ *   - Size limits, all reported as UNIT_ENOTSUP before anything is launched: every tensor of a
+ *     conv call (activations, packed activations, weights, output) and every 256-row band of a
+ *     matmul operand must be smaller than 2 GiB (the kernels address them through 32-bit buffer
+ *     offsets), and the batch n of a conv or pack call must be at most 65535.
  */
 #ifndef UNIT_H
 #define UNIT_H
@@ -115,8 +119,8 @@ size_t unit_conv2d_workspace(const unit_conv2d_desc *d, int dtype);
 size_t unit_conv2d_packed_workspace(const unit_conv2d_desc *d, int dtype);
 size_t unit_matmul_workspace(int32_t m, int32_t n, int32_t k, int64_t lda, int64_t ldb, int dtype);
 
-/* What the selector picks (the paper's tuner, Section III-C.3 / IV-B: register window,
- * fused spatial dims, split reduction).  conv: rows = k, cols = n*p*q, kbytes = r*s*cp. */
+/* What the selector picks (the paper's tuner, Section III-C.3 and the GPU tuning paragraphs of
+ * Section IV-C: register window, fused spatial dims, split reduction).  conv: rows = k, cols = n*p*q, kbytes = r*s*cp. */
 int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out);
 int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_info *out);
 /* unit_select_conv2d reports the choice for packed activations (unit_conv2d_packed_*, or a wpacked
@@ -124,6 +128,18 @@ int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_inf
  * cost differently): this variant reports the choice for the given unit_input_mode, whether or not
  * the problem qualifies for it (ask unit_conv2d_input_mode).  UNIT_EINVAL for an unknown mode. */
 int unit_select_conv2d_input(const unit_conv2d_desc *d, int dtype, int input_mode, unit_tile_info *out);
+
+/*
+ * Test and tuning-sweep hook (the "enumerate and profile" loop of Section IV-C drives it; Section
+ * VI-B's ablation is measured with it): every later call of this process uses compiled tile `tile`
+ * (0 .. 9, see unit_tile_info of a query for what it is) instead of the selector's choice, and
+ * `split_k` workgroups per output tile (clipped to the reduction's steps).  A negative tile and a
+ * split_k < 1 restore the rule for that half.  Process-wide and not synchronised with calls in
+ * flight on other threads: not for production code.  A forced tile that has no kernel for a
+ * call's input mode makes the call fall back to packed activations, or fail with UNIT_ENOTSUP.
+ * Returns UNIT_EINVAL for a tile index that does not exist.
+ */
+int unit_debug_force_tile(int32_t tile, int32_t split_k);
 
 /*
  * How unit_conv2d_wpacked_* (and unit_conv2d_*) will read the NCHW activations `x` of this

@@ -1,9 +1,10 @@
 // Tile-shape selector: maps (rows, cols, reduction length) of the implicit GEMM to one
 // of the compiled tile shapes plus a grid split of the reduction.  This is the paper's
-// tuner (Section III-C.3 and IV-B: accumulator window size, fused spatial dimensions,
-// split reduction; "profile and pick") reduced to a rule fitted to measurements, since
-// the paper finds that tuning beyond fuse + split adds little (Section VI-B).
-#include <cstdlib>
+// tuner (Section III-C.3 and the GPU tuning paragraphs of Section IV-C: accumulator window
+// size, fused spatial dimensions, split reduction; "profile and pick") reduced to a rule fitted
+// to measurements, since the paper finds that tuning beyond fuse + split adds little
+// (Section VI-B).
+#include <atomic>
 
 #include "unit_internal.h"
 
@@ -19,10 +20,27 @@ const TileCfg g_tiles_fp8[NUM_TILES] = {
 };
 #undef UNIT_TILE_CASE
 
-static int env_int(const char *name, int dflt)
+// Process-wide override of the rule (unit_debug_force_tile): -1 = none.  Set by tests and tuning
+// sweeps only; the hot path reads two relaxed atomics.
+static std::atomic<int> g_force_tile{-1}, g_force_split{-1};
+void force_tile(int tile, int split)
 {
-    const char *v = std::getenv(name);
-    return (v && *v) ? std::atoi(v) : dflt;
+    g_force_tile.store(tile, std::memory_order_relaxed);
+    g_force_split.store(split, std::memory_order_relaxed);
+}
+
+// Whether tile `t` has a kernel for this B source and operand type: the LDS footprint and the
+// vmcnt range of IgemmCfg::FITS, recomputed on the host.
+bool tile_fits(int tile, int dtype, int bsrc)
+{
+    if (tile < 0 || tile >= NUM_TILES) return false;
+    const TileCfg &c = (dtype == 4 /* fp8 */ ? g_tiles_fp8 : g_tiles)[tile];
+    const int nw = c.wgm * c.wgn * c.wgk, rpi = 1024 / c.bkb;
+    const int lpt = c.bm / rpi / nw + c.bn / rpi / nw;
+    const long edge = (bsrc == BSRC_NCHWS || bsrc == BSRC_NCHW) ? 1024 : 0;   // (NCHW may become NCHWE)
+    const long ring = (long)c.nst * (c.bm + c.bn) * c.bkb + edge;
+    const long red = c.wgk > 1 ? (long)c.wgk * c.bm * c.bn * 4 : 0;
+    return (ring > red ? ring : red) <= 160 * 1024 && (c.nst - 1) * lpt <= 63;
 }
 
 static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
@@ -70,7 +88,7 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
     if (tile == 4 && cb > 0 && cb % 8 != 0 && cb % 4 == 0 &&
         (bsrc == BSRC_NCHWS || (bsrc == BSRC_GATHER && kchunks <= 128)))
         tile = 9;
-    int forced = env_int("UNIT_TILE", -1);
+    const int forced = g_force_tile.load(std::memory_order_relaxed);
     if (forced >= 0 && forced < NUM_TILES) tile = forced;
 
     const TileCfg &c = g_tiles[tile];
@@ -93,7 +111,7 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
         // about 4 steps measured best (the 14x14 layers)
         split = ksteps / 4;
     }
-    int fs = env_int("UNIT_SPLITK", -1);
+    const int fs = g_force_split.load(std::memory_order_relaxed);
     if (fs >= 1) split = fs;
     if (!allow_split) split = 1;
     if (split > ksteps_tile) split = ksteps_tile;

@@ -101,6 +101,7 @@ int conv_geom(const ConvND *d, int dtype, ConvGeom *g)
 {
     if (!dtype_ok(dtype)) return UNIT_EINVAL;
     if (!desc_ok(d)) return UNIT_EINVAL;
+    if (d->n > 65535) return UNIT_ENOTSUP;        // the layout kernels put the image index in grid.z
     g->o = (d->d + 2 * d->pad_d - d->t) / d->stride_d + 1;
     g->p = (d->h + 2 * d->pad_h - d->r) / d->stride_h + 1;
     g->q = (d->w + 2 * d->pad_w - d->s) / d->stride_w + 1;
@@ -143,6 +144,7 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
 {
     const bool conv = bsrc != BSRC_PLAIN;
     TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, bsrc, allow_split, conv ? a.CB : 0);
+    if (!tile_fits(ch.tile, dtype, bsrc)) return UNIT_ENOTSUP;     // (only a forced tile can fail this)
     a.ksteps_per_split = ch.ksteps_per_split;
     // Tile order inside an XCD's run: while the whole B operand is small (<= 8 MiB: every XCD can afford its own
     // copy in L2) a run walks the column tiles of one row tile, so A (the weights) is fetched once in total; large
@@ -213,10 +215,11 @@ bool nchw_rows_unaligned(const ConvND *d, int dtype)
 
 bool nchw_direct_ok(const ConvND *d, int dtype, const void *x, const unit_requant *rq)
 {
+    ConvGeom g;
+    if (conv_geom(d, dtype, &g) != UNIT_OK) return false;
+    TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_NCHW, true, g.cp * elem_size(dtype) / 16);
+    if (!tile_fits(ch.tile, dtype, BSRC_NCHW)) return false;
     if (nchw_rows_unaligned(d, dtype)) {
-        ConvGeom g;
-        if (conv_geom(d, dtype, &g) != UNIT_OK) return false;
-        TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_NCHW);
         if (((long)d->c * elem_size(dtype)) % g_tiles[ch.tile].bkb != 0) return false;
         if ((long)d->d * d->h * d->w < chunk_elems(dtype)) return false;
     }
@@ -244,6 +247,7 @@ bool nchw_shift_ok(const ConvND *d, int dtype, const ConvGeom &g, const void *x,
     // measured on the 3x3 layers of the ResNet-50 set, fp16: at batch 16 packing first is 5-25 % faster.
     if ((long)g.rows * g.cols * g.kchunks * 16 > (256L << 20)) return false;
     TileChoice ch = select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_NCHWS, true, g.cp * elem_size(dtype) / 16);
+    if (!tile_fits(ch.tile, dtype, BSRC_NCHWS)) return false;
     const TileCfg &t = g_tiles[ch.tile];
     // several images whose pixels are not whole 16-byte chunks are tiled one image at a time: not worth it
     // when the tiles of an image would be more than half empty
@@ -585,6 +589,13 @@ int unit_conv2d_input_mode(const unit_conv2d_desc *d, int dtype, const void *x)
     return UNIT_INPUT_PACKED;
 }
 
+int unit_debug_force_tile(int32_t tile, int32_t split_k)
+{
+    if (tile >= NUM_TILES) return UNIT_EINVAL;
+    force_tile(tile < 0 ? -1 : tile, split_k < 1 ? -1 : split_k);
+    return UNIT_OK;
+}
+
 int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_info *out)
 {
     MatmulGeom g;
@@ -671,6 +682,7 @@ static int pack_act_any(int dtype, int32_t n, int32_t c, int32_t h, int32_t w, c
 {
     size_t need = unit_packed_act_bytes(n, c, h, w, dtype);
     if (!need || !x || !xp) return UNIT_EINVAL;
+    if (n > 65535) return UNIT_ENOTSUP;           // the image index is grid.z
     if (bytes < need) return UNIT_EWORKSPACE;
     if (!aligned16(xp)) return UNIT_EINVAL;
     UNIT_HIP(launch_pack_act(dtype, n, c, h, w, x, xp, static_cast<hipStream_t>(stream)));

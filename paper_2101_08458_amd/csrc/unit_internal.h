@@ -32,6 +32,10 @@ struct TileChoice {
 // bsrc: where the B operand comes from (BSRC_*); the tile depends on the shape only, the split also on bsrc
 // cb: 16-byte channel chunks per pixel (BSRC_NCHWS only: its steps must divide them), 0 = not applicable
 TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split = true, int cb = 0);
+// test / sweep hook behind unit_debug_force_tile: tile and grid split every later select_tile returns (-1 = the rule)
+void force_tile(int tile, int split);
+// whether `tile` has a kernel for this public dtype and B source (LDS footprint, vmcnt range)
+bool tile_fits(int tile, int dtype, int bsrc);
 
 // launchers (kernels_*.hip).  All return hipError_t from the launch.
 hipError_t launch_igemm(int dtype, int bsrc, int tile, const IgemmArgs &a, int split_k, hipStream_t st);

@@ -1,7 +1,6 @@
 """Helpers shared by the GPU parity tests: device upload, case announcement, selector
 overrides, and the fp16 error metric."""
 import contextlib
-import os
 import sys
 
 import numpy as np
@@ -24,23 +23,21 @@ def host(t):
     return t.cpu().numpy()
 
 
+_forced_now = [-1, -1]
+
+
 @contextlib.contextmanager
 def forced(tile=None, split=None):
-    """Override the selector through its environment knobs for the duration of a block."""
-    old = {k: os.environ.get(k) for k in ("UNIT_TILE", "UNIT_SPLITK")}
+    """Override the selector (unit_debug_force_tile) for the duration of a block."""
+    from paper_2101_08458_amd import unit
+    old = list(_forced_now)
+    _forced_now[:] = [-1 if tile is None else int(tile), -1 if split is None else int(split)]
+    unit.unit_debug_force_tile(*_forced_now)
     try:
-        for k, v in (("UNIT_TILE", tile), ("UNIT_SPLITK", split)):
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = str(v)
         yield
     finally:
-        for k, v in old.items():
-            if v is None:
-                os.environ.pop(k, None)
-            else:
-                os.environ[k] = v
+        _forced_now[:] = old
+        unit.unit_debug_force_tile(*old)
 
 
 def f16_rel_err(got, ref, kred):

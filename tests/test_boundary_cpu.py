@@ -166,3 +166,45 @@ def test_input_mode_decisions_are_host_logic(lib):
     # the ResNet-50-shaped set at batch 1: 46 of the 53 layers read NCHW directly
     direct = sum(mode(1, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad) != P for sh in wl.resnet50_convs())
     assert direct == 46
+
+
+def test_debug_force_tile_overrides_and_restores_the_rule(lib):
+    """The sweep / test hook is a setter, not an environment variable: what it forces shows up in the
+    selector queries, a tile without a kernel for an input mode falls back to packed activations,
+    and (-1, -1) restores the rule."""
+    import os
+    d = unit.conv_desc(1, 256, 14, 14, 256, 3, 3, 1, 1)
+    rule = unit.unit_select_conv2d(d, unit.UNIT_I8)
+    x = ctypes.c_void_p(0x7f0000000000)
+    assert lib.unit_conv2d_input_mode(ctypes.byref(d), unit.UNIT_I8, x) == unit.UNIT_INPUT_DIRECT_SHIFTED
+    try:
+        os.environ["UNIT_TILE"], os.environ["UNIT_SPLITK"] = "1", "5"      # not read any more
+        same = unit.unit_select_conv2d(d, unit.UNIT_I8)
+        assert (same.block_m, same.split_k) == (rule.block_m, rule.split_k)
+        unit.unit_debug_force_tile(3, 2)
+        f = unit.unit_select_conv2d(d, unit.UNIT_I8)
+        assert (f.block_m, f.block_n, f.waves_k, f.split_k) == (64, 64, 2, 2)
+        unit.unit_debug_force_tile(2, -1)                       # tile only: the split is the rule's again
+        assert unit.unit_select_conv2d(d, unit.UNIT_I8).waves_k == 4
+        # the direct modes' preconditions are re-checked against a forced tile: 64 int8 channels are half
+        # a step of the 128x128x128 B tile, so the call would pack first instead of running the shifted read
+        d64 = unit.conv_desc(1, 64, 56, 56, 64, 3, 3, 1, 1)
+        unit.unit_debug_force_tile(-1, -1)
+        assert lib.unit_conv2d_input_mode(ctypes.byref(d64), unit.UNIT_I8, x) == unit.UNIT_INPUT_DIRECT_SHIFTED
+        unit.unit_debug_force_tile(1, -1)
+        assert lib.unit_conv2d_input_mode(ctypes.byref(d64), unit.UNIT_I8, x) == unit.UNIT_INPUT_PACKED
+        assert lib.unit_debug_force_tile(10, 1) == unit.UNIT_EINVAL
+    finally:
+        os.environ.pop("UNIT_TILE", None)
+        os.environ.pop("UNIT_SPLITK", None)
+        unit.unit_debug_force_tile(-1, -1)
+    back = unit.unit_select_conv2d(d, unit.UNIT_I8)
+    assert (back.block_m, back.block_n, back.split_k) == (rule.block_m, rule.block_n, rule.split_k)
+
+
+def test_batch_limit_is_refused_before_launch(lib):
+    fake, st = 0x1000, 0
+    d = unit.conv_desc(65536, 16, 2, 2, 8, 1, 1, 1, 0)
+    assert lib.unit_conv2d_i8(ctypes.byref(d), fake, fake, fake, None, None, fake, 1 << 30, st) == unit.UNIT_ENOTSUP
+    assert lib.unit_pack_act_i8(65536, 16, 2, 2, fake, fake, 1 << 30, st) == unit.UNIT_ENOTSUP
+    assert unit.unit_conv2d_workspace(d, unit.UNIT_I8) == 0
