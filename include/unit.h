@@ -40,7 +40,9 @@ enum unit_status {
     UNIT_EOVERFLOW  = -3,   /* byte reduction longer than UNIT_MAX_REDUCTION_*: int32 sum not
                                provably exact                                                   */
     UNIT_EWORKSPACE = -4,   /* workspace NULL or too small                                      */
-    UNIT_EHIP       = -5    /* a HIP runtime call or kernel launch failed                       */
+    UNIT_EHIP       = -5,   /* a HIP runtime call or kernel launch failed                       */
+    UNIT_ESCRATCH   = -6    /* *_static entry point: the problem needs more scratch than
+                               UNIT_STATIC_SCRATCH_BYTES                                        */
 };
 
 /* Operand types: i8 x i8 -> i32, f16 x f16 -> f32, bf16 x bf16 -> f32, u8 x i8 -> i32
@@ -237,6 +239,24 @@ int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const voi
                            void *ws, size_t ws_bytes, void *stream);
 int unit_conv2d_wpacked_f16(const unit_conv2d_desc *d, const uint16_t *x, const void *w_packed,
                             float *y, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * unit_conv2d_wpacked_i8 for callers that cannot allocate device memory or carry a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments without `ws`: the scratch the call needs (packed activations of the layers that are
+ * packed first, partial sums of a reduction split across workgroups; what
+ * unit_conv2d_wpacked_workspace reports) lives in a buffer of UNIT_STATIC_SCRATCH_BYTES inside the
+ * library's device code, one copy per GPU, held until the process ends.  The call makes no
+ * allocating HIP call; its first use on a device looks up that device's copy of the buffer.
+ * A problem that needs more scratch is refused with UNIT_ESCRATCH before anything is launched
+ * (every layer of the ResNet-50- and ResNet-18-shaped sets fits up to batch 16).  All calls on one
+ * GPU share the buffer: calls that overlap in time on one GPU (two streams, two threads) race and
+ * must be serialised by the caller; consecutive calls on one stream are safe.  Results are
+ * identical to unit_conv2d_wpacked_i8's.  Other errors as for that call.
+ */
+#define UNIT_STATIC_SCRATCH_BYTES (16u << 20)
+int unit_conv2d_wpacked_i8_static(const unit_conv2d_desc *d, const int8_t *x, const void *w_packed,
+                                  int32_t *y_i32, const unit_requant *rq, int8_t *y_i8, void *stream);
 
 /* ------------------------------------------------------------------ conv3d
  * The paper's extensibility experiment (Section VI-C, "3D Convolution"): the same path with one

@@ -3,6 +3,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "../../include/unit.h"
 #include "unit_internal.h"
@@ -346,6 +347,8 @@ size_t wpacked_need(const ConvND *d, int dtype, const ConvGeom &g, const void *x
     return packed_act_bytes_nd(d, dtype) + conv_split_bytes(g, dtype, BSRC_GATHER);
 }
 
+int static_scratch(void **ptr);
+
 int conv_plain(const ConvND *d, int dtype, const void *x, const void *w,
                void *y_raw, const unit_requant *rq, int8_t *y_i8,
                void *ws, size_t ws_bytes, void *stream)
@@ -489,6 +492,34 @@ int matmul_any(int dtype, int m, int n, int k, const void *A, long lda, const vo
 
 }  // namespace
 
+// Scratch of unit_conv2d_wpacked_i8_static: one copy per GPU the library's code object is loaded on,
+// held until the process ends.  In host code the name is only a handle for hipGetSymbolAddress; the
+// device address it yields (per device) is what kernels and copies are given.
+static __device__ __align__(256) unsigned char scratch[UNIT_STATIC_SCRATCH_BYTES];
+
+namespace {
+enum { MAX_DEVICES = 64 };
+void *g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device, looked up once per device.
+int static_scratch(void **ptr)
+{
+    int dev = -1;
+    UNIT_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return UNIT_ENOTSUP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        UNIT_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return UNIT_EHIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return UNIT_OK;
+}
+}  // namespace
+
 extern "C" {
 
 int unit_version(void) { return 100; }
@@ -502,6 +533,7 @@ const char *unit_status_str(int status)
     case UNIT_EOVERFLOW:  return "byte reduction too long for an exact int32 sum";
     case UNIT_EWORKSPACE: return "workspace missing or too small";
     case UNIT_EHIP:       return "HIP runtime error";
+    case UNIT_ESCRATCH:   return "problem needs more scratch than the static buffer of the *_static entry point holds";
     default:              return "unknown status";
     }
 }
@@ -751,6 +783,23 @@ int unit_conv2d_wpacked_i8(const unit_conv2d_desc *d, const int8_t *x, const voi
     if (rq ? (!rq->scale || !y_i8) : (!y_i32 || y_i8)) return UNIT_EINVAL;
     ConvND nd(d);
     return conv_wpacked(&nd, UNIT_I8, x, wp, y_i32, rq, y_i8, ws, ws_bytes, stream);
+}
+
+int unit_conv2d_wpacked_i8_static(const unit_conv2d_desc *d, const int8_t *x, const void *wp,
+                                  int32_t *y_i32, const unit_requant *rq, int8_t *y_i8, void *stream)
+{
+    if (rq ? (!rq->scale || !y_i8) : (!y_i32 || y_i8)) return UNIT_EINVAL;
+    ConvND nd(d);
+    ConvGeom g;
+    int rc = conv_geom(&nd, UNIT_I8, &g);
+    if (rc != UNIT_OK) return rc;
+    if (!x || !wp) return UNIT_EINVAL;
+    // the size test comes before the first HIP call, like every other argument error
+    if (wpacked_need(&nd, UNIT_I8, g, x, rq) > (size_t)UNIT_STATIC_SCRATCH_BYTES) return UNIT_ESCRATCH;
+    void *ws = nullptr;
+    rc = static_scratch(&ws);
+    if (rc != UNIT_OK) return rc;
+    return conv_wpacked(&nd, UNIT_I8, x, wp, y_i32, rq, y_i8, ws, UNIT_STATIC_SCRATCH_BYTES, stream);
 }
 
 int unit_conv2d_wpacked_f16(const unit_conv2d_desc *d, const uint16_t *x, const void *wp,

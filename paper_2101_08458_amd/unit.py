@@ -12,7 +12,8 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libunit.so")
 
-UNIT_OK, UNIT_EINVAL, UNIT_ENOTSUP, UNIT_EOVERFLOW, UNIT_EWORKSPACE, UNIT_EHIP = 0, -1, -2, -3, -4, -5
+UNIT_OK, UNIT_EINVAL, UNIT_ENOTSUP, UNIT_EOVERFLOW, UNIT_EWORKSPACE, UNIT_EHIP, UNIT_ESCRATCH = 0, -1, -2, -3, -4, -5, -6
+UNIT_STATIC_SCRATCH_BYTES = 16 << 20
 UNIT_I8, UNIT_F16, UNIT_BF16, UNIT_U8I8, UNIT_FP8 = 0, 1, 2, 3, 4
 UNIT_MAX_REDUCTION_I8 = 131071
 UNIT_MAX_REDUCTION_U8I8 = 65793
@@ -72,6 +73,7 @@ EXPORTS = [
     "unit_unpack_act_i8", "unit_conv2d_packed_i8", "unit_conv2d_packed_f16",
     "unit_maxpool_packed_i8", "unit_global_avgpool_packed_i8", "unit_widen_residual_i8",
     "unit_conv2d_wpacked_workspace", "unit_conv2d_wpacked_i8", "unit_conv2d_wpacked_f16",
+    "unit_conv2d_wpacked_i8_static",
     "unit_conv3d_out_dims", "unit_conv3d_workspace", "unit_conv3d_i8", "unit_conv3d_f16",
     "unit_conv2d_bf16", "unit_matmul_bf16", "unit_conv2d_u8i8", "unit_matmul_u8i8",
     "unit_conv2d_fp8", "unit_matmul_fp8",
@@ -122,6 +124,7 @@ def load():
         "unit_conv2d_wpacked_workspace": (sz, [dp, ctypes.c_int]),
         "unit_conv2d_wpacked_i8": (ctypes.c_int, [dp, vp, vp, vp, rp, vp, vp, sz, vp]),
         "unit_conv2d_wpacked_f16": (ctypes.c_int, [dp, vp, vp, vp, vp, sz, vp]),
+        "unit_conv2d_wpacked_i8_static": (ctypes.c_int, [dp, vp, vp, vp, rp, vp, vp]),
         "unit_conv3d_out_dims": (ctypes.c_int, [d3, ip, ip, ip]),
         "unit_conv3d_workspace": (sz, [d3, ctypes.c_int]),
         "unit_conv3d_i8": (ctypes.c_int, [d3, vp, vp, vp, vp, sz, vp]),
@@ -318,6 +321,12 @@ def unit_conv2d_wpacked_i8(d, x, wp, y_i32, rq, y_i8, ws=None, stream=None):
     _check(load().unit_conv2d_wpacked_i8(ctypes.byref(d), _p(x), _p(wp), _p(y_i32),
                                          ctypes.byref(rq) if rq is not None else None, _p(y_i8),
                                          wsp, wsb, _stream(stream)), "unit_conv2d_wpacked_i8")
+
+
+def unit_conv2d_wpacked_i8_static(d, x, wp, y_i32, rq, y_i8, stream=None):
+    _check(load().unit_conv2d_wpacked_i8_static(ctypes.byref(d), _p(x), _p(wp), _p(y_i32),
+                                                ctypes.byref(rq) if rq is not None else None, _p(y_i8),
+                                                _stream(stream)), "unit_conv2d_wpacked_i8_static")
 
 
 def unit_conv2d_wpacked_f16(d, x, wp, y, ws=None, stream=None):

@@ -208,3 +208,17 @@ def test_batch_limit_is_refused_before_launch(lib):
     assert lib.unit_conv2d_i8(ctypes.byref(d), fake, fake, fake, None, None, fake, 1 << 30, st) == unit.UNIT_ENOTSUP
     assert lib.unit_pack_act_i8(65536, 16, 2, 2, fake, fake, 1 << 30, st) == unit.UNIT_ENOTSUP
     assert unit.unit_conv2d_workspace(d, unit.UNIT_I8) == 0
+
+
+def test_static_scratch_limit_and_argument_errors(lib):
+    """The entry point without a workspace refuses what its static buffer cannot hold, and bad
+    arguments, before its first HIP call (no GPU needed to see it)."""
+    fake = 0x7f0000000000
+    big = unit.conv_desc(64, 3, 224, 224, 64, 7, 7, 2, 3)        # 51 MB of packed activations
+    assert unit.unit_conv2d_wpacked_workspace(big, unit.UNIT_I8) > unit.UNIT_STATIC_SCRATCH_BYTES
+    f = lib.unit_conv2d_wpacked_i8_static
+    assert f(ctypes.byref(big), fake, fake, fake, None, None, 0) == unit.UNIT_ESCRATCH
+    d = unit.conv_desc(1, 64, 8, 8, 32, 3, 3, 2, 1)
+    assert f(ctypes.byref(d), None, fake, fake, None, None, 0) == unit.UNIT_EINVAL
+    assert f(ctypes.byref(d), fake, fake, None, None, None, 0) == unit.UNIT_EINVAL
+    assert "static" in unit.unit_status_str(unit.UNIT_ESCRATCH)

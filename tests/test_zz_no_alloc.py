@@ -1,0 +1,71 @@
+"""unit_conv2d_wpacked_i8_static (scratch in a static device buffer, no workspace argument, no
+allocation) against unit_conv2d_wpacked_i8 with a caller workspace: bit-identical int32 and
+requantised int8 outputs, on calls in a row that shrink (the buffer keeps the previous call's
+bytes: packed activations of one call lie where the next puts split partial sums).  Both sides
+are also held to the oracle, so the reference entry point cannot drift unseen."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2101_08458_amd import unit, workloads as wl
+from gpu_util import announce, dev, host
+
+pytestmark = pytest.mark.gpu
+
+
+def _run_pair(sh, n, seed, requant):
+    """One layer through both entry points; returns the static call's outputs after checking them."""
+    d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
+    p, q = unit.unit_conv2d_out_dims(d)
+    x, w = wl.conv_inputs_i8(sh, n, 77, seed)
+    acc = oracle.conv2d_i8(x, w, (sh.stride,) * 2, (sh.pad,) * 2)
+    xd = dev(x)
+    wp = torch.empty(unit.unit_packed_weights_bytes(d, unit.UNIT_I8), dtype=torch.uint8, device="cuda:0")
+    unit.unit_pack_weights_i8(d, dev(w), wp)
+    need = unit.unit_conv2d_wpacked_workspace(d, unit.UNIT_I8)
+    assert need <= unit.UNIT_STATIC_SCRATCH_BYTES
+    ws = torch.empty(max(need, 256), dtype=torch.uint8, device="cuda:0")
+    mode = unit.unit_conv2d_input_mode(d, unit.UNIT_I8, xd)
+    info = unit.unit_select_conv2d_input(d, unit.UNIT_I8, 0 if requant else mode)
+    announce("no-alloc", tuple(sh), "n", n, "requant", requant, "mode", mode, "split", info.split_k, "ws", need)
+    shape = (n, sh.k, p, q)
+    if requant:
+        g = wl.rng(77, 1000 + seed)
+        scale = (127.0 / np.abs(acc).max(axis=(0, 2, 3)).clip(1) * g.uniform(0.5, 1.0, sh.k)).astype(np.float32)
+        bias = g.integers(-2000, 2000, sh.k, dtype=np.int32)
+        exp8 = oracle.requant(acc + bias[None, :, None, None], scale, relu=True)
+        sd, bd = dev(scale), dev(bias)
+        rq = unit.make_requant(sd, bias=bd, relu=True)
+        y_ref32, y_ref8 = torch.zeros(shape, dtype=torch.int32, device="cuda:0"), torch.zeros(shape, dtype=torch.int8, device="cuda:0")
+        y32, y8 = torch.full(shape, 7, dtype=torch.int32, device="cuda:0"), torch.full(shape, 7, dtype=torch.int8, device="cuda:0")
+        unit.unit_conv2d_wpacked_i8(d, xd, wp, y_ref32, rq, y_ref8, ws)
+        unit.unit_conv2d_wpacked_i8_static(d, xd, wp, y32, rq, y8)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(y_ref8), exp8) and np.array_equal(host(y_ref32), acc)
+        assert np.array_equal(host(y8), host(y_ref8))
+        assert np.array_equal(host(y32), host(y_ref32))
+    else:
+        y_ref = torch.zeros(shape, dtype=torch.int32, device="cuda:0")
+        y = torch.full(shape, 7, dtype=torch.int32, device="cuda:0")
+        unit.unit_conv2d_wpacked_i8(d, xd, wp, y_ref, None, None, ws)
+        unit.unit_conv2d_wpacked_i8_static(d, xd, wp, y, None, None)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(y_ref), acc)
+        assert np.array_equal(host(y), host(y_ref))
+    return mode, info.split_k
+
+
+def test_static_scratch_matches_workspace_call_on_shrinking_calls():
+    # 1. packed first (stride 2) with a reduction split: packed activations + partial sums in the buffer
+    mode, split = _run_pair(wl.ConvShape(512, 14, 14, 512, 3, 3, 2, 1), 2, 0, requant=False)
+    assert mode == unit.UNIT_INPUT_PACKED and split > 1
+    # 2. smaller, shifted direct read with a split: its partial sums land on call 1's packed activations
+    mode, split = _run_pair(wl.ConvShape(256, 14, 14, 256, 3, 3, 1, 1), 1, 1, requant=False)
+    assert mode == unit.UNIT_INPUT_DIRECT_SHIFTED and split > 1
+    # 3. smaller again, requantise epilogue (always packs first), odd sizes: ragged tiles over stale bytes
+    _run_pair(wl.ConvShape(24, 13, 11, 40, 3, 3, 2, 1), 2, 2, requant=True)
+    # 4. a deep 7x7 layer whose epilogue runs in the reduce kernel, then the first (largest) case again
+    mode, split = _run_pair(wl.ConvShape(512, 7, 7, 512, 3, 3, 1, 1), 1, 3, requant=True)
+    assert split > 1
+    _run_pair(wl.ConvShape(512, 14, 14, 512, 3, 3, 2, 1), 2, 4, requant=False)
