@@ -7,9 +7,13 @@ hot path (pack_act NCHW -> blocked NHWC, tile selection, implicit-GEMM MFMA kern
 reduce where selected, NCHW int32 epilogue).  One "step" is one pass over all 53 layers;
 `value` is 2*MACs / time in TOPS and `ms_per_step` is the ResNet-50-shape batch-1 time.
 
-The same JSON line carries `roofline` (dominant kernel, HIP-event timed), `cpu_baseline`
-(the CPU oracle on a bounded sample) and `others` (the compute-bound configurations:
-GEMM 4096^3 and the large conv, int8 and fp16, each with its own MFMA roofline fraction).
+The same JSON line carries `roofline` (HIP events around the timed steps themselves: the
+kernels the step launches, nothing else), `per_layer` (each unique shape's call timed alone,
+with its own roofline time and fraction), `cold_ms_per_step` (the same step rotating over more
+than 512 MB of layer buffers), `cpu_baseline` (the CPU oracle on a bounded sample) and `others`
+(the compute-bound configurations: GEMM 4096^3 and the large conv, int8 and fp16, each with its
+own MFMA roofline fraction).  `--step-only` runs just the timed steps (for profiling: every
+kernel the profiler then sees belongs to a step).
 """
 import argparse
 import json
@@ -28,7 +32,8 @@ HBM_GBS = 8000.0
 # HBM-side bytes per launch (per step for the layer set) of the main kernel, from the committed
 # rocprofv3 counter runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy in the
 # same run); files profiles/igemm_*.md.  Not measurable live, so carried as constants.
-TRAFFIC = {"resnet50_i8_b1": 141.6e6, "gemm_i8_4096": 167.9e6, "gemm_f16_4096": 268.6e6, "large_conv_i8": 138.4e6}
+TRAFFIC = {"resnet50_i8_b1": 145.3e6, "gemm_i8_4096": 167.9e6, "gemm_f16_4096": 268.6e6, "large_conv_i8": 138.4e6}
+COLD_BYTES = 512 << 20     # the cold step rotates over layer-buffer sets totalling more than this
 
 
 def parse():
@@ -41,6 +46,10 @@ def parse():
                              "large_conv_f16", "resnet50_f16_b16", "table1_ablation", "conv3d_resnet18"])
     ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--step-only", action="store_true",
+                    help="layer-set workloads: run only the warm-up and the timed steps (no per-layer timing loops, no "
+                         "cold rotation, no other configurations, no CPU baseline), so that a profile of the run holds "
+                         "the step's kernels only")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (counter calibration for profiles)")
     return ap.parse_args()
@@ -73,6 +82,14 @@ class ConvCase:
         self.info = unit.unit_select_conv2d(self.d, self.ut)
         self.pack()
         torch.cuda.synchronize()
+
+    def clone(self, torch):
+        """Same layer on fresh device buffers (same values): for rotating over more memory than the caches hold."""
+        import copy
+        c = copy.copy(self)
+        c.x, c.wp = self.x.clone(), self.wp.clone()
+        c.xp, c.y, c.ws = torch.empty_like(self.xp), torch.empty_like(self.y), torch.empty_like(self.ws)
+        return c
 
     def pack(self):
         u, sh = self.unit, self.sh
@@ -193,6 +210,31 @@ def wall_ms(torch, fn, steps, warmup, use_graph=True):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def timed_steps(torch, replay, steps, warmup):
+    """`warmup` untimed steps, then exactly `steps` timed ones between two device synchronisations.
+    Returns (wall ms per step, HIP-event ms per step); the events are recorded on torch's current
+    stream, which is the stream the library launches on and the graph replays on."""
+    ramp_up(torch, replay)
+    for _ in range(warmup):
+        replay()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    a.record()
+    for _ in range(steps):
+        replay()
+    b.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    mark_busy()
+    return wall, a.elapsed_time(b) / steps
+
+
+def roof_us(macs, byts, dtype):
+    """Roofline time of one layer: the larger of its MFMA time and its HBM time at the published peaks."""
+    return max(2.0 * macs / (PEAK[dtype] * 1e12), byts / (HBM_GBS * 1e9)) * 1e6
+
+
 def tile_str(info):
     return (f"{info.block_m}x{info.block_n}x{info.block_k_bytes}B waves {info.waves_m}x{info.waves_n}x{info.waves_k} "
             f"mfma{info.mfma} split{info.split_k} wg{info.workgroups}")
@@ -219,9 +261,27 @@ def cpu_baseline(wl, budget_s=12.0):
             secs += time.perf_counter() - t0
             macs += wl.macs(sh)
         passes += 1
-    return {"value": round(2.0 * macs / secs / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
-            "kind": "oracle", "sample": f"{passes} full passes over the 53 ResNet-50-shaped int8 conv layers at "
-                                        f"batch 1, {macs / 1e9:.2f} GMAC in {secs:.2f} s, OpenMP direct loops"}
+    res = {"value": round(2.0 * macs / secs / 1e12, 5), "unit": "TOPS", "cores": oracle.num_threads(),
+           "kind": "oracle", "sample": f"{passes} full passes over the 53 ResNet-50-shaped int8 conv layers at "
+                                       f"batch 1, {macs / 1e9:.2f} GMAC in {secs:.2f} s, OpenMP direct loops"}
+    # the single conv of config 1 (1x64x56x56 * 64x64x3x3) on all cores and on one thread
+    x, w = wl.conv_inputs_i8(wl.CONFIG1, 1, 1, 0)
+    full = oracle.num_threads()
+
+    def best_of(reps):
+        best = 1e30
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            oracle.conv2d_i8(x, w, (1, 1), (1, 1))
+            best = min(best, time.perf_counter() - t0)
+        return best
+    res["config1_ms_all_cores"] = round(best_of(5) * 1e3, 3)
+    oracle.set_num_threads(1)
+    try:
+        res["config1_ms_single_thread"] = round(best_of(3) * 1e3, 3)
+    finally:
+        oracle.set_num_threads(full)
+    return res
 
 
 def conv3d_resnet18(torch, unit, wl, out):
@@ -345,26 +405,33 @@ def main():
     others = []
 
     def conv_set(dtype, n, config_id):
+        """The 53 layers, each with buffers and values of its own (as in a network: no two layers share weights
+        or activations, so a repeated shape gains nothing from the caches), plus the first case of every unique
+        shape for the per-layer table."""
         layers = wl.resnet50_convs()
+        seq = [ConvCase(torch, unit, wl, sh, n, dtype, config_id, idx) for idx, sh in enumerate(layers)]
         uniq = {}
-        for sh in layers:
-            if sh not in uniq:
-                uniq[sh] = ConvCase(torch, unit, wl, sh, n, dtype, config_id, len(uniq))
-        return layers, uniq
+        for sh, c in zip(layers, seq):
+            uniq.setdefault(sh, c)
+        return layers, seq, uniq
 
-    def run_conv_set(dtype, n, config_id, steps, warmup):
-        layers, uniq = conv_set(dtype, n, config_id)
-        seq = [uniq[sh] for sh in layers]
+    def run_conv_set(dtype, n, config_id, steps, warmup, step_only=False, cold=True):
+        layers, seq, uniq = conv_set(dtype, n, config_id)
 
         def step():
             for c in seq:
                 c.api()
-        ms = wall_ms(torch, step, steps, warmup)
-        ms_eager = wall_ms(torch, step, max(steps // 10, 3), 2, use_graph=False)
+        g = capture(torch, step)
+        ms, ev_ms = timed_steps(torch, g.replay, steps, warmup)
         macs = sum(c.macs for c in seq)
-        # per-layer kernel-only and pack durations from HIP events (same launch configuration)
+        byts = sum(c.bytes for c in seq)
+        res = {"ms": ms, "event_ms": ev_ms, "macs": macs, "bytes": byts}
+        if step_only:
+            return res
+        res["eager_ms"] = wall_ms(torch, step, max(steps // 10, 3), 2, use_graph=False)
+        # per unique shape, each call alone (a graph of 50 back-to-back calls of the same layer: warm caches):
+        # api = the call the step makes; conv / pack = the packed-path kernels of the same layer, for comparison
         t_conv = t_pack = t_api = 0.0
-        byts = 0
         per_layer = []
         for sh, c in uniq.items():
             mult = sum(1 for s in layers if s == sh)
@@ -373,16 +440,34 @@ def main():
             ta = event_ms(torch, c.api, 50)
             t_conv += mult * tc
             t_pack += mult * tp
-            byts += mult * c.bytes
             t_api += mult * ta
             mode = unit.unit_conv2d_input_mode(c.d, c.ut, c.x)
-            # api_us: the call the step makes (tile as chosen for its input mode); conv_us / pack_us: the
-            # packed-path kernels of the same layer timed on their own
+            ru = roof_us(c.macs, c.bytes, dtype)
             per_layer.append({"shape": list(sh), "x": mult, "api_us": round(ta * 1e3, 2),
-                              "conv_us": round(tc * 1e3, 2), "pack_us": round(tp * 1e3, 2),
+                              "roof_us": round(ru, 3), "frac": round(ru / (ta * 1e3), 4),
+                              "bytes": c.bytes, "GBps": round(c.bytes / (ta * 1e-3) / 1e9, 1),
+                              "packed_conv_us": round(tc * 1e3, 2), "pack_us": round(tp * 1e3, 2),
                               "tile": tile_str(unit.unit_select_conv2d_input(c.d, c.ut, mode)),
                               "input": ("packed", "direct", "direct-shifted")[mode]})
-        return ms, ms_eager, macs, t_conv, t_pack, byts, per_layer, t_api
+        res.update({"t_conv": t_conv, "t_pack": t_pack, "t_api": t_api, "per_layer": per_layer})
+        if cold:
+            # the same step on rotating buffer sets totalling more than COLD_BYTES, so that no layer finds its
+            # operands in L2 or the Infinity Cache from an earlier step
+            sets = [seq]
+            while len(sets) * byts <= COLD_BYTES:
+                sets.append([c.clone(torch) for c in seq])
+
+            def rotation():
+                for cases in sets:
+                    for c in cases:
+                        c.api()
+            gc = capture(torch, rotation)
+            _, cold_ev = timed_steps(torch, gc.replay, max(steps // len(sets), 5), 2)
+            res["cold_ms"] = cold_ev / len(sets)
+            res["cold_sets"] = len(sets)
+            del gc, sets
+            torch.cuda.empty_cache()
+        return res
 
     wlname = args.workload
     if wlname == "conv3d_resnet18":
@@ -395,7 +480,8 @@ def main():
         return
     if wlname in ("resnet50_i8_b1", "resnet50_f16_b16"):
         dtype, n, cid = ("i8", 1, 3) if wlname == "resnet50_i8_b1" else ("f16", 16, 4)
-        ms, ms_eager, macs, t_conv, t_pack, byts, per_layer, t_api = run_conv_set(dtype, n, cid, args.steps, args.warmup)
+        r = run_conv_set(dtype, n, cid, args.steps, args.warmup, step_only=args.step_only)
+        ms, macs, byts = r["ms"], r["macs"], r["bytes"]
         tops = 2.0 * macs / (ms * 1e-3) / 1e12
         out.update({
             "metric": "int8 conv2d TOPS" if dtype == "i8" else "fp16 conv2d TFLOPS",
@@ -406,20 +492,37 @@ def main():
                                    f"{'int8->int32' if dtype == 'i8' else 'fp16->fp32'}, NCHW in -> NCHW out per layer "
                                    "(one unit_conv2d_wpacked call: pack_act + implicit-GEMM conv [+ split reduce], or the "
                                    "kernel reading NCHW directly where the shape allows it: see per_layer.input), "
-                                   "weights pre-packed",
+                                   "weights pre-packed, every layer on buffers of its own",
                        "layers": 53, "batch": n, "gmacs_per_step": round(macs / 1e9, 3)},
             "launch": "one HIP graph per step (all kernels of the 53 layers), replayed",
-            "eager_ms_per_step": round(ms_eager, 4),
-            "api_call_ms_per_step": round(t_api, 4),
-            "kernel_only_ms_per_step": round(t_conv, 4), "pack_act_ms_per_step": round(t_pack, 4),
+            "event_ms_per_step": round(r["event_ms"], 4),
         })
-        gbs = byts / (t_conv * 1e-3) / 1e9
+        # The roofline figure is taken over the timed steps themselves: algorithmic bytes of the 53 layers (each
+        # operand once, each output once) / HIP-event time of a step, i.e. all 53 main-kernel launches plus the
+        # pack_act and split-reduce launches the step needs and the gaps between launches.
+        gbs = byts / (r["event_ms"] * 1e-3) / 1e9
         out["roofline"] = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_GBS, "unit": "GB/s",
                            "frac": round(gbs / HBM_GBS, 4), "traffic": TRAFFIC.get(wlname),
                            "algorithmic_bytes": byts,
-                           "kernel": "igemm_kernel (conv, all 53 launches; split-reduce time included where selected)",
-                           "note": "sum of algorithmic bytes (x + w + y once) / sum of HIP-event kernel durations"}
-        out["per_layer"] = per_layer
+                           "kernel": "igemm_kernel: the 53 launches of one step, with the step's pack_act and "
+                                     "splitk_reduce launches and the inter-launch gaps inside the measured time",
+                           "note": "sum of algorithmic bytes (x + w + y once per layer) / HIP-event time of one timed step"}
+        if not args.step_only:
+            t_roof = sum(l["roof_us"] * l["x"] for l in r["per_layer"]) / 1e3
+            out.update({
+                "eager_ms_per_step": round(r["eager_ms"], 4),
+                # sums over the 53 layers of each call timed alone (warm caches), and of the packed-path kernels
+                "api_call_ms_per_step": round(r["t_api"], 4),
+                "packed_path_kernel_only_ms_per_step": round(r["t_conv"], 4),
+                "packed_path_pack_act_ms_per_step": round(r["t_pack"], 4),
+                "roofline_ms_per_step": round(t_roof, 5),
+                "frac_of_per_layer_roofline": round(t_roof / r["event_ms"], 4),
+            })
+            if "cold_ms" in r:
+                out["cold_ms_per_step"] = round(r["cold_ms"], 4)
+                out["cold_note"] = (f"same step over {r['cold_sets']} rotating sets of layer buffers "
+                                    f"({r['cold_sets'] * byts / 2 ** 20:.0f} MiB of operands and outputs per rotation)")
+            out["per_layer"] = r["per_layer"]
     else:
         dtype = "i8" if "_i8" in wlname else "f16"
         if wlname.startswith("gemm"):
@@ -439,7 +542,7 @@ def main():
         out["roofline"]["algorithmic_bytes"] = c.bytes
         out["roofline"]["kernel_us"] = round(kms * 1e3, 2)
 
-    if not args.no_others:
+    if not args.no_others and not args.step_only:
         def add(name, dtype, macs, byts, ms, info, extra=None):
             tops = 2.0 * macs / (ms * 1e-3) / 1e12
             e = {"workload": name, "dtype": dtype, "us": round(ms * 1e3, 2), "value": round(tops, 2),
@@ -474,11 +577,14 @@ def main():
         g = GemmCase(torch, unit, wl, 1, 1000, 2048, "i8")
         add("gemm FC 1x1000x2048", "i8", g.macs, g.bytes, event_ms(torch, g.run, 200), g.info)
         if wlname != "resnet50_f16_b16":
-            ms, _, macs, t_conv, t_pack, byts, _, _ = run_conv_set("f16", 16, 4, 20, 3)
-            others.append({"workload": "53 ResNet-50-shaped conv layers, batch 16, fp16->fp32, pack_act + conv",
-                           "dtype": "f16", "ms": round(ms, 3), "value": round(2.0 * macs / (ms * 1e-3) / 1e12, 2),
-                           "unit": "TFLOPS", "kernel_only_ms": round(t_conv, 3), "pack_act_ms": round(t_pack, 3),
-                           "kernel_GBps": round(byts / (t_conv * 1e-3) / 1e9, 1)})
+            r = run_conv_set("f16", 16, 4, 20, 3, cold=False)
+            t_roof = sum(l["roof_us"] * l["x"] for l in r["per_layer"]) / 1e3
+            others.append({"workload": "53 ResNet-50-shaped conv layers, batch 16, fp16->fp32, one unit_conv2d_wpacked_f16 call per layer",
+                           "dtype": "f16", "ms": round(r["ms"], 3), "event_ms": round(r["event_ms"], 3),
+                           "value": round(2.0 * r["macs"] / (r["ms"] * 1e-3) / 1e12, 2), "unit": "TFLOPS",
+                           "GBps": round(r["bytes"] / (r["event_ms"] * 1e-3) / 1e9, 1),
+                           "roofline_ms": round(t_roof, 4), "frac_of_per_layer_roofline": round(t_roof / r["event_ms"], 4),
+                           "packed_path_kernel_only_ms": round(r["t_conv"], 3), "packed_path_pack_act_ms": round(r["t_pack"], 3)})
         from paper_2101_08458_amd.resnet18_int8 import ResNet18Int8, random_params
         for batch in (1, 8):
             net = ResNet18Int8(batch, random_params(wl.rng(5, batch)))
@@ -490,7 +596,7 @@ def main():
             del net
         out["others"] = others
 
-    if not args.no_cpu:
+    if not args.no_cpu and not args.step_only:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
 
