@@ -90,3 +90,16 @@ def same(got, exp, what=""):
               f"got {got.reshape(-1)[i].tolist()} exp {exp.reshape(-1)[i].tolist()}", flush=True)
         return False
     return True
+
+
+def as_accurate_as_oracle(got, ref, truth):
+    """Accuracy check that does not depend on the tolerance floor of f16_rel_err: against the float64
+    accumulation of the exact products, the kernel's rms error may be at most twice the rms error of
+    the sequential fp32 oracle, plus half an fp32 unit in the last place of the rms output (cases
+    whose sums are exact on both sides, and tiny samples).  A kernel that loses more precision than
+    plain fp32 accumulation in some order can lose, fails this whatever the floor is."""
+    t = truth.astype(np.float64)
+    e_got = float(np.sqrt(np.mean((got.astype(np.float64) - t) ** 2)))
+    e_ref = float(np.sqrt(np.mean((ref.astype(np.float64) - t) ** 2)))
+    floor = 2.0 ** -24 * float(np.sqrt(np.mean(t ** 2)))
+    return e_got <= 2.0 * e_ref + floor

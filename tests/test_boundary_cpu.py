@@ -222,3 +222,39 @@ def test_static_scratch_limit_and_argument_errors(lib):
     assert f(ctypes.byref(d), None, fake, fake, None, None, 0) == unit.UNIT_EINVAL
     assert f(ctypes.byref(d), fake, fake, None, None, None, 0) == unit.UNIT_EINVAL
     assert "static" in unit.unit_status_str(unit.UNIT_ESCRATCH)
+
+
+def test_build_check_rejects_spills_in_inline_asm_variants(tmp_path):
+    """The build fails when a direct-read kernel variant that issues its transposing LDS reads as inline
+    assembly has scratch or spilled vector registers (the compiler's resource remarks are parsed by
+    csrc/check_resources.py); variants that keep the builtins may spill."""
+    import glob
+    import subprocess
+    import sys
+    script = os.path.join(ROOT, "paper_2101_08458_amd", "csrc", "check_resources.py")
+
+    def remark(args, scratch, vspill):
+        name = "_ZN4unit12igemm_kernelI" + "".join(f"Li{a}E" for a in args) + "EEvNS_9IgemmArgsE"
+        tail = " [-Rpass-analysis=kernel-resource-usage]\n"
+        return (f"./igemm.hpp:301:1: remark: Function Name: {name}{tail}"
+                f"./igemm.hpp:301:1: remark:     VGPRs: 128{tail}"
+                f"./igemm.hpp:301:1: remark:     ScratchSize [bytes/lane]: {scratch}{tail}"
+                f"./igemm.hpp:301:1: remark:     SGPRs Spill: 9{tail}"
+                f"./igemm.hpp:301:1: remark:     VGPRs Spill: {vspill}{tail}")
+
+    def run(text):
+        f = tmp_path / "k.res"
+        f.write_text(text)
+        return subprocess.run([sys.executable, script, str(f)], capture_output=True, text=True).returncode
+
+    direct_i8 = [0, 32, 32, 128, 1, 1, 4, 32, 4, 2, 3, 0]
+    gather_i8 = [0, 32, 32, 128, 1, 1, 4, 32, 4, 2, 1, 0]
+    fp8_big = [5, 256, 256, 128, 2, 4, 1, 32, 2, 1, 2, 0]       # 32-byte fragments, 8 MFMA tiles: builtin reads
+    assert run(remark(direct_i8, 0, 0) + remark(gather_i8, 64, 12)) == 0     # spills elsewhere do not matter
+    assert run(remark(direct_i8, 16, 0)) == 1
+    assert run(remark(direct_i8, 0, 3)) == 1
+    assert run(remark(fp8_big, 40, 7) + remark(direct_i8, 0, 0)) == 0
+    assert run(remark(gather_i8, 0, 0)) == 1                                 # nothing to check: wrong input
+    res = sorted(glob.glob(os.path.join(ROOT, "paper_2101_08458_amd", "csrc", "_build", "*.res")))
+    if res:                                                                  # the tree's own build, when present
+        assert subprocess.run([sys.executable, script] + res, capture_output=True).returncode == 0

@@ -5,7 +5,7 @@ import torch
 
 import oracle
 from paper_2101_08458_amd import unit, workloads as wl
-from gpu_util import announce, dev, host, forced, f16_rel_err, same
+from gpu_util import announce, dev, host, forced, f16_rel_err, as_accurate_as_oracle, same
 
 pytestmark = pytest.mark.gpu
 
@@ -50,6 +50,7 @@ def test_conv3d_parity(case):
         got = host(yh)
         assert f16_rel_err(got, refh, kred) <= 1e-3, (tile, split)
         assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), (tile, split)
+        assert as_accurate_as_oracle(got, refh, truth), (tile, split)
 
 
 def test_conv3d_depth_one_matches_conv2d_call():

@@ -9,7 +9,7 @@ import torch
 
 import oracle
 from paper_2101_08458_amd import unit, workloads as wl
-from gpu_util import announce, dev, host, forced, f16_rel_err, fp8_rel_err, fp8_bound, same
+from gpu_util import announce, dev, host, forced, f16_rel_err, as_accurate_as_oracle, fp8_rel_err, fp8_bound, same
 
 pytestmark = pytest.mark.gpu
 
@@ -101,6 +101,7 @@ def test_shifted_direct_f16_bf16_fp8(case):
             else:
                 assert f16_rel_err(got, ref, kred) <= 1e-3, (name, tile, split)
                 assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), (name, tile, split)
+                assert as_accurate_as_oracle(got, ref, truth), (name, tile, split)
 
 
 BATCHES = [   # (n, shape): images of whole 16-byte chunks (tiles span images) and others (tiled per image)
@@ -160,6 +161,7 @@ def test_shifted_direct_batches(case):
             else:
                 assert f16_rel_err(got, reff, kred) <= 1e-3, (name, tile)
                 assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), (name, tile)
+                assert as_accurate_as_oracle(got, reff, truth), (name, tile)
 
 
 def test_shifted_direct_border_taps_exact():

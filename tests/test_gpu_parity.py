@@ -9,7 +9,7 @@ import torch
 
 import oracle
 from paper_2101_08458_amd import unit, workloads as wl
-from gpu_util import announce, dev, host, forced, f16_rel_err, same
+from gpu_util import announce, dev, host, forced, f16_rel_err, as_accurate_as_oracle, same
 
 pytestmark = pytest.mark.gpu
 
@@ -109,6 +109,7 @@ def test_matmul_f16_parity(M, N, K):
             got = run_matmul_f16(A, B)
         assert f16_rel_err(got, ref, K) <= 1e-3, (tile, split)
         assert np.all(np.abs(got - truth) <= 2 * K * 2.0 ** -24 * mag + 1e-30), (tile, split)
+        assert as_accurate_as_oracle(got, ref, truth), (tile, split)
 
 
 def test_matmul_f16_exact_cases():
@@ -148,11 +149,16 @@ def test_matmul_f16_full_size_sampled():
     A, B = wl.gemm_inputs_f16(M, N, K)
     announce("matmul_f16 4096^3")
     got = run_matmul_f16(A, B)
-    rows = np.array([0, 1, 255, 256, 2047, 4095])
-    ref = oracle.matmul_f16(np.ascontiguousarray(A[rows]), B)
-    truth, mag = oracle.matmul_f16_f64(np.ascontiguousarray(A[rows]), B)
-    assert f16_rel_err(got[rows], ref, K) <= 1e-3
-    assert np.all(np.abs(got[rows] - truth) <= 2 * K * 2.0 ** -24 * mag)
+    g = wl.rng(26)
+    rows = np.unique(np.concatenate([[0, 1, 255, 256, 2047, 4095], g.integers(0, M, 12)]))
+    cols = np.unique(np.concatenate([[0, 255, 256, 4095], g.integers(0, N, 12)]))
+    for sel, Asel, Bsel in ((np.s_[rows], np.ascontiguousarray(A[rows]), B),
+                            (np.s_[:, cols], A, np.ascontiguousarray(B[cols]))):
+        ref = oracle.matmul_f16(Asel, Bsel)
+        truth, mag = oracle.matmul_f16_f64(Asel, Bsel)
+        assert f16_rel_err(got[sel], ref, K) <= 1e-3
+        assert np.all(np.abs(got[sel] - truth) <= 2 * K * 2.0 ** -24 * mag)
+        assert as_accurate_as_oracle(got[sel], ref, truth)
 
 
 # ------------------------------------------------------------------ conv2d
@@ -251,6 +257,7 @@ def test_conv_wpacked_nchw_direct(sh, n):
         got = host(yh)
         assert f16_rel_err(got, refh, sh.c) <= 1e-3, (tile, split)
         assert np.all(np.abs(got - truth) <= 2 * sh.c * 2.0 ** -24 * mag + 1e-30), (tile, split)
+        assert as_accurate_as_oracle(got, refh, truth), (tile, split)
 
 
 def test_conv_i8_more_than_four_million_columns():
@@ -331,6 +338,7 @@ def test_conv_f16_table1_layers():
         got = run_conv_f16(sh, 1, x, w)
         assert f16_rel_err(got, ref, kred) <= 1e-3, sh
         assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), sh
+        assert as_accurate_as_oracle(got, ref, truth), sh
 
 
 @pytest.mark.parametrize("sh,n", SMALL_CONVS[:6])
@@ -346,6 +354,7 @@ def test_conv_f16_small_all_tiles(sh, n):
             got = run_conv_f16(sh, n, x, w)
         assert f16_rel_err(got, ref, kred) <= 1e-3, (tile, split)
         assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), (tile, split)
+        assert as_accurate_as_oracle(got, ref, truth), (tile, split)
 
 
 def test_conv_f16_power_of_two_inputs_bit_exact():
@@ -367,37 +376,37 @@ def test_conv_f16_power_of_two_inputs_bit_exact():
     assert same(b1.view(np.uint32), b2.view(np.uint32))
 
 
-def sampled_conv_check_f16(sh, n, x, w, got, samples, g):
-    """Compare sampled outputs with the oracle run on the receptive field of each."""
-    P, Q = wl.out_hw(sh)
+def plane_check_f16(sh, n, x, w, got, planes):
+    """Whole output planes (one image, one output channel: every pixel, so every column tile, image border and
+    ragged tail of that row of the implicit GEMM) against the oracle run on that image and that filter."""
+    st, pd = (sh.stride,) * 2, (sh.pad,) * 2
     kred = sh.c * sh.r * sh.s
-    worst = 0.0
-    refs, gots = [], []
-    for _ in range(samples):
-        ni, k, p, q = int(g.integers(n)), int(g.integers(sh.k)), int(g.integers(P)), int(g.integers(Q))
-        patch = np.zeros((1, sh.c, sh.r, sh.s), np.uint16)
-        for r in range(sh.r):
-            for s in range(sh.s):
-                h, ww = p * sh.stride + r - sh.pad, q * sh.stride + s - sh.pad
-                if 0 <= h < sh.h and 0 <= ww < sh.w:
-                    patch[0, :, r, s] = x[ni, :, h, ww]
-        ref = oracle.conv2d_f16(patch, np.ascontiguousarray(w[k:k + 1]))[0, 0, 0, 0]
-        truth, mag = oracle.conv2d_f16_f64(patch, np.ascontiguousarray(w[k:k + 1]))
-        assert abs(got[ni, k, p, q] - truth[0, 0, 0, 0]) <= 2 * kred * 2.0 ** -24 * mag[0, 0, 0, 0] + 1e-30
-        refs.append(ref); gots.append(got[ni, k, p, q])
-    return f16_rel_err(np.array(gots), np.array(refs), kred)
+    refs, gots, truths = [], [], []
+    for ni, k in planes:
+        xi, wk = np.ascontiguousarray(x[ni:ni + 1]), np.ascontiguousarray(w[k:k + 1])
+        ref = oracle.conv2d_f16(xi, wk, st, pd)[0, 0]
+        truth, mag = oracle.conv2d_f16_f64(xi, wk, st, pd)
+        g_ = got[ni, k]
+        assert np.all(np.abs(g_ - truth[0, 0]) <= 2 * kred * 2.0 ** -24 * mag[0, 0] + 1e-30), (sh, ni, k)
+        refs.append(ref.ravel()); gots.append(g_.ravel()); truths.append(truth[0, 0].ravel())
+    refs, gots, truths = np.concatenate(refs), np.concatenate(gots), np.concatenate(truths)
+    assert as_accurate_as_oracle(gots, refs, truths), sh
+    return f16_rel_err(gots, refs, kred)
 
 
-def test_conv_f16_resnet50_layers_batch16_sampled():
+def test_conv_f16_resnet50_layers_batch16_planes():
+    """Config 4 at its full size, every one of the 23 unique shapes, in the launch configuration the benchmark
+    times.  Six whole (image, channel) planes per layer: first and last image, first and last output channel
+    (first and last row tile), and four random pairs."""
     g = wl.rng(43)
+    n = 16
     for idx, (sh, mult) in enumerate(wl.unique_shapes(wl.resnet50_convs())):
-        if idx % 3 != 0 and sh.r == 1:
-            continue                                  # every 3x3 / 7x7 layer, a third of the 1x1 ones
-        x, w = wl.conv_inputs_f16(sh, 16, 4, idx)
+        x, w = wl.conv_inputs_f16(sh, n, 4, idx)
         announce("conv_f16 resnet50 b16", idx, sh)
-        got = run_conv_f16(sh, 16, x, w)
+        got = run_conv_f16(sh, n, x, w)
         assert np.all(np.isfinite(got))
-        assert sampled_conv_check_f16(sh, 16, x, w, got, 48, g) <= 1e-3, sh
+        planes = [(0, 0), (n - 1, sh.k - 1)] + [(int(g.integers(n)), int(g.integers(sh.k))) for _ in range(4)]
+        assert plane_check_f16(sh, n, x, w, got, planes) <= 1e-3, sh
 
 
 # ------------------------------------------------------------------ fused epilogue / packed path

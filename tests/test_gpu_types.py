@@ -6,7 +6,7 @@ import torch
 
 import oracle
 from paper_2101_08458_amd import unit, workloads as wl
-from gpu_util import announce, dev, host, forced, f16_rel_err, fp8_rel_err, fp8_bound, same
+from gpu_util import announce, dev, host, forced, f16_rel_err, as_accurate_as_oracle, fp8_rel_err, fp8_bound, same
 
 pytestmark = pytest.mark.gpu
 
@@ -157,6 +157,7 @@ def test_matmul_bf16_parity(M, N, K):
             got = run_matmul("bf16", A, B)
         assert f16_rel_err(got, ref, K) <= 1e-3, (tile, split)
         assert np.all(np.abs(got - truth) <= 2 * K * 2.0 ** -24 * mag + 1e-30), (tile, split)
+        assert as_accurate_as_oracle(got, ref, truth), (tile, split)
 
 
 def test_matmul_bf16_exact_and_strided():
@@ -187,6 +188,7 @@ def test_conv_bf16_parity(case):
             got = run_conv("bf16", sh, n, x, w)
         assert f16_rel_err(got, ref, kred) <= 1e-3, (tile, split)
         assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), (tile, split)
+        assert as_accurate_as_oracle(got, ref, truth), (tile, split)
 
 
 def test_conv_bf16_direct_1x1():
@@ -200,6 +202,7 @@ def test_conv_bf16_direct_1x1():
                 got = run_conv("bf16", sh, n, x, w)
             assert f16_rel_err(got, ref, sh.c) <= 1e-3, tile
             assert np.all(np.abs(got - truth) <= 2 * sh.c * 2.0 ** -24 * mag + 1e-30), tile
+            assert as_accurate_as_oracle(got, ref, truth), tile
 
 
 def test_matmul_bf16_full_size_sampled():
@@ -211,6 +214,7 @@ def test_matmul_bf16_full_size_sampled():
     ref, truth, mag = oracle.matmul_bf16(np.ascontiguousarray(A[rows]), B)
     assert f16_rel_err(got[rows], ref, K) <= 1e-3
     assert np.all(np.abs(got[rows] - truth) <= 2 * K * 2.0 ** -24 * mag)
+    assert as_accurate_as_oracle(got[rows], ref, truth)
 
 
 # ------------------------------------------------------------------ fp8 (E4M3)
