@@ -235,6 +235,29 @@ def roof_us(macs, byts, dtype):
     return max(2.0 * macs / (PEAK[dtype] * 1e12), byts / (HBM_GBS * 1e9)) * 1e6
 
 
+def mfma_ceiling(torch, unit):
+    """What the matrix units sustain with nothing else running (unit_measure_mfma: the large tile's MFMA
+    sequence on register-resident operands), on constant and on uniformly random operands, for a launch
+    with as many MFMAs as the 4096^3 matmul and for a long one.  The clock is what the waves measured
+    in-kernel (core cycles per 100 MHz real-time tick)."""
+    res = []
+    counters = torch.zeros(unit.UNIT_MEASURE_COUNTERS_BYTES // 8, dtype=torch.int64, device="cuda:0")
+    for dtype, ut, kb in (("i8", unit.UNIT_I8, 32), ("f16", unit.UNIT_F16, 16)):
+        for rnd in (0, 1):
+            for steps in (4096 * (1 if dtype == "i8" else 2) // 128, 2048):
+                fn = lambda: unit.unit_measure_mfma(ut, steps, rnd, counters)
+                reps = 20 if steps < 1000 else 3
+                ms = event_ms(torch, fn, reps)
+                c = counters.cpu().numpy().reshape(-1, 4)
+                ops = 256 * 8 * steps * 32 * 2.0 * 32 * 32 * kb
+                res.append({"dtype": dtype, "operands": "random" if rnd else "constant", "steps": steps,
+                            "us": round(ms * 1e3, 1), "value": round(ops / (ms * 1e-3) / 1e12, 1),
+                            "unit": "TOPS" if dtype == "i8" else "TFLOPS",
+                            "frac_of_nominal_peak": round(ops / (ms * 1e-3) / 1e12 / PEAK[dtype], 4),
+                            "shader_clock_MHz": round(float(c[:, 0].sum()) / max(float(c[:, 1].sum()), 1.0) * 100.0)})
+    return res
+
+
 def tile_str(info):
     return (f"{info.block_m}x{info.block_n}x{info.block_k_bytes}B waves {info.waves_m}x{info.waves_n}x{info.waves_k} "
             f"mfma{info.mfma} split{info.split_k} wg{info.workgroups}")
@@ -595,6 +618,12 @@ def main():
                            "value": round(2.0 * 1.8136e9 * batch / (ms * 1e-3) / 1e12, 2), "unit": "TOPS"})
             del net
         out["others"] = others
+        # register-resident MFMA loop: the rate the matrix units sustain on this machine, on this kind of data
+        out["mfma_ceiling"] = mfma_ceiling(torch, unit)
+        ceil = {c["dtype"]: c["value"] for c in out["mfma_ceiling"] if c["operands"] == "random" and c["steps"] < 1000}
+        for e in others:
+            if e.get("workload", "").startswith("gemm 4096^3") and e["dtype"] in ceil:
+                e["frac_of_measured_mfma_ceiling"] = round(e["value"] / ceil[e["dtype"]], 4)
 
     if not args.no_cpu and not args.step_only:
         out["cpu_baseline"] = cpu_baseline(wl)

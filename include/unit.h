@@ -132,6 +132,27 @@ int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_inf
 int unit_select_conv2d_input(const unit_conv2d_desc *d, int dtype, int input_mode, unit_tile_info *out);
 
 /*
+ * Measurement aid: the rate the matrix units sustain on register-resident operands.  The paper judges
+ * its kernels by whether they keep the matrix units busy (Section VI-B); on this chip the clock of a
+ * busy matrix pipe is set by power management and depends on the operands' switching activity, so the
+ * nominal peak is not what a kernel on the benchmark's uniformly random operands can reach.  The call
+ * launches 256 workgroups of eight waves that execute `steps` steps of the large tile's MFMA sequence
+ * (32 MFMA 32x32 per wave and step = 256 x 256 x 128 bytes of reduction per workgroup and step, as in
+ * the 4096^3 matmul: 32 steps for int8, 64 for fp16) on operands held in registers: no LDS, no memory
+ * traffic.  random_operands != 0 fills them with uniformly random bytes (fp16 / bf16: random signs and
+ * mantissas); 0 with constants.  The caller times the launch (events on `stream`); work per launch =
+ * 256 * 8 * steps * 32 MFMAs * 32*32*K MACs each (K = 32 bytes of reduction: 32 for int8, 16 for
+ * 2-byte types).  `counters` (device, 8-byte aligned, UNIT_MEASURE_COUNTERS_BYTES) receives per wave four
+ * uint64: core clock cycles and 100 MHz real-time ticks from the wave's first to its last instruction,
+ * and its start and end tick; cycles / ticks * 100 MHz is the shader clock the wave saw.  (The two waves
+ * of a SIMD do not share the pipe evenly: the older one runs at nearly the full rate first.)
+ * dtype: UNIT_I8, UNIT_F16 or UNIT_BF16.  Errors: UNIT_EINVAL, UNIT_EWORKSPACE, UNIT_EHIP.
+ */
+#define UNIT_MEASURE_COUNTERS_BYTES (256 * 8 * 4 * 8)
+int unit_measure_mfma(int dtype, int32_t steps, int32_t random_operands, void *counters, size_t counters_bytes,
+                      void *stream);
+
+/*
  * Test and tuning-sweep hook (the "enumerate and profile" loop of Section IV-C drives it; Section
  * VI-B's ablation is measured with it): every later call of this process uses compiled tile `tile`
  * (0 .. 9, see unit_tile_info of a query for what it is) instead of the selector's choice, and

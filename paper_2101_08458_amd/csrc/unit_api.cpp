@@ -628,6 +628,16 @@ int unit_debug_force_tile(int32_t tile, int32_t split_k)
     return UNIT_OK;
 }
 
+int unit_measure_mfma(int dtype, int32_t steps, int32_t random_operands, void *counters, size_t counters_bytes,
+                      void *stream)
+{
+    if (dtype < UNIT_I8 || dtype > UNIT_BF16 || steps <= 0 || !counters) return UNIT_EINVAL;
+    if (counters_bytes < (size_t)UNIT_MEASURE_COUNTERS_BYTES) return UNIT_EWORKSPACE;
+    if (reinterpret_cast<uintptr_t>(counters) & 7) return UNIT_EINVAL;
+    UNIT_HIP(launch_mfma_ceiling(dtype, steps, random_operands ? 1 : 0, counters, static_cast<hipStream_t>(stream)));
+    return UNIT_OK;
+}
+
 int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_info *out)
 {
     MatmulGeom g;

@@ -51,6 +51,9 @@ hipError_t launch_pad_rows(const void *src, long ld_bytes, int rows, int row_byt
 // out[r] = 128 * sum of the signed bytes of row r (rows 16-byte aligned, chunks*16 bytes long)
 hipError_t launch_rowsum128_i8(const void *m, long ld, int rows, int chunks, int32_t *out, hipStream_t st);
 
+// register-resident MFMA loop (measurement aid); out: 256 * 8 waves * 4 counters of 8 bytes
+hipError_t launch_mfma_ceiling(int dtype, int steps, int random_operands, void *out, hipStream_t st);
+
 struct ReduceArgs {
     const void *partials;  int nsplit;  long split_stride;      // elements
     int dtype;

@@ -77,7 +77,7 @@ EXPORTS = [
     "unit_conv3d_out_dims", "unit_conv3d_workspace", "unit_conv3d_i8", "unit_conv3d_f16",
     "unit_conv2d_bf16", "unit_matmul_bf16", "unit_conv2d_u8i8", "unit_matmul_u8i8",
     "unit_conv2d_fp8", "unit_matmul_fp8",
-    "unit_conv2d_input_mode", "unit_debug_force_tile",
+    "unit_conv2d_input_mode", "unit_debug_force_tile", "unit_measure_mfma",
     "unit_inspect", "unit_describe_mfma", "unit_describe_conv2d", "unit_describe_matmul",
 ]
 
@@ -140,6 +140,7 @@ def load():
         "unit_matmul_u8i8": (ctypes.c_int, [i32, i32, i32, vp, i64, vp, i64, vp, i64, vp, sz, vp]),
         "unit_conv2d_input_mode": (ctypes.c_int, [dp, ctypes.c_int, vp]),
         "unit_debug_force_tile": (ctypes.c_int, [i32, i32]),
+        "unit_measure_mfma": (ctypes.c_int, [ctypes.c_int, i32, i32, vp, sz, vp]),
         "unit_inspect": (ctypes.c_int, [ctypes.c_char_p, ctypes.c_char_p, ctypes.POINTER(unit_inspect_result)]),
         "unit_describe_mfma": (ctypes.c_int, [ctypes.c_int, i32, ctypes.c_char_p, sz]),
         "unit_describe_conv2d": (ctypes.c_int, [dp, ctypes.c_int, ctypes.c_char_p, sz]),
@@ -383,6 +384,15 @@ def unit_conv2d_input_mode(d, dtype, x):
     if rc < 0:
         _check(rc, "unit_conv2d_input_mode")
     return rc
+
+
+UNIT_MEASURE_COUNTERS_BYTES = 256 * 8 * 4 * 8
+
+
+def unit_measure_mfma(dtype, steps, random_operands, counters, stream=None):
+    cp, cb = _ws(counters)
+    _check(load().unit_measure_mfma(dtype, int(steps), int(bool(random_operands)), cp, cb, _stream(stream)),
+           "unit_measure_mfma")
 
 
 def unit_debug_force_tile(tile, split_k):
