@@ -259,8 +259,9 @@ def mfma_ceiling(torch, unit):
 
 
 def tile_str(info):
+    tail = f" + tail 256x{info.tail_block_n} wg{info.tail_workgroups}" if info.tail_block_n else ""
     return (f"{info.block_m}x{info.block_n}x{info.block_k_bytes}B waves {info.waves_m}x{info.waves_n}x{info.waves_k} "
-            f"mfma{info.mfma} split{info.split_k} wg{info.workgroups}")
+            f"mfma{info.mfma} split{info.split_k} wg{info.workgroups}{tail}")
 
 
 def mfma_roofline(dtype, macs, ms, traffic=None):

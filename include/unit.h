@@ -96,7 +96,13 @@ typedef struct unit_tile_info {
     int32_t waves_m, waves_n, waves_k;  /* wave grid inside the workgroup (waves_k = in-group split) */
     int32_t mfma;               /* 32 or 16: MFMA tile edge                                        */
     int32_t split_k;            /* number of workgroups sharing one output tile (grid split)       */
-    int32_t workgroups;         /* total launched                                                  */
+    int32_t workgroups;         /* launched with this tile                                         */
+    /* A large problem whose count of 256 x 256 tiles would leave the last round of workgroups partly
+     * empty runs as two launches: whole rounds of the tile above over the first columns, then the
+     * remaining columns with a narrower tile (256 x tail_block_n) that fits them into one round.   */
+    int32_t tail_block_n;       /* 0: one launch                                                   */
+    int32_t tail_workgroups;
+    int32_t tail_first_col;     /* first output column (pixel index / matmul n) of the second launch */
 } unit_tile_info;
 
 int         unit_version(void);

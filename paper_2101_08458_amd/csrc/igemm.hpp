@@ -94,6 +94,9 @@ struct IgemmArgs {
     // prologue; inserting these three in front of dv_tiles_n, or sorting all fields by use into 64-byte lines, cost
     // 3-4 % of the batch-1 step each time it was tried)
     DivU dv_cb, dv_s, dv_r;                         // CB, S, R (the per-lane tap walk of the gather)
+    // column range this launch tiles: [col_base, col_limit) of the cols columns (one launch: 0 and cols; a problem
+    // whose tile count leaves the last round of workgroups mostly empty is launched as two ranges with two tile shapes)
+    int col_base, col_limit;
 };
 
 // One element of the requantise rule.  v_cvt_f32_i32 and v_rndne_f32 both round to
@@ -285,7 +288,11 @@ struct IgemmCfg {
         RING_BYTES   = NST * STAGE_BYTES + EDGE_BYTES,
         REDUCE_BYTES = (WGK > 1) ? WGK * BM * BN * 4 : 0,
         SMEM_BYTES   = (RING_BYTES > REDUCE_BYTES) ? RING_BYTES : REDUCE_BYTES,
-        FITS  = (SMEM_BYTES <= 160 * 1024) && ((NST - 1) * LPT <= 63),   // LDS capacity, vmcnt range
+        // direct NCHW reads: a wave-level DMA instruction must cover whole channel rows of the B tile
+        ESZ   = (DT == DT_F16 || DT == DT_BF16) ? 2 : 1,
+        DIRECT = (BSRC == BSRC_NCHW || BSRC == BSRC_NCHWS || BSRC == BSRC_NCHWE) ? 1 : 0,
+        ROWS_OK = !DIRECT || ((BN * ESZ / 16) <= 64 && 64 % (BN * ESZ / 16) == 0),
+        FITS  = (SMEM_BYTES <= 160 * 1024) && ((NST - 1) * LPT <= 63) && ROWS_OK,   // LDS capacity, vmcnt range, row rule
     };
     static_assert(BM % (WGM * MF) == 0 && BN % (WGN * MF) == 0, "wave tiles must be whole MFMA tiles");
     static_assert(NKSUB % WGK == 0 && NKSUB >= WGK, "in-group split must divide the sub-steps");
@@ -342,7 +349,7 @@ igemm_kernel(const IgemmArgs g)
     constexpr bool NCHW1 = (BSRC == BSRC_NCHW || BSRC == BSRC_NCHWE);     // 1x1 direct read, without / with edge patch
     constexpr bool EDGE1 = (BSRC == BSRC_NCHWE);
     const bool per_img = (NCHW1 || BSRC == BSRC_NCHWS) && g.per_img;
-    const int tiles_n = per_img ? tiles_img * g.nimg : (g.cols + BN - 1) / BN;
+    const int tiles_n = per_img ? tiles_img * g.nimg : (g.col_limit - g.col_base + BN - 1) / BN;
     const int ntiles  = tiles_m * tiles_n;
     int bid = blockIdx.x;
     {   // XCD x = bid % 8 receives workgroups x, x + 8, ...: they become one contiguous run of the tile order
@@ -365,7 +372,7 @@ igemm_kernel(const IgemmArgs g)
         tm = band_m0 + in_band - tn * band_rows;
     }
     const int row0 = tm * BM;
-    int col0 = tn * BN, col_end = g.cols;           // first column of the tile, end of its column range
+    int col0 = g.col_base + tn * BN, col_end = g.col_limit;   // first column of the tile, end of its column range
     if (per_img) {
         const int img = divu(tn, g.dv_tiles_img);
         col0 = img * g.PQ + (tn - img * tiles_img) * BN;

@@ -40,6 +40,10 @@ bool tile_fits(int tile, int dtype, int bsrc)
     const long edge = (bsrc == BSRC_NCHWS || bsrc == BSRC_NCHW) ? 1024 : 0;   // (NCHW may become NCHWE)
     const long ring = (long)c.nst * (c.bm + c.bn) * c.bkb + edge;
     const long red = c.wgk > 1 ? (long)c.wgk * c.bm * c.bn * 4 : 0;
+    const bool direct = bsrc == BSRC_NCHW || bsrc == BSRC_NCHWS || bsrc == BSRC_NCHWE;
+    const int es = (dtype == 1 || dtype == 2) ? 2 : 1;              // fp16 / bf16: two-byte elements
+    const int cpr = c.bn * es / 16;                                  // 16-byte chunks per channel row of the B tile
+    if (direct && (cpr > 64 || 64 % cpr != 0)) return false;
     return (ring > red ? ring : red) <= 160 * 1024 && (c.nst - 1) * lpt <= 63;
 }
 
@@ -123,6 +127,50 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
     ch.ksteps_per_split = per;
     ch.workgroups = (int)(nt * split);
     return ch;
+}
+
+// Relative cost of one tile of the narrower relatives of the 256 x 256 tile, per unit of reduction, in units of the
+// large tile's own cost (measured on matmuls that fill exactly one round of 256 workgroups with each shape).
+static const struct { int tile, bn; double cost; } g_tail_tiles[] = {{10, 192, 0.79}, {11, 128, 0.60}};
+
+RangePlan plan_ranges(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split, int cb, bool allow_ranges)
+{
+    RangePlan p;
+    p.n = 1;
+    p.col_begin[0] = 0;  p.col_end[0] = cols;
+    p.col_begin[1] = p.col_end[1] = cols;
+    p.choice[0] = select_tile(rows, cols, kchunks, dtype, bsrc, allow_split, cb);
+    p.choice[1] = p.choice[0];
+    if (!allow_ranges || g_force_tile.load(std::memory_order_relaxed) >= 0) return p;
+    if (p.choice[0].tile != 8 || p.choice[0].split_k != 1) return p;
+    const int CUS = 256, BN = 256;
+    const long tm = cdiv(rows, 256), tn = cdiv(cols, BN), nt = tm * tn;
+    if (nt <= CUS || nt % CUS == 0) return p;
+    // main range: the column tiles that make whole rounds of workgroups; tail: the rest
+    const long n1 = (nt / CUS) * CUS / tm;
+    if (n1 <= 0 || n1 >= tn) return p;
+    const long c1 = n1 * BN, tail_cols = cols - c1;
+    const double plain = (double)cdiv(tm * cdiv(tail_cols, BN), CUS);      // rounds the tail takes as large tiles
+    int best = -1;
+    double best_cost = 0.92 * plain;                                       // a second launch must pay for itself
+    for (unsigned i = 0; i < sizeof g_tail_tiles / sizeof g_tail_tiles[0]; ++i) {
+        const long t = tm * cdiv(tail_cols, g_tail_tiles[i].bn);
+        if (t <= CUS && g_tail_tiles[i].cost < best_cost && tile_fits(g_tail_tiles[i].tile, dtype, bsrc)) {
+            best = (int)i;
+            best_cost = g_tail_tiles[i].cost;
+        }
+    }
+    if (best < 0) return p;
+    const TileCfg &c = g_tiles[g_tail_tiles[best].tile];
+    p.n = 2;
+    p.col_end[0] = (int)c1;
+    p.choice[0].workgroups = (int)(n1 * tm);
+    p.col_begin[1] = (int)c1;  p.col_end[1] = cols;
+    p.choice[1].tile = g_tail_tiles[best].tile;
+    p.choice[1].split_k = 1;
+    p.choice[1].ksteps_per_split = cdiv(kchunks, c.bkb / 16);
+    p.choice[1].workgroups = (int)(tm * cdiv(tail_cols, c.bn));
+    return p;
 }
 
 }  // namespace unit

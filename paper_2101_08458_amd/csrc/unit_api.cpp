@@ -122,12 +122,17 @@ int conv_geom(const ConvND *d, int dtype, ConvGeom *g)
     return UNIT_OK;
 }
 
-void fill_tile_info(const TileChoice &ch, int dtype, unit_tile_info *out)
+void fill_tile_info(const RangePlan &p, int dtype, unit_tile_info *out)
 {
-    const TileCfg &c = (dtype == UNIT_FP8 ? g_tiles_fp8 : g_tiles)[ch.tile];
+    const TileChoice &ch = p.choice[0];
+    const TileCfg *tiles = dtype == UNIT_FP8 ? g_tiles_fp8 : g_tiles;
+    const TileCfg &c = tiles[ch.tile];
     out->block_m = c.bm;  out->block_n = c.bn;  out->block_k_bytes = c.bkb;
     out->waves_m = c.wgm; out->waves_n = c.wgn; out->waves_k = c.wgk;
     out->mfma = c.mf;     out->split_k = ch.split_k;  out->workgroups = ch.workgroups;
+    out->tail_block_n = p.n > 1 ? tiles[p.choice[1].tile].bn : 0;
+    out->tail_workgroups = p.n > 1 ? p.choice[1].workgroups : 0;
+    out->tail_first_col = p.n > 1 ? p.col_begin[1] : 0;
 }
 
 // divisor + truncated reciprocal for the kernels' divisions (IgemmArgs::dv_*)
@@ -144,22 +149,18 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
               void *ws, size_t ws_bytes, hipStream_t st, bool allow_split = true)
 {
     const bool conv = bsrc != BSRC_PLAIN;
-    TileChoice ch = select_tile(a.rows, a.cols, a.kchunks, dtype, bsrc, allow_split, conv ? a.CB : 0);
-    if (!tile_fits(ch.tile, dtype, bsrc)) return UNIT_ENOTSUP;     // (only a forced tile can fail this)
-    a.ksteps_per_split = ch.ksteps_per_split;
+    // (column ranges need tiles that may start anywhere in an image: not with per-image tiling)
+    const RangePlan plan = plan_ranges(a.rows, a.cols, a.kchunks, dtype, bsrc, allow_split, conv ? a.CB : 0,
+                                       !(conv && a.per_img));
+    const TileChoice ch = plan.choice[0];
+    for (int r = 0; r < plan.n; ++r)
+        if (!tile_fits(plan.choice[r].tile, dtype, bsrc)) return UNIT_ENOTSUP;     // (only a forced tile can fail this)
     // Tile order inside an XCD's run: while the whole B operand is small (<= 8 MiB: every XCD can afford its own
     // copy in L2) a run walks the column tiles of one row tile, so A (the weights) is fetched once in total; large
     // problems walk bands of 8 row tiles, which bounds the re-fetching of both operands.
     a.row_runs = ((long)a.cols * a.kchunks * 16 <= (8L << 20)) ? 1 : 0;
-    {   // divisors of the index arithmetic (the tile coordinates depend on the tile chosen here)
-        const TileCfg &t = g_tiles[ch.tile];
-        const long pq = a.PQ > 0 ? a.PQ : 1;
-        const long tiles_img = (pq + t.bn - 1) / t.bn;
-        a.nimg = (int)(a.cols / pq);
-        const long tiles_n = (conv && a.per_img) ? tiles_img * a.nimg : ((long)a.cols + t.bn - 1) / t.bn;
-        a.dv_tiles_n = make_div(tiles_n);
-        a.dv_band = make_div(8 * tiles_n);
-        a.dv_tiles_img = make_div(tiles_img);
+    {   // divisors of the index arithmetic that do not depend on the tile
+        a.nimg = (int)(a.cols / (a.PQ > 0 ? a.PQ : 1));
         a.dv_pq = make_div(a.PQ);
         a.dv_ppq = make_div((long)a.P * a.Q);
         a.dv_q = make_div(a.Q);
@@ -169,11 +170,29 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
         a.dv_s = make_div(a.S);
         a.dv_r = make_div(a.R);
     }
+    // ... and the ones of a launch's tile coordinates
+    auto set_range = [&](IgemmArgs &x, int r) {
+        const TileCfg &t = g_tiles[plan.choice[r].tile];
+        const long pq = x.PQ > 0 ? x.PQ : 1;
+        const long tiles_img = (pq + t.bn - 1) / t.bn;
+        x.col_base = plan.col_begin[r];
+        x.col_limit = plan.col_end[r];
+        const long tiles_n = (conv && x.per_img) ? tiles_img * x.nimg
+                                                 : ((long)x.col_limit - x.col_base + t.bn - 1) / t.bn;
+        x.dv_tiles_n = make_div(tiles_n);
+        x.dv_band = make_div(8 * tiles_n);
+        x.dv_tiles_img = make_div(tiles_img);
+        x.ksteps_per_split = plan.choice[r].ksteps_per_split;
+    };
     if (ch.split_k == 1) {
         a.split_stride = 0;
-        UNIT_HIP(launch_igemm(dtype, bsrc, ch.tile, a, 1, st));
+        for (int r = 0; r < plan.n; ++r) {
+            set_range(a, r);
+            UNIT_HIP(launch_igemm(dtype, bsrc, plan.choice[r].tile, a, 1, st));
+        }
         return UNIT_OK;
     }
+    set_range(a, 0);                               // (a split reduction is always one range)
     const long slice = (out_elems + 3) & ~3L;     // 16-byte aligned slices for the reduce kernel
     size_t need = (size_t)ch.split_k * slice * 4;
     if (!ws || ws_bytes < need) return UNIT_EWORKSPACE;
@@ -593,7 +612,7 @@ int unit_select_conv2d(const unit_conv2d_desc *d, int dtype, unit_tile_info *out
     int rc = conv_geom(&nd, dtype, &g);
     if (rc != UNIT_OK) return rc;
     if (!out) return UNIT_EINVAL;
-    fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_GATHER, true, g.cp * elem_size(dtype) / 16), dtype, out);
+    fill_tile_info(plan_ranges(g.rows, (int)g.cols, g.kchunks, dtype, BSRC_GATHER, true, g.cp * elem_size(dtype) / 16, true), dtype, out);
     return UNIT_OK;
 }
 
@@ -605,7 +624,7 @@ int unit_select_conv2d_input(const unit_conv2d_desc *d, int dtype, int input_mod
     if (rc != UNIT_OK) return rc;
     if (!out || input_mode < UNIT_INPUT_PACKED || input_mode > UNIT_INPUT_DIRECT_SHIFTED) return UNIT_EINVAL;
     const int bsrc = input_mode == UNIT_INPUT_DIRECT ? BSRC_NCHW : input_mode == UNIT_INPUT_DIRECT_SHIFTED ? BSRC_NCHWS : BSRC_GATHER;
-    fill_tile_info(select_tile(g.rows, (int)g.cols, g.kchunks, dtype, bsrc, true, g.cp * elem_size(dtype) / 16), dtype, out);
+    fill_tile_info(plan_ranges(g.rows, (int)g.cols, g.kchunks, dtype, bsrc, true, g.cp * elem_size(dtype) / 16, true), dtype, out);
     return UNIT_OK;
 }
 
@@ -644,7 +663,7 @@ int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_inf
     int rc = matmul_geom(m, n, k, k, k, dtype, &g);
     if (rc != UNIT_OK) return rc;
     if (!out) return UNIT_EINVAL;
-    fill_tile_info(select_tile(m, n, g.kchunks, dtype, BSRC_PLAIN), dtype, out);
+    fill_tile_info(plan_ranges(m, n, g.kchunks, dtype, BSRC_PLAIN, true, 0, true), dtype, out);
     return UNIT_OK;
 }
 

@@ -17,7 +17,7 @@ struct TileCfg {
     int mf;                   // MFMA edge
     int nst;                  // LDS stages
 };
-enum { NUM_TILES = 10 };
+enum { NUM_TILES = 12 };
 extern const TileCfg g_tiles[NUM_TILES];
 extern const TileCfg g_tiles_fp8[NUM_TILES];   // same tiles, wave grids of the fp8 kernels
 
@@ -32,6 +32,15 @@ struct TileChoice {
 // bsrc: where the B operand comes from (BSRC_*); the tile depends on the shape only, the split also on bsrc
 // cb: 16-byte channel chunks per pixel (BSRC_NCHWS only: its steps must divide them), 0 = not applicable
 TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split = true, int cb = 0);
+// A problem as one or two column ranges, each with a tile shape of its own.  Large problems whose count of
+// 256 x 256 tiles leaves the last round of workgroups partly empty get their whole rounds as one launch and
+// the remaining columns as a second launch with a narrower tile that fits them into one round.
+struct RangePlan {
+    int n;                    // 1 or 2 launches
+    int col_begin[2], col_end[2];
+    TileChoice choice[2];
+};
+RangePlan plan_ranges(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split, int cb, bool allow_ranges);
 // test / sweep hook behind unit_debug_force_tile: tile and grid split every later select_tile returns (-1 = the rule)
 void force_tile(int tile, int split);
 // whether `tile` has a kernel for this public dtype and B source (LDS footprint, vmcnt range)

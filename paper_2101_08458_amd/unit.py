@@ -39,7 +39,7 @@ class unit_requant(ctypes.Structure):
 class unit_tile_info(ctypes.Structure):
     _fields_ = [(f, ctypes.c_int32) for f in
                 ("block_m", "block_n", "block_k_bytes", "waves_m", "waves_n", "waves_k",
-                 "mfma", "split_k", "workgroups")]
+                 "mfma", "split_k", "workgroups", "tail_block_n", "tail_workgroups", "tail_first_col")]
 
 
 UNIT_INSPECT_MAX, UNIT_INSPECT_NAME = 8, 16

@@ -127,6 +127,32 @@ def test_size_limits_and_wpacked_errors(lib):
     assert lib.unit_conv2d_wpacked_f16(ctypes.byref(d), fake, fake, None, None, 0, st) == unit.UNIT_EINVAL
 
 
+def test_column_range_plan(lib):
+    """Tile-count-aware selection: whole rounds of 256 x 256 tiles, then a narrower tile for the remaining columns
+    when those would otherwise leave a round of workgroups mostly empty."""
+    q = lambda m, n, k=4096: unit.unit_select_matmul(m, n, k, unit.UNIT_I8)
+    i = q(4096, 4096)
+    assert (i.block_n, i.workgroups, i.tail_block_n) == (256, 256, 0)                  # exactly one round
+    assert q(8192, 8192).tail_block_n == 0                                             # four whole rounds
+    i = q(4096, 6144)                                                                  # 1.5 rounds: tail of 128 tiles -> 256 x 128
+    assert (i.workgroups, i.tail_block_n, i.tail_workgroups, i.tail_first_col) == (256, 128, 256, 4096)
+    i = q(4096, 4096 + 34 * 256)                                                       # 800 tiles = 3 rounds + 32: those as 64 tiles of 256 x 128
+    assert (i.workgroups, i.tail_block_n, i.tail_workgroups, i.tail_first_col) == (768, 128, 64, 48 * 256)
+    assert q(2048, 40000).tail_block_n == 0                                            # last round 91 % full: left alone
+    assert q(4096, 4096, 256).tail_block_n == 0                                        # short reductions do not use the large tile
+    sh = wl.LARGE_CONV                                                                 # the benchmark's large conv: 392 tiles
+    d = unit.conv_desc(32, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
+    for dt in (unit.UNIT_I8, unit.UNIT_F16, unit.UNIT_FP8):
+        i = unit.unit_select_conv2d(d, dt)
+        assert (i.block_m, i.block_n, i.workgroups) == (256, 256, 256)
+        assert (i.tail_block_n, i.tail_workgroups, i.tail_first_col) == (192, 182, 65536)
+    unit.unit_debug_force_tile(8, -1)                                                  # a forced tile is one launch
+    try:
+        assert unit.unit_select_conv2d(d, unit.UNIT_I8).tail_block_n == 0
+    finally:
+        unit.unit_debug_force_tile(-1, -1)
+
+
 def test_input_mode_decisions_are_host_logic(lib):
     """Which layers skip pack_act is decided on the host from the shape and the alignment of
     `x` alone (nothing is dereferenced), so the rule can be checked without a GPU."""
@@ -193,7 +219,15 @@ def test_debug_force_tile_overrides_and_restores_the_rule(lib):
         assert lib.unit_conv2d_input_mode(ctypes.byref(d64), unit.UNIT_I8, x) == unit.UNIT_INPUT_DIRECT_SHIFTED
         unit.unit_debug_force_tile(1, -1)
         assert lib.unit_conv2d_input_mode(ctypes.byref(d64), unit.UNIT_I8, x) == unit.UNIT_INPUT_PACKED
-        assert lib.unit_debug_force_tile(10, 1) == unit.UNIT_EINVAL
+        # the 256 x 192 tile has no direct-read kernels (a DMA instruction must cover whole channel rows of the
+        # column tile): forcing it makes a direct-capable layer pack first
+        unit.unit_debug_force_tile(10, -1)
+        d1 = unit.conv_desc(1, 256, 56, 56, 64, 1, 1, 1, 0)
+        assert lib.unit_conv2d_input_mode(ctypes.byref(d1), unit.UNIT_I8, x) == unit.UNIT_INPUT_PACKED
+        assert lib.unit_conv2d_input_mode(ctypes.byref(d), unit.UNIT_I8, x) == unit.UNIT_INPUT_PACKED
+        unit.unit_debug_force_tile(-1, -1)
+        assert lib.unit_conv2d_input_mode(ctypes.byref(d1), unit.UNIT_I8, x) == unit.UNIT_INPUT_DIRECT
+        assert lib.unit_debug_force_tile(99, 1) == unit.UNIT_EINVAL
     finally:
         os.environ.pop("UNIT_TILE", None)
         os.environ.pop("UNIT_SPLITK", None)

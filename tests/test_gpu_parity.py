@@ -13,7 +13,7 @@ from gpu_util import announce, dev, host, forced, f16_rel_err, as_accurate_as_or
 
 pytestmark = pytest.mark.gpu
 
-ALL_TILES = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9]
+ALL_TILES = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11]
 
 
 def ws_bytes(nbytes):
@@ -622,3 +622,61 @@ def test_matmul_i8_longest_exact_reduction():
     got = run_matmul_i8(A, B)
     assert same(got, A.astype(np.int64) @ B.astype(np.int64).T, "longest reduction")
     assert got[0, 0] == K * 16384 and got.max() < 2 ** 31
+
+
+# ------------------------------------------------------------------ two column ranges (whole rounds + narrower tail)
+
+def test_matmul_two_column_ranges():
+    """A problem whose 256 x 256 tiles leave a last round of workgroups mostly empty runs as two launches with two
+    tile shapes (the selector query reports the second one); rows and columns on both sides of the seam, and the
+    tail's own ragged end, against the oracle."""
+    M, N, K = 4096, 4352 + 37, 512
+    info = unit.unit_select_matmul(M, N, K, unit.UNIT_I8)
+    assert (info.block_m, info.block_n) == (256, 256) and info.tail_block_n in (128, 192) and info.tail_first_col == 4096
+    g = wl.rng(27)
+    A, B = wl.int8_weights(g, (M, K)), wl.int8_weights(g, (N, K))
+    announce("matmul_i8 two ranges", M, N, K, "tail", info.tail_block_n)
+    got = run_matmul_i8(A, B)
+    rows = np.unique(np.concatenate([[0, 255, 256, 4095], g.integers(0, M, 8)]))
+    cols = np.unique(np.concatenate([[0, 4095, 4096, 4097, 4223, 4224, 4351, 4352, N - 1], g.integers(4000, N, 8)]))
+    assert same(got[rows], oracle.matmul_i8(np.ascontiguousarray(A[rows]), B))
+    assert same(got[:, cols], oracle.matmul_i8(A, np.ascontiguousarray(B[cols])))
+    colsum = B.astype(np.int64).sum(axis=0)
+    assert same(got.astype(np.int64).sum(axis=1), A.astype(np.int64) @ colsum)
+    Ah, Bh = wl.f16_activations(g, (M, K)), wl.f16_weights(g, (N, K), K)
+    announce("matmul_f16 two ranges")
+    goth = run_matmul_f16(Ah, Bh)
+    ref = oracle.matmul_f16(Ah, np.ascontiguousarray(Bh[cols]))
+    truth, mag = oracle.matmul_f16_f64(Ah, np.ascontiguousarray(Bh[cols]))
+    assert f16_rel_err(goth[:, cols], ref, K) <= 1e-3
+    assert np.all(np.abs(goth[:, cols] - truth) <= 2 * K * 2.0 ** -24 * mag + 1e-30)
+    assert as_accurate_as_oracle(goth[:, cols], ref, truth)
+
+
+def test_large_conv_two_column_ranges():
+    """The compute-bound conv the benchmark times (N=32, C=K=256, 56x56, 3x3): 392 tiles of 256 x 256 = one full
+    round plus a tail that runs on a narrower tile.  Whole output planes of the images around the seam (output
+    column 65536 lies in image 20), the first and the last image."""
+    sh, n = wl.LARGE_CONV, 32
+    d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
+    info = unit.unit_select_conv2d(d, unit.UNIT_I8)
+    assert info.tail_block_n > 0 and info.tail_first_col == 65536 and info.workgroups == 256
+    x, w = wl.conv_inputs_i8(sh, n, 9, 0)
+    announce("large conv i8, two ranges: tail", info.tail_block_n, info.tail_workgroups)
+    got = run_conv_i8(sh, n, x, w)
+    g = wl.rng(28)
+    planes = [(0, 0), (20, 255), (20, 17), (21, 100), (31, 255), (19, 3)] + [(int(g.integers(n)), int(g.integers(sh.k))) for _ in range(6)]
+    for ni, k in planes:
+        ref = oracle.conv2d_i8(np.ascontiguousarray(x[ni:ni + 1]), np.ascontiguousarray(w[k:k + 1]), (1, 1), (1, 1))
+        assert same(got[ni, k], ref[0, 0], f"image {ni} channel {k}")
+    # a property that holds at any size: summed over output channels, the conv equals the conv with the summed filter
+    wsum = w.astype(np.int64).sum(axis=0, keepdims=True)
+    for ni in (20, 27):
+        xs = x[ni:ni + 1].astype(np.float64)
+        import torch.nn.functional as F
+        exp = F.conv2d(torch.from_numpy(xs), torch.from_numpy(wsum.astype(np.float64)), padding=1).numpy()[0, 0]
+        assert np.array_equal(got[ni].astype(np.int64).sum(axis=0), exp.astype(np.int64)), ni
+    xh, wh = wl.conv_inputs_f16(sh, n, 9, 0)
+    announce("large conv f16, two ranges")
+    goth = run_conv_f16(sh, n, xh, wh)
+    assert plane_check_f16(sh, n, xh, wh, goth, planes[:8]) <= 1e-3
