@@ -94,7 +94,9 @@ typedef struct unit_tile_info {
                                    block_n output columns (pixels / matmul n)                      */
     int32_t block_k_bytes;      /* reduction bytes staged per main-loop step                       */
     int32_t waves_m, waves_n, waves_k;  /* wave grid inside the workgroup (waves_k = in-group split) */
-    int32_t mfma;               /* 32 or 16: MFMA tile edge                                        */
+    int32_t mfma;               /* 32 or 16: MFMA tile edge; 0: a matmul of at most 4 rows (int8, fp16)
+                                   runs on the vector ALU's dot-product instructions instead, one
+                                   wave per output column, block_n columns per workgroup            */
     int32_t split_k;            /* number of workgroups sharing one output tile (grid split)       */
     int32_t workgroups;         /* launched with this tile                                         */
     /* A large problem whose count of 256 x 256 tiles would leave the last round of workgroups partly

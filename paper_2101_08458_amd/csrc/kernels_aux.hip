@@ -421,6 +421,96 @@ hipError_t launch_rowsum128_i8(const void *m, long ld, int rows, int chunks, int
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------------ matmul with very few rows
+// C[r][col] = sum_k A[r][k] * B[col][k] for a handful of rows (the fully connected layer of batch-1 inference: the paper's
+// matmul with one row, Section II-A).  The matrix units would run 15/16 empty and, worse, a 16 x 64 tile leaves
+// only n / 64 workgroups to stream B, the one operand of any size.  Here one wave owns one output column: it reads
+// that column's reduction row of B once, 16 bytes per lane and load, multiplies each chunk with the same chunk of
+// every row of A by the dot-product instructions of the vector ALU (v_dot4_i32_i8: four byte products added into an
+// int32, exact; v_dot2_f32_f16: two half products added into an fp32) and adds the lanes' sums with a butterfly.
+// n / 4 workgroups keep every compute unit streaming.  Rows of both operands start 16-byte aligned and are
+// `kchunks` 16-byte chunks long (the caller pads otherwise).  MR = compiled number of rows (rows past m repeat row 0
+// and are not stored).
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
+
+template <int DT, int MR>
+__global__ void __launch_bounds__(256)
+gemv_kernel(const uint8_t *__restrict__ A, long lda, const uint8_t *__restrict__ B, long ldb,
+            int m, int n, int kchunks, void *__restrict__ C, long ldc)
+{
+    typedef typename Mma<DT, 32>::elem_t elem_t;
+    const int col = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
+    if (col >= n) return;
+    const v4i *b = reinterpret_cast<const v4i *>(B + (long)col * ldb);
+    const v4i *a[MR];
+#pragma unroll
+    for (int r = 0; r < MR; ++r) a[r] = reinterpret_cast<const v4i *>(A + (long)(r < m ? r : 0) * lda);
+    elem_t acc[MR];
+#pragma unroll
+    for (int r = 0; r < MR; ++r) acc[r] = 0;
+    auto mac = [&](const v4i &bv, const v4i &av, elem_t &c) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            const int ai = av[d], bi = bv[d];       // (values, not vector-element lvalues: those do not bit_cast element-wise)
+            if constexpr (DT == DT_I8) {
+                c = __builtin_amdgcn_sdot4(ai, bi, c, false);
+            } else {
+                c = __builtin_amdgcn_fdot2(__builtin_bit_cast(v2h, ai), __builtin_bit_cast(v2h, bi), c, false);
+            }
+        }
+    };
+    // two chunks per lane and trip: all loads of a trip are issued before the first multiply
+    int c = lane;
+    for (; c + 64 < kchunks; c += 128) {
+        const v4i b0 = b[c], b1 = b[c + 64];
+        v4i a0[MR], a1[MR];
+#pragma unroll
+        for (int r = 0; r < MR; ++r) { a0[r] = a[r][c];  a1[r] = a[r][c + 64]; }
+#pragma unroll
+        for (int r = 0; r < MR; ++r) { mac(b0, a0[r], acc[r]);  mac(b1, a1[r], acc[r]); }
+    }
+    if (c < kchunks) {
+        const v4i b0 = b[c];
+#pragma unroll
+        for (int r = 0; r < MR; ++r) mac(b0, a[r][c], acc[r]);
+    }
+#pragma unroll
+    for (int r = 0; r < MR; ++r) {
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc[r] += __shfl_xor(acc[r], off, 64);
+    }
+    if (lane == 0) {
+        elem_t *out = static_cast<elem_t *>(C);
+#pragma unroll
+        for (int r = 0; r < MR; ++r)
+            if (r < m) out[(long)r * ldc + col] = acc[r];
+    }
+}
+
+template <int DT>
+static hipError_t launch_gemv_dt(const void *A, long lda, const void *B, long ldb, int m, int n, int kchunks,
+                                 void *C, long ldc, hipStream_t st)
+{
+    const dim3 grid((n + 3) / 4), block(256);
+    const uint8_t *a = static_cast<const uint8_t *>(A), *b = static_cast<const uint8_t *>(B);
+    if (m == 1)      hipLaunchKernelGGL((gemv_kernel<DT, 1>), grid, block, 0, st, a, lda, b, ldb, m, n, kchunks, C, ldc);
+    else if (m == 2) hipLaunchKernelGGL((gemv_kernel<DT, 2>), grid, block, 0, st, a, lda, b, ldb, m, n, kchunks, C, ldc);
+    else if (m <= 4) hipLaunchKernelGGL((gemv_kernel<DT, 4>), grid, block, 0, st, a, lda, b, ldb, m, n, kchunks, C, ldc);
+    else             hipLaunchKernelGGL((gemv_kernel<DT, 8>), grid, block, 0, st, a, lda, b, ldb, m, n, kchunks, C, ldc);
+    return hipGetLastError();
+}
+
+// dtype: DT_I8 or DT_F16; m <= 8 (the API uses it up to GEMV_MAX_ROWS); lda, ldb in bytes
+hipError_t launch_gemv(int dtype, const void *A, long lda, const void *B, long ldb, int m, int n, int kchunks,
+                       void *C, long ldc, hipStream_t st)
+{
+    if (m < 1 || m > 8) return hipErrorInvalidValue;
+    if (dtype == DT_I8) return launch_gemv_dt<DT_I8>(A, lda, B, ldb, m, n, kchunks, C, ldc, st);
+    if (dtype == DT_F16) return launch_gemv_dt<DT_F16>(A, lda, B, ldb, m, n, kchunks, C, ldc, st);
+    return hipErrorInvalidValue;
+}
+
 // ------------------------------------------------------------------ int8 network glue
 // max-pool on packed int8: one thread per (n, p, q, 16-channel chunk).  With a compile-time
 // window (WIN > 0) all window loads are issued at once through a buffer descriptor (taps in the

@@ -29,6 +29,8 @@ void force_tile(int tile, int split)
     g_force_split.store(split, std::memory_order_relaxed);
 }
 
+bool tile_is_forced() { return g_force_tile.load(std::memory_order_relaxed) >= 0; }
+
 // Whether tile `t` has a kernel for this B source and operand type: the LDS footprint and the
 // vmcnt range of IgemmCfg::FITS, recomputed on the host.
 bool tile_fits(int tile, int dtype, int bsrc)

@@ -441,6 +441,7 @@ int conv_wpacked(const ConvND *d, int dtype, const void *x, const void *wp,
 struct MatmulGeom {
     int kpad_bytes, kchunks;
     bool pad_a, pad_b;
+    bool gemv;                 // at most GEMV_MAX_ROWS rows: the dot-product kernel instead of the matrix units
     size_t a_bytes, b_bytes, fix_bytes, split_bytes;
 };
 
@@ -460,8 +461,9 @@ int matmul_geom(int m, int n, int k, long lda, long ldb, int dtype, MatmulGeom *
     g->a_bytes = g->pad_a ? align256((size_t)m * g->kpad_bytes) : 0;
     g->b_bytes = g->pad_b ? align256((size_t)n * g->kpad_bytes) : 0;
     g->fix_bytes = dtype == UNIT_U8I8 ? align256((size_t)n * 4) : 0;
+    g->gemv = m <= GEMV_MAX_ROWS && (dtype == UNIT_I8 || dtype == UNIT_F16) && !tile_is_forced();
     TileChoice ch = select_tile(m, n, g->kchunks, dtype, BSRC_PLAIN);
-    g->split_bytes = ch.split_k > 1 ? align256((size_t)ch.split_k * (((long)m * n + 3) & ~3L) * 4) : 0;
+    g->split_bytes = (ch.split_k > 1 && !g->gemv) ? align256((size_t)ch.split_k * (((long)m * n + 3) & ~3L) * 4) : 0;
     return UNIT_OK;
 }
 
@@ -491,6 +493,10 @@ int matmul_any(int dtype, int m, int n, int k, const void *A, long lda, const vo
     if (g.pad_b) {
         UNIT_HIP(launch_pad_rows(B, ldb_b, n, k * es, wsp, g.kpad_bytes, st));
         Bp = wsp;  ldb_b = g.kpad_bytes;  wsp += g.b_bytes;
+    }
+    if (g.gemv) {
+        UNIT_HIP(launch_gemv(dtype == UNIT_I8 ? DT_I8 : DT_F16, Ap, lda_b, Bp, ldb_b, m, n, g.kchunks, C, ldc, st));
+        return UNIT_OK;
     }
     IgemmArgs a;
     std::memset(&a, 0, sizeof a);
@@ -664,6 +670,12 @@ int unit_select_matmul(int32_t m, int32_t n, int32_t k, int dtype, unit_tile_inf
     if (rc != UNIT_OK) return rc;
     if (!out) return UNIT_EINVAL;
     fill_tile_info(plan_ranges(m, n, g.kchunks, dtype, BSRC_PLAIN, true, 0, true), dtype, out);
+    if (g.gemv) {               // one wave per output column on the vector ALU's dot-product instructions
+        out->block_m = m == 1 ? 1 : m == 2 ? 2 : m <= 4 ? 4 : 8;  out->block_n = 4;  out->block_k_bytes = 2048;
+        out->waves_m = 1;  out->waves_n = 4;  out->waves_k = 1;  out->mfma = 0;
+        out->split_k = 1;  out->workgroups = (n + 3) / 4;
+        out->tail_block_n = out->tail_workgroups = out->tail_first_col = 0;
+    }
     return UNIT_OK;
 }
 

@@ -43,6 +43,7 @@ struct RangePlan {
 RangePlan plan_ranges(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split, int cb, bool allow_ranges);
 // test / sweep hook behind unit_debug_force_tile: tile and grid split every later select_tile returns (-1 = the rule)
 void force_tile(int tile, int split);
+bool tile_is_forced();
 // whether `tile` has a kernel for this public dtype and B source (LDS footprint, vmcnt range)
 bool tile_fits(int tile, int dtype, int bsrc);
 
@@ -62,6 +63,11 @@ hipError_t launch_rowsum128_i8(const void *m, long ld, int rows, int chunks, int
 
 // register-resident MFMA loop (measurement aid); out: 256 * 8 waves * 4 counters of 8 bytes
 hipError_t launch_mfma_ceiling(int dtype, int steps, int random_operands, void *out, hipStream_t st);
+
+// matmul with at most UNIT_GEMV_MAX_ROWS rows on the vector ALU's dot-product instructions (DT_I8 / DT_F16)
+enum { GEMV_MAX_ROWS = 4 };      // (measured: from 8 rows on the 16 x 64 MFMA tile is as fast or faster)
+hipError_t launch_gemv(int dtype, const void *A, long lda, const void *B, long ldb, int m, int n, int kchunks,
+                       void *C, long ldc, hipStream_t st);
 
 struct ReduceArgs {
     const void *partials;  int nsplit;  long split_stride;      // elements

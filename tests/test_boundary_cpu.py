@@ -46,6 +46,13 @@ def test_selector_answers(lib):
     info = unit.unit_select_matmul(4096, 4096, 4096, unit.UNIT_I8)
     assert info.block_m * info.block_n >= 128 * 128 and info.split_k == 1
     assert info.workgroups == (4096 // info.block_m) * (4096 // info.block_n)
+    # the batch-1 fully connected shape runs on the dot-product path (one wave per column), from 5 rows on the MFMA tile
+    info = unit.unit_select_matmul(1, 1000, 2048, unit.UNIT_I8)
+    assert (info.mfma, info.block_n, info.workgroups, info.split_k) == (0, 4, 250, 1)
+    assert unit.unit_select_matmul(4, 1000, 512, unit.UNIT_F16).mfma == 0
+    assert unit.unit_select_matmul(8, 1000, 512, unit.UNIT_I8).mfma == 16
+    assert unit.unit_select_matmul(1, 1000, 2048, unit.UNIT_FP8).mfma == 16
+    assert unit.unit_matmul_workspace(1, 1000, 2048, 2048, 2048, unit.UNIT_I8) == 0
     # a deep, small layer must be split across workgroups (7x7 output, reduction 4608)
     d = unit.conv_desc(1, 512, 7, 7, 512, 3, 3, 1, 1)
     info = unit.unit_select_conv2d(d, unit.UNIT_I8)

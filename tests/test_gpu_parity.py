@@ -680,3 +680,46 @@ def test_large_conv_two_column_ranges():
     announce("large conv f16, two ranges")
     goth = run_conv_f16(sh, n, xh, wh)
     assert plane_check_f16(sh, n, xh, wh, goth, planes[:8]) <= 1e-3
+
+
+# ------------------------------------------------------------------ matmul with very few rows (dot-product path)
+
+@pytest.mark.parametrize("M", [1, 2, 3, 4, 5, 8])
+def test_matmul_few_rows_dot_product_path(M):
+    """m <= 4 (int8, fp16) runs one wave per output column on v_dot4 / v_dot2 instead of the matrix units (5 and 8
+    rows, which take the 16-row MFMA tile, run through the same cases): the
+    FC shape of the benchmark (1 x 1000 x 2048), ragged reductions (tail chunks, fewer chunks than lanes, padded
+    copies of misaligned operands), leading dimensions larger than the rows, saturated operands."""
+    g = wl.rng(29, M)
+    for N, K, lda_extra, ldb_extra, ldc_extra in [(1000, 2048, 0, 0, 0), (37, 16, 0, 0, 0), (130, 1040, 16, 32, 5),
+                                                  (9, 3000, 0, 0, 0), (64, 131, 3, 1, 0), (257, 4096 + 16, 0, 0, 3)]:
+        info = unit.unit_select_matmul(M, N, K, unit.UNIT_I8)
+        assert (info.mfma == 0 and info.workgroups == (N + 3) // 4) if M <= 4 else info.mfma == 16
+        A, B = wl.int8_weights(g, (M, K + lda_extra)), wl.int8_weights(g, (N, K + ldb_extra))
+        if K == 16:
+            A[:], B[:] = -128, -128                                       # 16 * 2^14 per output
+        ref = oracle.matmul_i8(np.ascontiguousarray(A[:, :K]), np.ascontiguousarray(B[:, :K]))
+        C = torch.full((M, N + ldc_extra), -7, dtype=torch.int32, device="cuda:0")
+        ws = ws_bytes(unit.unit_matmul_workspace(M, N, K, K + lda_extra, K + ldb_extra, unit.UNIT_I8))
+        announce("matmul_i8 few rows", M, N, K, lda_extra, ldb_extra, ldc_extra)
+        unit.unit_matmul_i8(M, N, K, dev(A), K + lda_extra, dev(B), K + ldb_extra, C, N + ldc_extra, ws)
+        torch.cuda.synchronize()
+        got = host(C)
+        assert same(got[:, :N], ref)
+        assert np.all(got[:, N:] == -7)                                   # nothing written past a row's n columns
+        Ah, Bh = wl.f16_activations(g, (M, K + lda_extra)), wl.f16_weights(g, (N, K + ldb_extra), K)
+        Ak, Bk = np.ascontiguousarray(Ah[:, :K]), np.ascontiguousarray(Bh[:, :K])
+        refh = oracle.matmul_f16(Ak, Bk)
+        truth, mag = oracle.matmul_f16_f64(Ak, Bk)
+        Ch = torch.full((M, N + ldc_extra), -7.0, dtype=torch.float32, device="cuda:0")
+        ws = ws_bytes(unit.unit_matmul_workspace(M, N, K, K + lda_extra, K + ldb_extra, unit.UNIT_F16))
+        announce("matmul_f16 few rows", M, N, K)
+        unit.unit_matmul_f16(M, N, K, dev(Ah), K + lda_extra, dev(Bh), K + ldb_extra, Ch, N + ldc_extra, ws)
+        torch.cuda.synchronize()
+        goth = host(Ch)[:, :N]
+        assert f16_rel_err(goth, refh, K) <= 1e-3
+        assert np.all(np.abs(goth - truth) <= 2 * K * 2.0 ** -24 * mag + 1e-30)
+        assert as_accurate_as_oracle(goth, refh, truth)
+    # a forced tile takes the matrix-unit path again (what the tile sweeps of the other tests run)
+    with forced(tile=5, split=1):
+        assert unit.unit_select_matmul(M, 1000, 2048, unit.UNIT_I8).mfma == 16
