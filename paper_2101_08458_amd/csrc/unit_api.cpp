@@ -547,7 +547,7 @@ int static_scratch(void **ptr)
 
 extern "C" {
 
-int unit_version(void) { return 100; }
+int unit_version(void) { return 110; }
 
 const char *unit_status_str(int status)
 {

@@ -442,7 +442,7 @@ def test_requant_epilogue_all_paths():
             exp = oracle.requant(acc, scale, bias if use_bias else None, total_res, relu)
             rq = unit.make_requant(sd, bd if use_bias else None, rd if use_res else None, relu,
                                    skp if use_skip else None, skip_mult)
-            for tile, split in [(None, None), (2, 1), (2, 2), (3, 1), (4, 3), (5, 1), (1, 1)]:
+            for tile, split in [(None, None), (2, 1), (2, 2), (3, 1), (4, 3), (5, 1), (1, 1), (10, 1), (11, 2)]:
                 announce("requant", sh, "bias", use_bias, "res", use_res, "skip", use_skip, "relu", relu,
                          "tile", tile, "split", split)
                 y8 = torch.full((n, sh.k, p, q), 99, dtype=torch.int8, device="cuda:0")
@@ -723,3 +723,31 @@ def test_matmul_few_rows_dot_product_path(M):
     # a forced tile takes the matrix-unit path again (what the tile sweeps of the other tests run)
     with forced(tile=5, split=1):
         assert unit.unit_select_matmul(M, 1000, 2048, unit.UNIT_I8).mfma == 16
+
+
+def test_direct_1x1_two_column_ranges():
+    """Two column ranges in the direct NCHW read of a 1x1 conv (24 images of 56x56, 512 -> 256 channels: 294 tiles of
+    256 x 256 = one round + 38 column tiles, which run as 256 x 128 tiles; the 256 x 192 tile has no direct-read
+    kernel).  The seam (column 65536) lies inside image 20."""
+    sh, n = wl.ConvShape(512, 56, 56, 256, 1, 1, 1, 0), 24
+    d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
+    x, w = wl.conv_inputs_i8(sh, n, 9, 5)
+    xd = dev(x)
+    assert unit.unit_conv2d_input_mode(d, unit.UNIT_I8, xd) == unit.UNIT_INPUT_DIRECT
+    info = unit.unit_select_conv2d_input(d, unit.UNIT_I8, unit.UNIT_INPUT_DIRECT)
+    assert (info.block_n, info.workgroups, info.tail_block_n, info.tail_first_col) == (256, 256, 128, 65536)
+    wp = ws_bytes(unit.unit_packed_weights_bytes(d, unit.UNIT_I8))
+    unit.unit_pack_weights_i8(d, dev(w), wp)
+    y = torch.full((n, sh.k, 56, 56), -7, dtype=torch.int32, device="cuda:0")
+    announce("direct 1x1, two ranges", info.tail_block_n, info.tail_workgroups)
+    unit.unit_conv2d_wpacked_i8(d, xd, wp, y, None, None, ws_bytes(unit.unit_conv2d_wpacked_workspace(d, unit.UNIT_I8)))
+    torch.cuda.synchronize()
+    got = host(y)
+    g = wl.rng(30)
+    for ni, k in [(0, 0), (20, 255), (20, 1), (21, 77), (23, 255)] + [(int(g.integers(n)), int(g.integers(sh.k))) for _ in range(5)]:
+        ref = oracle.conv2d_i8(np.ascontiguousarray(x[ni:ni + 1]), np.ascontiguousarray(w[k:k + 1]))
+        assert same(got[ni, k], ref[0, 0], f"image {ni} channel {k}")
+    wsum = w.astype(np.int64).sum(axis=0)[:, 0, 0]                    # [c]: the conv summed over output channels
+    for ni in (20, 22):
+        exp = np.tensordot(wsum, x[ni].astype(np.int64), axes=(0, 0))
+        assert np.array_equal(got[ni].astype(np.int64).sum(axis=0), exp), ni
