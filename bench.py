@@ -50,6 +50,9 @@ def parse():
                     help="layer-set workloads: run only the warm-up and the timed steps (no per-layer timing loops, no "
                          "cold rotation, no other configurations, no CPU baseline), so that a profile of the run holds "
                          "the step's kernels only")
+    ap.add_argument("--phase-probe", action="store_true",
+                    help="ResNet-50 batch-1 set on the instrumented library (make -C paper_2101_08458_amd/csrc probe): per-layer "
+                         "time stamps of the main kernel's phases inside the replayed 53-layer graph; prints its own JSON line")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (counter calibration for profiles)")
     return ap.parse_args()
@@ -258,6 +261,74 @@ def mfma_ceiling(torch, unit):
     return res
 
 
+def phase_probe(torch, unit, wl):
+    """Where the 53-layer step's time goes, from inside the kernels: the instrumented library stamps the cycle and the
+    100 MHz real-time counters at the main kernel's phase boundaries in every wave (UNIT_STAMP in csrc/igemm.hpp); the
+    step is captured as usual, every layer writing to a probe region of its own, and replayed."""
+    import ctypes
+    lib = unit.load()
+    layers = wl.resnet50_convs()
+    seq = [ConvCase(torch, unit, wl, sh, 1, "i8", 3, idx) for idx, sh in enumerate(layers)]
+    slot = 1 << 16                                       # uint64 per layer: up to 4096 waves x 16 stamps
+    probe = torch.zeros(len(seq) * slot, dtype=torch.int64, device="cuda:0")
+    lib.unit_probe_set.restype, lib.unit_probe_set.argtypes = None, [ctypes.c_void_p]
+
+    def step():
+        for i, c in enumerate(seq):
+            lib.unit_probe_set(probe.data_ptr() + i * slot * 8)
+            c.api()
+        lib.unit_probe_set(None)
+    g = capture(torch, step)
+    for _ in range(20):
+        g.replay()
+    torch.cuda.synchronize()
+    probe.zero_()
+    torch.cuda.synchronize()
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    g.replay()
+    b.record()
+    torch.cuda.synchronize()
+    P = probe.cpu().numpy().reshape(len(seq), slot)
+    rows, prev_end = [], None
+    keys = ("gap_us", "skew_us", "prologue_math_us", "prologue_issue_us", "prologue_wait_us", "loop_us", "drain_us",
+            "epilogue_issue_us", "stores_ack_us", "span_us")
+    tot = dict.fromkeys(keys, 0.0)
+    for i, c in enumerate(seq):
+        mode = unit.unit_conv2d_input_mode(c.d, c.ut, c.x)
+        info = unit.unit_select_conv2d_input(c.d, c.ut, mode)
+        nw = (info.workgroups // info.split_k) * info.waves_m * info.waves_n * info.waves_k
+        p = P[i, :nw * 16].reshape(nw, 16)
+        rt = p[:, 8:16].astype(np.float64) / 100.0        # microseconds (100 MHz counter)
+        rt = rt[rt[:, 0] > 0]
+        # stamp order in time: 0 entry, 6 arithmetic done, 7 tiles requested, 1 loop start, 2 loop end, 3 drained,
+        # 4 stores issued, 5 stores acknowledged (with a reduction split the slices share the region: last writer wins)
+        t = rt[:, [0, 6, 7, 1, 2, 3, 4, 5]]
+        start, end = t[:, 0].min(), t[:, 7].max()
+        d = np.diff(t, axis=1).mean(axis=0)
+        r = {"layer": i, "shape": list(layers[i]), "input": ("packed", "direct", "direct-shifted")[mode],
+             "workgroups": info.workgroups, "split": info.split_k,
+             "gap_us": round(start - prev_end, 2) if prev_end is not None else 0.0,
+             "skew_us": round(t[:, 0].mean() - start, 2)}
+        for k, v in zip(keys[2:9], d):
+            r[k] = round(float(v), 2)
+        r["span_us"] = round(end - start, 2)
+        # shader clock over the loop: core cycles per real-time tick
+        cyc = p[:, :8].astype(np.float64)[p[:, 8] > 0]
+        # (only without a reduction split: its slices share a probe region, and the cycle counters of different XCDs differ)
+        r["loop_clock_MHz"] = (round(float((cyc[:, 2] - cyc[:, 1]).mean() / max((rt[:, 2] - rt[:, 1]).mean(), 1e-9)))
+                               if info.split_k == 1 else None)
+        prev_end = end
+        rows.append(r)
+        for k in keys:
+            tot[k] += r[k]
+    return {"metric": "phase time stamps inside the replayed 53-layer step", "unit": "us",
+            "probed_step_us": round(a.elapsed_time(b) * 1e3, 1),
+            "note": "gap = last wave of the previous main kernel to first wave of this one (contains any pack_act / "
+                    "splitk_reduce launched in between); the instrumented kernels are a few percent slower than the product's",
+            "sums_us": {k: round(v, 1) for k, v in tot.items()}, "layers": rows}
+
+
 def tile_str(info):
     tail = f" + tail 256x{info.tail_block_n} wg{info.tail_workgroups}" if info.tail_block_n else ""
     return (f"{info.block_m}x{info.block_n}x{info.block_k_bytes}B waves {info.waves_m}x{info.waves_n}x{info.waves_k} "
@@ -413,9 +484,17 @@ def main():
         sys.exit(2)
     import torch
     from paper_2101_08458_amd import unit, workloads as wl
+    if args.phase_probe:
+        unit.LIB_PATH = os.path.join(os.path.dirname(unit.LIB_PATH), "libunit_probe.so")
+        if not os.path.exists(unit.LIB_PATH):
+            print("bench.py --phase-probe needs the instrumented library: make -C paper_2101_08458_amd/csrc probe", file=sys.stderr)
+            sys.exit(2)
     unit.load()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.phase_probe:
+        print(json.dumps(phase_probe(torch, unit, wl)))
+        return
 
     if args.copy_calibration_mib:
         src = torch.ones(args.copy_calibration_mib << 20, dtype=torch.uint8, device="cuda:0")

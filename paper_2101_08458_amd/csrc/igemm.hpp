@@ -97,7 +97,22 @@ struct IgemmArgs {
     // column range this launch tiles: [col_base, col_limit) of the cols columns (one launch: 0 and cols; a problem
     // whose tile count leaves the last round of workgroups mostly empty is launched as two ranges with two tile shapes)
     int col_base, col_limit;
+#ifdef UNIT_PROBE
+    // instrumented build only (make probe): per wave 16 x 8 bytes of time stamps, see UNIT_STAMP
+    unsigned long long *probe;
+#endif
 };
+
+// Instrumented build (make probe -> libunit_probe.so, never the product library): every wave stamps the core cycle
+// counter and the 100 MHz real-time counter at the kernel's phase boundaries -- 0 entry, 6 prologue arithmetic done,
+// 7 first tiles requested, 1 first tile landed (loop start), 2 loop end, 3 ring drained, 4 epilogue stores issued,
+// 5 stores acknowledged -- and writes them to probe[(workgroup * waves + wave) * 16 + i] (cycles) and [... + 8 + i]
+// (real time) at the end.  Compiled out of the product.
+#ifdef UNIT_PROBE
+#define UNIT_STAMP(i) do { if (g.probe) { unit_pt[i] = __builtin_readcyclecounter(); unit_pr[i] = __builtin_amdgcn_s_memrealtime(); } } while (0)
+#else
+#define UNIT_STAMP(i) do { } while (0)
+#endif
 
 // One element of the requantise rule.  v_cvt_f32_i32 and v_rndne_f32 both round to
 // nearest even; the multiply is a single fp32 operation (no fused add exists here).
@@ -329,6 +344,10 @@ igemm_kernel(const IgemmArgs g)
     auto nchw_swz = [&](int r) { return SWZ_MOD > 1 ? SWZ_UNIT * ((r / SWZ_DIV) % SWZ_MOD) : 0; };
 
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+#ifdef UNIT_PROBE
+    unsigned long long unit_pt[8] = {0, 0, 0, 0, 0, 0, 0, 0}, unit_pr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+    UNIT_STAMP(0);
 
     const int tid  = threadIdx.x;
     const int lane = tid & 63;
@@ -878,10 +897,13 @@ igemm_kernel(const IgemmArgs g)
         if ((BSRC == BSRC_NCHWS || EDGE1) && wave == 0)   // first and last 16 bytes of the tensor (see read_frags)
             dma16(rsB, smem + NST * C::STAGE_BYTES,
                   lane == 0 ? 0u : lane == 1 ? (unsigned)(g.b_bytes - 16) : UNIT_OOB);
+        UNIT_STAMP(6);
 #pragma unroll
         for (int t = 0; t < AHEAD; ++t) issue_tile(t);          // (zeros past the slice end)
+        UNIT_STAMP(7);
         UNIT_WAIT_VM_LGKM0((AHEAD - 1) * C::LPT);               // own part of tile 0 has landed
         UNIT_BARRIER();
+        UNIT_STAMP(1);
         int stage = 0;
         if (WHOLE) {
 #pragma unroll
@@ -1014,8 +1036,10 @@ igemm_kernel(const IgemmArgs g)
             stage = next_stage;
         }
         }
+        UNIT_STAMP(2);
         UNIT_WAIT_VM_LGKM0(0);                       // drain the (zero-fill) DMAs of the tiles past the end
         UNIT_BARRIER();
+        UNIT_STAMP(3);
     }
 
     // ---- in-group split reduction and epilogue.  With an in-group reduction split every wave parks
@@ -1124,6 +1148,18 @@ igemm_kernel(const IgemmArgs g)
             }
         }
     }
+#ifdef UNIT_PROBE
+    UNIT_STAMP(4);
+    if (g.probe) {
+        __builtin_amdgcn_s_waitcnt(0);
+        UNIT_STAMP(5);
+        if (lane == 0) {
+            unsigned long long *o = g.probe + ((size_t)blockIdx.x * NW + wave) * 16;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) { o[i] = unit_pt[i];  o[8 + i] = unit_pr[i]; }
+        }
+    }
+#endif
 }
 
 }  // namespace unit

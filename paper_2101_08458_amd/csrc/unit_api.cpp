@@ -34,6 +34,9 @@ using namespace unit;
 namespace {
 
 thread_local char g_hip_err[256] = "";
+#ifdef UNIT_PROBE
+void *g_probe_ptr = nullptr;        // instrumented build: where the next launches write their time stamps
+#endif
 
 // Internal problem description: conv2d is the depth-1 case of conv3d (the only thing that
 // changes between them is the address generator of the gather).
@@ -159,6 +162,9 @@ int run_igemm(int dtype, int bsrc, IgemmArgs a, long out_elems, int K, int PQ,
     // copy in L2) a run walks the column tiles of one row tile, so A (the weights) is fetched once in total; large
     // problems walk bands of 8 row tiles, which bounds the re-fetching of both operands.
     a.row_runs = ((long)a.cols * a.kchunks * 16 <= (8L << 20)) ? 1 : 0;
+#ifdef UNIT_PROBE
+    a.probe = static_cast<unsigned long long *>(g_probe_ptr);
+#endif
     {   // divisors of the index arithmetic that do not depend on the tile
         a.nimg = (int)(a.cols / (a.PQ > 0 ? a.PQ : 1));
         a.dv_pq = make_div(a.PQ);
@@ -546,6 +552,12 @@ int static_scratch(void **ptr)
 }  // namespace
 
 extern "C" {
+
+#ifdef UNIT_PROBE
+// Instrumented build only: main-kernel launches from now on write their per-wave time stamps to `buf`
+// (device memory, (workgroups * waves) * 128 bytes for the largest launch; NULL switches it off).
+void unit_probe_set(void *buf) { g_probe_ptr = buf; }
+#endif
 
 int unit_version(void) { return 110; }
 
