@@ -344,3 +344,32 @@ def test_measure_mfma_runs_and_reports_plausible_counters():
     lib = unit.load()
     assert lib.unit_measure_mfma(unit.UNIT_FP8, 8, 0, counters.data_ptr(), counters.numel() * 8, 0) == unit.UNIT_EINVAL
     assert lib.unit_measure_mfma(unit.UNIT_I8, 8, 0, counters.data_ptr(), 64, 0) == unit.UNIT_EWORKSPACE
+
+
+def test_two_column_ranges_other_operand_types():
+    """The two-launch column-range plan (whole rounds of the large tile + a narrower tile) for u8 x i8, bf16 and fp8:
+    columns on both sides of the seam at 4096 and the ragged end, sampled against the oracle."""
+    M, N, K = 4096, 4352 + 21, 512
+    for ut in (unit.UNIT_U8I8, unit.UNIT_BF16, unit.UNIT_FP8):
+        info = unit.unit_select_matmul(M, N, K, ut)
+        assert info.block_n == 256 and info.tail_block_n in (128, 192) and info.tail_first_col == 4096, ut
+    cols = np.array([0, 4095, 4096, 4097, 4223, 4224, 4351, 4352, N - 1])
+    rows = np.array([0, 255, 256, 4095])
+    A, B = wl.gemm_inputs_u8i8(M, N, K, 48, 1)
+    announce("matmul_u8i8 two ranges")
+    got = run_matmul("u8i8", A, B)
+    assert same(got[:, cols], oracle.matmul_u8i8(A, np.ascontiguousarray(B[cols])))
+    assert same(got[rows], oracle.matmul_u8i8(np.ascontiguousarray(A[rows]), B))
+    A, B = wl.gemm_inputs_bf16(M, N, K, 48, 2)
+    announce("matmul_bf16 two ranges")
+    got = run_matmul("bf16", A, B)
+    ref, truth, mag = oracle.matmul_bf16(A, np.ascontiguousarray(B[cols]))
+    assert f16_rel_err(got[:, cols], ref, K) <= 1e-3
+    assert np.all(np.abs(got[:, cols] - truth) <= 2 * K * 2.0 ** -24 * mag + 1e-30)
+    assert as_accurate_as_oracle(got[:, cols], ref, truth)
+    A, B = wl.gemm_inputs_fp8(M, N, K, 48, 3)
+    announce("matmul_fp8 two ranges")
+    got = run_matmul("fp8", A, B)
+    ref, truth, mag = oracle.matmul_fp8(A, np.ascontiguousarray(B[cols]))
+    assert fp8_rel_err(got[:, cols], ref) <= 1e-3
+    assert np.all(np.abs(got[:, cols] - truth) <= fp8_bound(K, mag))
