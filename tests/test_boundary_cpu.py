@@ -299,3 +299,29 @@ def test_build_check_rejects_spills_in_inline_asm_variants(tmp_path):
     res = sorted(glob.glob(os.path.join(ROOT, "paper_2101_08458_amd", "csrc", "_build", "*.res")))
     if res:                                                                  # the tree's own build, when present
         assert subprocess.run([sys.executable, script] + res, capture_output=True).returncode == 0
+
+
+def test_column_range_plan_invariants_on_random_shapes(lib):
+    """Host logic of the two-launch plan over 3000 seeded random matmul shapes: the first launch covers whole column tiles
+    of the large tile from column 0, the second the rest in at most one round of workgroups, and together exactly [0, n)."""
+    import numpy as np
+    g = wl.rng(77, 1)
+    two = 0
+    for _ in range(3000):
+        m = int(g.integers(1, 9000)); n = int(g.integers(1, 200000)); k = int(g.choice([64, 256, 512, 1024, 4096, 9000]))
+        for ut in (unit.UNIT_I8, unit.UNIT_F16, unit.UNIT_FP8):
+            i = unit.unit_select_matmul(m, n, k, ut)
+            tm = -(-m // i.block_m) if i.mfma else 0
+            if not i.tail_block_n:
+                assert i.tail_workgroups == 0 and i.tail_first_col == 0
+                if i.mfma:
+                    assert i.workgroups == tm * -(-n // i.block_n) * i.split_k
+                continue
+            two += 1
+            assert (i.block_m, i.block_n, i.split_k) == (256, 256, 1) and i.tail_block_n in (128, 192)
+            assert 0 < i.tail_first_col < n and i.tail_first_col % 256 == 0
+            assert i.workgroups == tm * (i.tail_first_col // 256)
+            rounds = -(-i.workgroups // 256)                                               # whole rounds, short by less than one column of tiles
+            assert 0 <= 256 * rounds - i.workgroups < tm
+            assert i.tail_workgroups == tm * -(-(n - i.tail_first_col) // i.tail_block_n) <= 256
+    assert two > 50          # the sample does exercise the two-launch branch
