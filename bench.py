@@ -43,7 +43,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="resnet50_i8_b1",
                     choices=["resnet50_i8_b1", "gemm_i8_4096", "large_conv_i8", "gemm_f16_4096",
-                             "large_conv_f16", "resnet50_f16_b16", "table1_ablation", "conv3d_resnet18"])
+                             "large_conv_f16", "resnet50_f16_b16", "table1_ablation", "conv3d_resnet18",
+                             "gemm_i8_8192", "gemm_f16_8192"])
     ap.add_argument("--no-others", action="store_true", help="skip the secondary configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--step-only", action="store_true",
@@ -52,7 +53,8 @@ def parse():
                          "the step's kernels only")
     ap.add_argument("--phase-probe", action="store_true",
                     help="ResNet-50 batch-1 set on the instrumented library (make -C paper_2101_08458_amd/csrc probe): per-layer "
-                         "time stamps of the main kernel's phases inside the replayed 53-layer graph; prints its own JSON line")
+                         "time stamps of the main kernel's phases inside the replayed 53-layer graph; with a gemm_* workload, "
+                         "the phases of that GEMM's rounds of workgroups; prints its own JSON line")
     ap.add_argument("--copy-calibration-mib", type=int, default=0,
                     help="also run one plain device copy of this many MiB (counter calibration for profiles)")
     return ap.parse_args()
@@ -329,6 +331,75 @@ def phase_probe(torch, unit, wl):
             "sums_us": {k: round(v, 1) for k, v in tot.items()}, "layers": rows}
 
 
+def phase_probe_gemm(torch, unit, wl, dtype, size):
+    """Phase stamps of the large-tile kernel on one size^3 GEMM (instrumented library): per round of 256 workgroups,
+    when its waves pass each phase boundary, and the median length of each phase of a wave."""
+    import ctypes
+    lib = unit.load()
+    lib.unit_probe_set.restype, lib.unit_probe_set.argtypes = None, [ctypes.c_void_p]
+    c = GemmCase(torch, unit, wl, size, size, size, dtype)
+    info = c.info
+    nwpg = info.waves_m * info.waves_n * info.waves_k
+    nw = info.workgroups * nwpg
+    probe = torch.zeros(nw * 16, dtype=torch.int64, device="cuda:0")
+    ramp_up(torch, c.run)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for _ in range(10):
+        c.run()
+    b.record()
+    torch.cuda.synchronize()
+    plain_us = a.elapsed_time(b) * 100.0
+    lib.unit_probe_set(probe.data_ptr())
+    for _ in range(3):
+        c.run()
+    torch.cuda.synchronize()
+    a.record()
+    c.run()
+    b.record()
+    torch.cuda.synchronize()
+    lib.unit_probe_set(None)
+    P = probe.cpu().numpy().reshape(info.workgroups, nwpg, 16)
+    rt = P[:, :, 8:16].astype(np.float64)[:, :, [0, 6, 7, 1, 2, 3, 4, 5]] / 100.0     # microseconds, in time order
+    cyc = P[:, :, :8].astype(np.float64)
+    t0 = rt[:, :, 0].min()
+    order = np.argsort(rt[:, :, 0].min(axis=1))
+    names = ("entry", "arithmetic_done", "tiles_requested", "loop_start", "loop_end", "drained", "stores_issued", "stores_acked")
+    phases = ("prologue_math_us", "prologue_issue_us", "prologue_wait_us", "loop_us", "drain_us", "epilogue_issue_us", "stores_ack_us")
+    es = 1 if dtype == "i8" else 2
+    steps = (size * es + info.block_k_bytes - 1) // info.block_k_bytes
+    mfma_k = 32 if dtype == "i8" else 16
+    mfma_cycles = info.block_m * info.block_n * (info.block_k_bytes // es) // (32 * 32 * mfma_k) * 32 // 4
+    rounds = []
+    for r in range(0, info.workgroups, 256):
+        sel = order[r:r + 256]
+        d = rt[sel]
+        row = {"workgroups": len(sel)}
+        for i, nm in enumerate(names):
+            row[nm] = [round(float(d[:, :, i].min() - t0), 2), round(float(np.median(d[:, :, i]) - t0), 2),
+                       round(float(d[:, :, i].max() - t0), 2)]
+        for i, nm in enumerate(phases):
+            row[nm] = round(float(np.median(d[:, :, i + 1] - d[:, :, i])), 2)
+        lc = cyc[sel][:, :, 2] - cyc[sel][:, :, 1]              # core cycles of the loop, per wave
+        lt = d[:, :, 4] - d[:, :, 3]
+        row["loop_clock_MHz"] = round(float(lc.mean() / max(lt.mean(), 1e-9)))
+        row["loop_cycles_per_step"] = round(float(lc.mean()) / steps)
+        # every XCD runs at a clock of its own under the power limit (workgroup id % 8 = XCD)
+        row["per_xcd"] = [{"xcd": x, "loop_us": round(float(np.median(lt[sel % 8 == x])), 1),
+                           "clock_MHz": round(float((lc[sel % 8 == x] / lt[sel % 8 == x]).mean()))} for x in range(8)]
+        rounds.append(row)
+    return {"metric": f"phase time stamps of one {dtype} GEMM {size}^3", "unit": "us", "tile": tile_str(info),
+            "steps_per_tile": steps,
+            # MFMA issue cycles one SIMD needs for a step of the tile (32 cycles per 32x32 MFMA, four SIMDs per workgroup):
+            # loop_cycles_per_step below is to be read against this
+            "mfma_cycles_per_step": mfma_cycles,
+            "unprobed_us": round(plain_us, 1), "probed_us": round(a.elapsed_time(b) * 1e3, 1),
+            "kernel_span_us": round(float(rt[:, :, 7].max() - t0), 2),
+            "note": "per boundary [min, median, max] over the waves of the round, from the first wave's entry; workgroups "
+                    "sorted by entry time, 256 to a round",
+            "rounds": rounds}
+
+
 def tile_str(info):
     tail = f" + tail 256x{info.tail_block_n} wg{info.tail_workgroups}" if info.tail_block_n else ""
     return (f"{info.block_m}x{info.block_n}x{info.block_k_bytes}B waves {info.waves_m}x{info.waves_n}x{info.waves_k} "
@@ -493,7 +564,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     if args.phase_probe:
-        print(json.dumps(phase_probe(torch, unit, wl)))
+        if args.workload.startswith("gemm_"):
+            _, dt, size = args.workload.split("_")
+            print(json.dumps(phase_probe_gemm(torch, unit, wl, dt, int(size))))
+        else:
+            print(json.dumps(phase_probe(torch, unit, wl)))
         return
 
     if args.copy_calibration_mib:
@@ -629,8 +704,9 @@ def main():
     else:
         dtype = "i8" if "_i8" in wlname else "f16"
         if wlname.startswith("gemm"):
-            c = GemmCase(torch, unit, wl, 4096, 4096, 4096, dtype)
-            fn, desc = c.run, f"GEMM 4096^3 {dtype}"
+            size = int(wlname.rsplit("_", 1)[1])
+            c = GemmCase(torch, unit, wl, size, size, size, dtype)
+            fn, desc = c.run, f"GEMM {size}^3 {dtype}"
         else:
             c = ConvCase(torch, unit, wl, wl.LARGE_CONV, 32, dtype, 9, 0)
             fn, desc = c.api, f"conv N=32 C=K=256 56x56 3x3 {dtype} (pack_act + conv)"
