@@ -671,8 +671,9 @@ igemm_kernel(const IgemmArgs g)
     // reduction below), otherwise the groups of its own accumulators, one MFMA tile at a time.
     constexpr int NA = M::NACC, GPT = NA / 4;       // groups per MFMA tile
     constexpr int NG = TM * TN * GPT;               // groups per wave window
-    static_assert(NG % WGK == 0, "the groups of a window must split evenly over its waves");
-    constexpr int UG = (WGK > 1) ? NG / WGK : GPT;  // groups handled together (their loads are issued first)
+    static_assert(NG % WGK == 0 || NG < WGK, "the groups of a window must split evenly over its waves");
+    // (a window with fewer groups than waves -- one 16x16 MFMA tile under a four-way split -- is finished by its first NG waves)
+    constexpr int UG = (WGK > 1) ? (NG + WGK - 1) / WGK : GPT;  // groups handled together (their loads are issued first)
     constexpr int NU = (WGK > 1) ? 1 : TM * TN;     // such units per wave
     // first row (of four), column, and offset of (row 0, column) in the output of group q of unit u
     auto group_at = [&](int u, int q, int &grow, int &gcol, long &gcb) {
@@ -1060,6 +1061,7 @@ igemm_kernel(const IgemmArgs g)
                     park[((wk * WGM * WGN + wmn) * NG + (i * TN + j) * GPT + a4) * 64 + lane] =
                         v4e{acc[i][j][4 * a4], acc[i][j][4 * a4 + 1], acc[i][j][4 * a4 + 2], acc[i][j][4 * a4 + 3]};
         __syncthreads();
+        if (NG < WGK && wk >= NG) return;           // (no barrier follows)
     }
 
     const elem_t *tile_base = reinterpret_cast<const elem_t *>(g.out) + (long)blockIdx.z * g.split_stride +

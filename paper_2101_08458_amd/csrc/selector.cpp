@@ -37,6 +37,7 @@ bool tile_fits(int tile, int dtype, int bsrc)
 {
     if (tile < 0 || tile >= NUM_TILES) return false;
     const TileCfg &c = (dtype == 4 /* fp8 */ ? g_tiles_fp8 : g_tiles)[tile];
+    if (c.bm == 0) return false;                                     // no kernel of this tile for the type
     const int nw = c.wgm * c.wgn * c.wgk, rpi = 1024 / c.bkb;
     const int lpt = c.bm / rpi / nw + c.bn / rpi / nw;
     const long edge = (bsrc == BSRC_NCHWS || bsrc == BSRC_NCHW) ? 1024 : 0;   // (NCHW may become NCHWE)
@@ -53,7 +54,6 @@ static inline int cdiv(long a, long b) { return (int)((a + b - 1) / b); }
 
 TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, bool allow_split, int cb)
 {
-    (void)dtype;
     const int CUS = 256;
     int tile = -1;
     if (rows <= 16) {
@@ -94,6 +94,15 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
     if (tile == 4 && cb > 0 && cb % 8 != 0 && cb % 4 == 0 &&
         (bsrc == BSRC_NCHWS || (bsrc == BSRC_GATHER && kchunks <= 128)))
         tile = 9;
+    // Few output elements (at most 64 tiles of 32x32: the 14x14 and 7x7 layers at batch 1) and a reduction of four to
+    // ten 256-byte steps: 16x16 tiles give most compute units a workgroup of their own without a grid split of the
+    // reduction, i.e. without the reduce launch (ResNet-50 batch-1 step: -1.1 us on each 256-channel 3x3 layer at
+    // 14x14, -0.5 us on 1024 -> 256 at 14x14, -2.5 us on 2048 -> 512 at 7x7).  Deeper reductions are as fast split
+    // across 32x32 workgroups, and with more tiles than that the 16x16 tile's extra operand traffic costs more
+    // than the idle compute units (256 -> 1024 at 14x14: +0.8 us).
+    if (tile == 4 && (long)cdiv(rows, 32) * cdiv(cols, 32) <= 64 && kchunks >= 64 && kchunks <= 160 &&
+        (bsrc != BSRC_NCHWS || (cb > 0 && cb % 16 == 0)) && tile_fits(12, dtype, bsrc))
+        tile = 12;
     const int forced = g_force_tile.load(std::memory_order_relaxed);
     if (forced >= 0 && forced < NUM_TILES) tile = forced;
 

@@ -17,7 +17,7 @@ struct TileCfg {
     int mf;                   // MFMA edge
     int nst;                  // LDS stages
 };
-enum { NUM_TILES = 12 };
+enum { NUM_TILES = 13 };
 extern const TileCfg g_tiles[NUM_TILES];
 extern const TileCfg g_tiles_fp8[NUM_TILES];   // same tiles, wave grids of the fp8 kernels
 

@@ -59,8 +59,8 @@ def test_selector_answers(lib):
     assert info.split_k > 1 and info.workgroups >= 128
     assert unit.unit_conv2d_packed_workspace(d, unit.UNIT_I8) >= info.split_k * 512 * 49 * 4
     # per input mode: the packed answer is unit_select_conv2d's; the shifted direct read splits a
-    # 14x14 layer of 18 steps that the packed path leaves whole; an unknown mode is an error
-    d = unit.conv_desc(1, 256, 14, 14, 256, 3, 3, 1, 1)
+    # 14x14 layer of 14 steps that the packed path leaves whole; an unknown mode is an error
+    d = unit.conv_desc(1, 192, 14, 14, 192, 3, 3, 1, 1)
     packed = unit.unit_select_conv2d(d, unit.UNIT_I8)
     same = unit.unit_select_conv2d_input(d, unit.UNIT_I8, unit.UNIT_INPUT_PACKED)
     assert (same.block_m, same.block_n, same.split_k, same.workgroups) == \
@@ -68,6 +68,21 @@ def test_selector_answers(lib):
     shifted = unit.unit_select_conv2d_input(d, unit.UNIT_I8, unit.UNIT_INPUT_DIRECT_SHIFTED)
     assert packed.split_k == 1 and shifted.split_k > 1
     assert shifted.workgroups == packed.workgroups // packed.split_k * shifted.split_k
+    # few output elements and a reduction of four to ten 256-byte steps: the 16x16 tile, one workgroup per 16 channels x
+    # 16 pixels and no split, in every input mode (the 256-channel 14x14 layers, 1024 -> 256 at 14x14, 2048 -> 512 at 7x7);
+    # not for a deeper reduction, for more output elements, or for fp8 (no kernel of that tile)
+    for shape, wgs in (((256, 14, 14, 256, 3, 3, 1, 1), 16 * 13), ((1024, 14, 14, 256, 1, 1, 1, 0), 16 * 13),
+                       ((2048, 7, 7, 512, 1, 1, 1, 0), 32 * 4)):
+        d = unit.conv_desc(1, *shape)
+        modes = (unit.UNIT_INPUT_PACKED, unit.UNIT_INPUT_DIRECT_SHIFTED if shape[4] == 3 else unit.UNIT_INPUT_DIRECT)
+        for mode in modes:
+            info = unit.unit_select_conv2d_input(d, unit.UNIT_I8, mode)
+            assert (info.block_m, info.block_n, info.block_k_bytes, info.mfma, info.split_k, info.workgroups) == \
+                   (16, 16, 256, 16, 1, wgs), (shape, mode)
+        assert unit.unit_select_conv2d_input(d, unit.UNIT_FP8, unit.UNIT_INPUT_PACKED).block_m == 32
+    assert unit.unit_select_conv2d(unit.conv_desc(1, 512, 7, 7, 512, 3, 3, 1, 1), unit.UNIT_I8).block_m == 32
+    assert unit.unit_select_conv2d(unit.conv_desc(1, 256, 14, 14, 1024, 1, 1, 1, 0), unit.UNIT_I8).block_m == 32
+    assert unit.unit_select_matmul(256, 196, 2304, unit.UNIT_I8).block_m == 16
     info = unit.unit_tile_info()
     assert lib.unit_select_conv2d_input(ctypes.byref(d), unit.UNIT_I8, 3, ctypes.byref(info)) == unit.UNIT_EINVAL
     assert lib.unit_select_conv2d_input(ctypes.byref(d), unit.UNIT_I8, 0, None) == unit.UNIT_EINVAL

@@ -13,7 +13,7 @@ from gpu_util import announce, dev, host, forced, f16_rel_err, as_accurate_as_or
 
 pytestmark = pytest.mark.gpu
 
-ALL_TILES = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11]
+ALL_TILES = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12]
 SHIFTED, DIRECT, PACKED = unit.UNIT_INPUT_DIRECT_SHIFTED, unit.UNIT_INPUT_DIRECT, unit.UNIT_INPUT_PACKED
 
 
@@ -88,6 +88,8 @@ def test_shifted_direct_f16_bf16_fp8(case):
         if name == "f16" and sh.k > 16:
             assert unit.unit_conv2d_input_mode(d, ut, xd) == mode_f16
         for tile, split in [(None, None)] + [(t, 1) for t in ALL_TILES] + [(3, 2), (4, 3)]:
+            if name == "fp8" and tile == 12:
+                continue                                    # (the 16x16 tile has no fp8 kernel)
             with forced(tile=tile, split=split):
                 mode = unit.unit_conv2d_input_mode(d, ut, xd)
                 announce("shifted", name, tuple(sh), "tile", tile, "split", split, "mode", mode)

@@ -13,7 +13,7 @@ from gpu_util import announce, dev, host, forced, f16_rel_err, as_accurate_as_or
 
 pytestmark = pytest.mark.gpu
 
-ALL_TILES = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11]
+ALL_TILES = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12]
 
 
 def ws_bytes(nbytes):

@@ -10,7 +10,8 @@ from gpu_util import announce, dev, host, forced, f16_rel_err, as_accurate_as_or
 
 pytestmark = pytest.mark.gpu
 
-ALL_TILES = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11]
+ALL_TILES = [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12]
+FP8_TILES = [t for t in ALL_TILES if t != 12]       # the 16x16 tile has no fp8 kernel (too few waves for its DMA blocks)
 
 
 def ws_bytes(nbytes):
@@ -227,7 +228,7 @@ def test_matmul_fp8_exact_ints_every_tile():
         Ai = g.integers(-8, 9, size=(M, K))
         Bi = g.integers(-8, 9, size=(N, K))
         A, B = wl.fp8_e4m3_bits(Ai), wl.fp8_e4m3_bits(Bi)
-        for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 2)]:
+        for tile, split in [(None, None)] + [(t, s) for t in FP8_TILES for s in (1, 2)]:
             announce("matmul_fp8 ints", M, N, K, "tile", tile, "split", split)
             with forced(tile=tile, split=split):
                 got = run_matmul("fp8", A, B)
@@ -242,7 +243,7 @@ def test_matmul_fp8_exact_ints_every_tile():
 def test_matmul_fp8_parity(M, N, K):
     A, B = wl.gemm_inputs_fp8(M, N, K, 49, M + K)
     ref, truth, mag = oracle.matmul_fp8(A, B)
-    for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 2)]:
+    for tile, split in [(None, None)] + [(t, s) for t in FP8_TILES for s in (1, 2)]:
         announce("matmul_fp8", M, N, K, "tile", tile, "split", split)
         with forced(tile=tile, split=split):
             got = run_matmul("fp8", A, B)
@@ -286,7 +287,7 @@ def test_conv_fp8_parity(case):
     x, w = wl.conv_inputs_fp8(sh, n, 50, case)
     ref, truth, mag = oracle.conv2d_fp8(x, w, (sh.stride, sh.stride), (sh.pad, sh.pad))
     kred = sh.c * sh.r * sh.s
-    for tile, split in [(None, None)] + [(t, s) for t in ALL_TILES for s in (1, 2)]:
+    for tile, split in [(None, None)] + [(t, s) for t in FP8_TILES for s in (1, 2)]:
         announce("conv_fp8", tuple(sh), "n", n, "tile", tile, "split", split)
         with forced(tile=tile, split=split):
             got = run_conv("fp8", sh, n, x, w)
@@ -300,7 +301,7 @@ def test_conv_fp8_direct_1x1():
     for sh, n in [(wl.conv_shape(256, 14, 64, 1, 1, 0), 1), (wl.conv_shape(72, 8, 40, 1, 1, 0), 3)]:
         x, w = wl.conv_inputs_fp8(sh, n, 51, sh.c)
         ref, truth, mag = oracle.conv2d_fp8(x, w, (1, 1), (0, 0))
-        for tile in ALL_TILES:
+        for tile in FP8_TILES:
             announce("conv_fp8 direct", tuple(sh), "n", n, "tile", tile)
             with forced(tile=tile, split=1):
                 got = run_conv("fp8", sh, n, x, w)

@@ -61,8 +61,11 @@ def test_static_scratch_matches_workspace_call_on_shrinking_calls():
     mode, split = _run_pair(wl.ConvShape(512, 14, 14, 512, 3, 3, 2, 1), 2, 0, requant=False)
     assert mode == unit.UNIT_INPUT_PACKED and split > 1
     # 2. smaller, shifted direct read with a split: its partial sums land on call 1's packed activations
-    mode, split = _run_pair(wl.ConvShape(256, 14, 14, 256, 3, 3, 1, 1), 1, 1, requant=False)
+    mode, split = _run_pair(wl.ConvShape(512, 7, 7, 512, 3, 3, 1, 1), 1, 1, requant=False)
     assert mode == unit.UNIT_INPUT_DIRECT_SHIFTED and split > 1
+    #    ... and a shifted direct read on 16x16 tiles, which needs no scratch at all
+    mode, split = _run_pair(wl.ConvShape(256, 14, 14, 256, 3, 3, 1, 1), 1, 5, requant=False)
+    assert mode == unit.UNIT_INPUT_DIRECT_SHIFTED and split == 1
     # 3. smaller again, requantise epilogue (always packs first), odd sizes: ragged tiles over stale bytes
     _run_pair(wl.ConvShape(24, 13, 11, 40, 3, 3, 2, 1), 2, 2, requant=True)
     # 4. a deep 7x7 layer whose epilogue runs in the reduce kernel, then the first (largest) case again
