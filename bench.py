@@ -527,7 +527,7 @@ def table1_ablation(torch, unit, wl, out):
 
             generic = timed(3, 1)
             splitk = min(t for t in (timed(3, s) for s in splits) if t is not None)
-            tuned = min(t for t in (timed(tl, s) for tl in (1, 2, 3, 4, 9) for s in splits) if t is not None)
+            tuned = min(t for t in (timed(tl, s) for tl in (1, 2, 3, 4, 9, 12) for s in splits) if t is not None)
             need = unit.unit_conv2d_packed_workspace(c.d, c.ut)
             if need > c.ws.numel():
                 c.ws = torch.empty(need, dtype=torch.uint8, device="cuda:0")

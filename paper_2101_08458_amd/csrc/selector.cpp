@@ -94,15 +94,25 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
     if (tile == 4 && cb > 0 && cb % 8 != 0 && cb % 4 == 0 &&
         (bsrc == BSRC_NCHWS || (bsrc == BSRC_GATHER && kchunks <= 128)))
         tile = 9;
-    // Few output elements (at most 64 tiles of 32x32: the 14x14 and 7x7 layers at batch 1) and a reduction of four to
-    // ten 256-byte steps: 16x16 tiles give most compute units a workgroup of their own without a grid split of the
-    // reduction, i.e. without the reduce launch (ResNet-50 batch-1 step: -1.1 us on each 256-channel 3x3 layer at
-    // 14x14, -0.5 us on 1024 -> 256 at 14x14, -2.5 us on 2048 -> 512 at 7x7).  Deeper reductions are as fast split
-    // across 32x32 workgroups, and with more tiles than that the 16x16 tile's extra operand traffic costs more
-    // than the idle compute units (256 -> 1024 at 14x14: +0.8 us).
-    if (tile == 4 && (long)cdiv(rows, 32) * cdiv(cols, 32) <= 64 && kchunks >= 64 && kchunks <= 160 &&
-        (bsrc != BSRC_NCHWS || (cb > 0 && cb % 16 == 0)) && tile_fits(12, dtype, bsrc))
-        tile = 12;
+    // Few output elements (the 14x14 and 7x7 layers at batch 1): 16x16 tiles with 256-byte steps give most compute
+    // units a workgroup of their own without a grid split of the reduction, i.e. without the reduce launch.
+    //  * Operand rows that are contiguous reduction bytes (packed activations, plain matmul): from 32 chunks of
+    //    reduction on and up to 128 tiles of 32x32, whatever the pixel size -- fastest on 28 of the 32 small Table I
+    //    cases (both types; 3.3-5.7 us against 3.9-6.9 us for the best other tile and split), on the stride-2 layers of
+    //    the ResNet-50 set and through the ResNet-18 chain.
+    //  * Direct reads: a 16-pixel tile takes 16 bytes from each 128-byte line of a channel row, so its steps cost
+    //    0.26-0.38 us against 0.17 us on packed rows; it pays up to 64 tiles of 32x32 and for four to ten steps
+    //    (ResNet-50 batch-1 step: -1.1 us on each 256-channel 3x3 layer at 14x14, -0.5 us on 1024 -> 256 at 14x14,
+    //    -2.5 us on 2048 -> 512 at 7x7; 512-channel 3x3 at 7x7, 18 steps: as fast split across 32x32 workgroups;
+    //    256 -> 1024 at 14x14, 224 tiles: +0.8 us).  The shifted read needs 256-byte pixels (a step stays inside a tap).
+    if (tile == 4 || tile == 9) {
+        const long n32 = (long)cdiv(rows, 32) * cdiv(cols, 32);
+        const bool contiguous = bsrc == BSRC_PLAIN || bsrc == BSRC_GATHER;
+        const bool pick = contiguous ? (n32 <= 128 && kchunks >= 32)
+                                     : (tile == 4 && n32 <= 64 && kchunks >= 64 && kchunks <= 160 &&
+                                        (bsrc != BSRC_NCHWS || (cb > 0 && cb % 16 == 0)));
+        if (pick && tile_fits(12, dtype, bsrc)) tile = 12;
+    }
     const int forced = g_force_tile.load(std::memory_order_relaxed);
     if (forced >= 0 && forced < NUM_TILES) tile = forced;
 
@@ -115,7 +125,11 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
     // main-loop step of a small tile costs ~0.2 us of DMA latency, while the extra reduce
     // launch costs ~3 us, so it pays from about 24 steps on (slices of ~6 steps).
     int split = 1;
-    if (ksteps >= 24 && nt <= CUS / 2) {
+    if (tile == 12) {
+        // the 16x16 tile exists to avoid the reduce launch: measured best unsplit up to 20 of its steps (Table I layer 1
+        // in fp16, the 512-channel 3x3 layers); only far deeper reductions are cut, into slices of 32 steps
+        if (ksteps_tile >= 64) split = ksteps_tile / 32;
+    } else if (ksteps >= 24 && nt <= CUS / 2) {
         split = ksteps / 6;
         int cap = (int)(2 * CUS / nt);
         if (split > cap) split = cap;

@@ -53,11 +53,17 @@ def test_selector_answers(lib):
     assert unit.unit_select_matmul(8, 1000, 512, unit.UNIT_I8).mfma == 16
     assert unit.unit_select_matmul(1, 1000, 2048, unit.UNIT_FP8).mfma == 16
     assert unit.unit_matmul_workspace(1, 1000, 2048, 2048, 2048, unit.UNIT_I8) == 0
-    # a deep, small layer must be split across workgroups (7x7 output, reduction 4608)
+    # a deep, small layer (7x7 output, reduction 4608): split across 32x32 workgroups in the shifted direct read, whole
+    # on 16x16 tiles when the activations are packed; the workspace query covers the partial sums of the split
     d = unit.conv_desc(1, 512, 7, 7, 512, 3, 3, 1, 1)
+    info = unit.unit_select_conv2d_input(d, unit.UNIT_I8, unit.UNIT_INPUT_DIRECT_SHIFTED)
+    assert info.block_m == 32 and info.split_k > 1 and info.workgroups >= 128
+    assert unit.unit_conv2d_wpacked_workspace(d, unit.UNIT_I8) >= info.split_k * 512 * 49 * 4
     info = unit.unit_select_conv2d(d, unit.UNIT_I8)
-    assert info.split_k > 1 and info.workgroups >= 128
-    assert unit.unit_conv2d_packed_workspace(d, unit.UNIT_I8) >= info.split_k * 512 * 49 * 4
+    assert (info.block_m, info.block_n, info.split_k, info.workgroups) == (16, 16, 1, 32 * 4)
+    # ... and a reduction far beyond that is cut into slices of 32 of the tile's steps
+    info = unit.unit_select_matmul(64, 64, 32768, unit.UNIT_I8)
+    assert (info.block_m, info.block_k_bytes, info.split_k) == (16, 256, 4)
     # per input mode: the packed answer is unit_select_conv2d's; the shifted direct read splits a
     # 14x14 layer of 14 steps that the packed path leaves whole; an unknown mode is an error
     d = unit.conv_desc(1, 192, 14, 14, 192, 3, 3, 1, 1)
@@ -67,7 +73,9 @@ def test_selector_answers(lib):
            (packed.block_m, packed.block_n, packed.split_k, packed.workgroups)
     shifted = unit.unit_select_conv2d_input(d, unit.UNIT_I8, unit.UNIT_INPUT_DIRECT_SHIFTED)
     assert packed.split_k == 1 and shifted.split_k > 1
-    assert shifted.workgroups == packed.workgroups // packed.split_k * shifted.split_k
+    assert (shifted.block_m, shifted.block_n, shifted.block_k_bytes) == (32, 32, 64)      # 192-byte pixels: 64-byte steps
+    assert shifted.workgroups == 6 * 7 * shifted.split_k
+    assert (packed.block_m, packed.block_n, packed.workgroups) == (16, 16, 12 * 13)       # packed rows: the 16x16 tile
     # few output elements and a reduction of four to ten 256-byte steps: the 16x16 tile, one workgroup per 16 channels x
     # 16 pixels and no split, in every input mode (the 256-channel 14x14 layers, 1024 -> 256 at 14x14, 2048 -> 512 at 7x7);
     # not for a deeper reduction, for more output elements, or for fp8 (no kernel of that tile)
@@ -80,8 +88,14 @@ def test_selector_answers(lib):
             assert (info.block_m, info.block_n, info.block_k_bytes, info.mfma, info.split_k, info.workgroups) == \
                    (16, 16, 256, 16, 1, wgs), (shape, mode)
         assert unit.unit_select_conv2d_input(d, unit.UNIT_FP8, unit.UNIT_INPUT_PACKED).block_m == 32
-    assert unit.unit_select_conv2d(unit.conv_desc(1, 512, 7, 7, 512, 3, 3, 1, 1), unit.UNIT_I8).block_m == 32
-    assert unit.unit_select_conv2d(unit.conv_desc(1, 256, 14, 14, 1024, 1, 1, 1, 0), unit.UNIT_I8).block_m == 32
+    d = unit.conv_desc(1, 256, 14, 14, 1024, 1, 1, 1, 0)        # 224 tiles of 32x32: stays, packed or direct
+    assert unit.unit_select_conv2d(d, unit.UNIT_I8).block_m == 32
+    assert unit.unit_select_conv2d_input(d, unit.UNIT_I8, unit.UNIT_INPUT_DIRECT).block_m == 32
+    d = unit.conv_desc(1, 1024, 14, 14, 512, 1, 1, 1, 0)        # 112 tiles: 16x16 on packed rows only
+    assert unit.unit_select_conv2d(d, unit.UNIT_I8).block_m == 16
+    assert unit.unit_select_conv2d_input(d, unit.UNIT_I8, unit.UNIT_INPUT_DIRECT).block_m == 32
+    d = unit.conv_desc(1, 64, 56, 56, 128, 1, 1, 2, 0)          # four chunks of reduction: too shallow
+    assert unit.unit_select_conv2d(d, unit.UNIT_I8).block_m == 32
     assert unit.unit_select_matmul(256, 196, 2304, unit.UNIT_I8).block_m == 16
     info = unit.unit_tile_info()
     assert lib.unit_select_conv2d_input(ctypes.byref(d), unit.UNIT_I8, 3, ctypes.byref(info)) == unit.UNIT_EINVAL

@@ -9,13 +9,19 @@ import torch
 
 import oracle
 from paper_2101_08458_amd import unit, workloads as wl
-from gpu_util import announce, dev, host
+from gpu_util import announce, dev, host, forced
 
 pytestmark = pytest.mark.gpu
 
 
-def _run_pair(sh, n, seed, requant):
-    """One layer through both entry points; returns the static call's outputs after checking them."""
+def _run_pair(sh, n, seed, requant, split=None):
+    """One layer through both entry points (optionally with the reduction split forced); returns the input mode and
+    the split the calls ran with, after checking the outputs."""
+    with forced(split=split):
+        return _run_pair_now(sh, n, seed, requant)
+
+
+def _run_pair_now(sh, n, seed, requant):
     d = unit.conv_desc(n, sh.c, sh.h, sh.w, sh.k, sh.r, sh.s, sh.stride, sh.pad)
     p, q = unit.unit_conv2d_out_dims(d)
     x, w = wl.conv_inputs_i8(sh, n, 77, seed)
@@ -58,8 +64,9 @@ def _run_pair(sh, n, seed, requant):
 
 def test_static_scratch_matches_workspace_call_on_shrinking_calls():
     # 1. packed first (stride 2) with a reduction split: packed activations + partial sums in the buffer
-    mode, split = _run_pair(wl.ConvShape(512, 14, 14, 512, 3, 3, 2, 1), 2, 0, requant=False)
-    assert mode == unit.UNIT_INPUT_PACKED and split > 1
+    #    (the selector no longer splits this layer by itself: the split is forced)
+    mode, split = _run_pair(wl.ConvShape(512, 14, 14, 512, 3, 3, 2, 1), 2, 0, requant=False, split=3)
+    assert mode == unit.UNIT_INPUT_PACKED and split == 3
     # 2. smaller, shifted direct read with a split: its partial sums land on call 1's packed activations
     mode, split = _run_pair(wl.ConvShape(512, 7, 7, 512, 3, 3, 1, 1), 1, 1, requant=False)
     assert mode == unit.UNIT_INPUT_DIRECT_SHIFTED and split > 1
@@ -68,7 +75,7 @@ def test_static_scratch_matches_workspace_call_on_shrinking_calls():
     assert mode == unit.UNIT_INPUT_DIRECT_SHIFTED and split == 1
     # 3. smaller again, requantise epilogue (always packs first), odd sizes: ragged tiles over stale bytes
     _run_pair(wl.ConvShape(24, 13, 11, 40, 3, 3, 2, 1), 2, 2, requant=True)
-    # 4. a deep 7x7 layer whose epilogue runs in the reduce kernel, then the first (largest) case again
-    mode, split = _run_pair(wl.ConvShape(512, 7, 7, 512, 3, 3, 1, 1), 1, 3, requant=True)
-    assert split > 1
-    _run_pair(wl.ConvShape(512, 14, 14, 512, 3, 3, 2, 1), 2, 4, requant=False)
+    # 4. a deep 7x7 layer whose epilogue runs in the reduce kernel (split forced), then the first (largest) case again
+    mode, split = _run_pair(wl.ConvShape(512, 7, 7, 512, 3, 3, 1, 1), 1, 3, requant=True, split=4)
+    assert split == 4
+    _run_pair(wl.ConvShape(512, 14, 14, 512, 3, 3, 2, 1), 2, 4, requant=False, split=3)
