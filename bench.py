@@ -263,15 +263,15 @@ def mfma_ceiling(torch, unit):
     return res
 
 
-def phase_probe(torch, unit, wl):
+def phase_probe(torch, unit, wl, dtype="i8", n=1, config_id=3):
     """Where the 53-layer step's time goes, from inside the kernels: the instrumented library stamps the cycle and the
     100 MHz real-time counters at the main kernel's phase boundaries in every wave (UNIT_STAMP in csrc/igemm.hpp); the
     step is captured as usual, every layer writing to a probe region of its own, and replayed."""
     import ctypes
     lib = unit.load()
     layers = wl.resnet50_convs()
-    seq = [ConvCase(torch, unit, wl, sh, 1, "i8", 3, idx) for idx, sh in enumerate(layers)]
-    slot = 1 << 16                                       # uint64 per layer: up to 4096 waves x 16 stamps
+    seq = [ConvCase(torch, unit, wl, sh, n, dtype, config_id, idx) for idx, sh in enumerate(layers)]
+    slot = 1 << 18                                       # uint64 per layer: up to 16384 waves x 16 stamps
     probe = torch.zeros(len(seq) * slot, dtype=torch.int64, device="cuda:0")
     lib.unit_probe_set.restype, lib.unit_probe_set.argtypes = None, [ctypes.c_void_p]
 
@@ -324,7 +324,7 @@ def phase_probe(torch, unit, wl):
         rows.append(r)
         for k in keys:
             tot[k] += r[k]
-    return {"metric": "phase time stamps inside the replayed 53-layer step", "unit": "us",
+    return {"metric": f"phase time stamps inside the replayed 53-layer step ({dtype}, batch {n})", "unit": "us",
             "probed_step_us": round(a.elapsed_time(b) * 1e3, 1),
             "note": "gap = last wave of the previous main kernel to first wave of this one (contains any pack_act / "
                     "splitk_reduce launched in between); the instrumented kernels are a few percent slower than the product's",
@@ -567,6 +567,8 @@ def main():
         if args.workload.startswith("gemm_"):
             _, dt, size = args.workload.split("_")
             print(json.dumps(phase_probe_gemm(torch, unit, wl, dt, int(size))))
+        elif args.workload == "resnet50_f16_b16":
+            print(json.dumps(phase_probe(torch, unit, wl, "f16", 16, 4)))
         else:
             print(json.dumps(phase_probe(torch, unit, wl)))
         return
