@@ -163,7 +163,7 @@ int unit_measure_mfma(int dtype, int32_t steps, int32_t random_operands, void *c
 /*
  * Test and tuning-sweep hook (the "enumerate and profile" loop of Section IV-C drives it; Section
  * VI-B's ablation is measured with it): every later call of this process uses compiled tile `tile`
- * (0 .. 9, see unit_tile_info of a query for what it is) instead of the selector's choice, and
+ * (0 .. 12, see unit_tile_info of a query for what it is) instead of the selector's choice, and
  * `split_k` workgroups per output tile (clipped to the reduction's steps).  A negative tile and a
  * split_k < 1 restore the rule for that half.  Process-wide and not synchronised with calls in
  * flight on other threads: not for production code.  A forced tile that has no kernel for a
