@@ -751,3 +751,89 @@ def test_direct_1x1_two_column_ranges():
     for ni in (20, 22):
         exp = np.tensordot(wsum, x[ni].astype(np.int64), axes=(0, 0))
         assert np.array_equal(got[ni].astype(np.int64).sum(axis=0), exp), ni
+
+
+# ------------------------------------------------------------------ random geometries, the selector's own choices
+
+def _random_conv_cases(seed, count):
+    """Seeded geometries around the selector's decision boundaries: few to some hundred channels (reductions on both
+    sides of 32 / 64 / 160 chunks), 3..30 pixels a side (tile counts on both sides of 64 and 128 tiles of 32x32),
+    windows 1..5 with their own stride and padding per axis, one to three images."""
+    g = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    while len(out) < count:
+        n = int(g.integers(1, 4))
+        c = int(g.choice([1, 3, 8, 16, 24, 32, 48, 64, 96, 128, 160, 256, 288, 512]))
+        k = int(g.choice([1, 5, 16, 17, 32, 64, 100, 128, 192, 256, 300]))
+        h, w_ = int(g.integers(3, 31)), int(g.integers(3, 31))
+        kind = int(g.integers(0, 4))        # half of the cases can take a direct read: 1x1 / "same" 3x3 at stride 1
+        if kind == 0:
+            r = s = sh_ = sw_ = 1
+            ph = pw = 0
+        elif kind == 1:
+            r = s = 3
+            sh_ = sw_ = ph = pw = 1
+        else:
+            r, s = int(g.choice([1, 1, 3, 3, 5])), int(g.choice([1, 1, 3, 3, 2]))
+            sh_, sw_ = int(g.integers(1, 3)), int(g.integers(1, 3))
+            ph, pw = int(g.integers(0, (r + 1) // 2 + 1)), int(g.integers(0, (s + 1) // 2 + 1))
+        if h + 2 * ph < r or w_ + 2 * pw < s or c * r * s > 6000:
+            continue
+        out.append((n, c, h, w_, k, r, s, sh_, sw_, ph, pw))
+    return out
+
+
+@pytest.mark.parametrize("seed", [0, 1])
+def test_conv_random_geometries_selector_choice(seed):
+    """Both entry points that take NCHW activations, with whatever input mode, tile and split the library picks by
+    itself: int8 bit-exact, fp16 within tolerance and as accurate as the sequential oracle."""
+    for i, (n, c, h, w_, k, r, s, sh_, sw_, ph, pw) in enumerate(_random_conv_cases(9000 + seed, 40)):
+        g = wl.rng(70 + seed, i)
+        d = unit.unit_conv2d_desc(n, c, h, w_, k, r, s, sh_, sw_, ph, pw)
+        p, q = unit.unit_conv2d_out_dims(d)
+        x8, w8 = wl.int8_activations(g, (n, c, h, w_)), wl.int8_weights(g, (k, c, r, s))
+        ref = oracle.conv2d_i8(x8, w8, (sh_, sw_), (ph, pw))
+        xd = dev(x8)
+        mode = unit.unit_conv2d_input_mode(d, unit.UNIT_I8, xd)
+        info = unit.unit_select_conv2d_input(d, unit.UNIT_I8, mode)
+        announce("conv random i8", (n, c, h, w_, k, r, s, sh_, sw_, ph, pw), "mode", mode,
+                 "tile", info.block_m, info.block_n, info.block_k_bytes, "split", info.split_k)
+        y = torch.full((n, k, p, q), -7, dtype=torch.int32, device="cuda:0")
+        unit.unit_conv2d_i8(d, xd, dev(w8), y, None, None, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_I8)))
+        torch.cuda.synchronize()
+        assert same(host(y), ref, str((n, c, h, w_, k, r, s, sh_, sw_, ph, pw)))
+        if i % 2:
+            continue
+        xf, wf = wl.f16_activations(g, (n, c, h, w_)), wl.f16_weights(g, (k, c, r, s), c * r * s)
+        reff = oracle.conv2d_f16(xf, wf, (sh_, sw_), (ph, pw))
+        truth, mag = oracle.conv2d_f16_f64(xf, wf, (sh_, sw_), (ph, pw))
+        announce("conv random f16", (n, c, h, w_, k, r, s, sh_, sw_, ph, pw))
+        yf = torch.empty((n, k, p, q), dtype=torch.float32, device="cuda:0")
+        unit.unit_conv2d_f16(d, dev(xf), dev(wf), yf, ws_bytes(unit.unit_conv2d_workspace(d, unit.UNIT_F16)))
+        torch.cuda.synchronize()
+        got, kred = host(yf), c * r * s
+        assert f16_rel_err(got, reff, kred) <= 1e-3, (n, c, h, w_, k, r, s)
+        assert np.all(np.abs(got - truth) <= 2 * kred * 2.0 ** -24 * mag + 1e-30), (n, c, h, w_, k, r, s)
+        assert as_accurate_as_oracle(got, reff, truth), (n, c, h, w_, k, r, s)
+
+
+def test_matmul_random_shapes_selector_choice():
+    g = np.random.Generator(np.random.PCG64(9100))
+    for i in range(40):
+        M, N = int(g.integers(1, 300)), int(g.integers(1, 400))
+        K = int(g.choice([1, 15, 16, 64, 200, 511, 512, 513, 1024, 1500, 2560, 2561, 4100]))
+        gg = wl.rng(72, i)
+        A, B = wl.int8_weights(gg, (M, K)), wl.int8_weights(gg, (N, K))
+        info = unit.unit_select_matmul(M, N, K, unit.UNIT_I8)
+        announce("matmul random i8", M, N, K, "tile", info.block_m, info.block_n, info.block_k_bytes, "split", info.split_k)
+        assert same(run_matmul_i8(A, B), oracle.matmul_i8(A, B), str((M, N, K)))
+        if i % 2:
+            continue
+        Af, Bf = wl.f16_activations(gg, (M, K)), wl.f16_weights(gg, (N, K), K)
+        ref = oracle.matmul_f16(Af, Bf)
+        truth, mag = oracle.matmul_f16_f64(Af, Bf)
+        announce("matmul random f16", M, N, K)
+        got = run_matmul_f16(Af, Bf)
+        assert f16_rel_err(got, ref, K) <= 1e-3, (M, N, K)
+        assert np.all(np.abs(got - truth) <= 2 * K * 2.0 ** -24 * mag + 1e-30), (M, N, K)
+        assert as_accurate_as_oracle(got, ref, truth), (M, N, K)
