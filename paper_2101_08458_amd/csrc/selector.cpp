@@ -78,12 +78,14 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
         // small problems are launch- and latency-bound: measured over the ResNet-50 batch-1
         // layers, 64x64 (2x2x2 waves) wins once it yields ~160 workgroups, 32x32 below that (at ~100 the
         // 32x32 tile's ~400 workgroups fill the chip and finish 0.2-0.4 us earlier, unless the reduction is
-        // deep: there the 64x64 tile's fewer bytes per MAC count for more)
+        // deep, beyond 160 chunks: there the 64x64 tile's fewer bytes per MAC count for more; the 256-channel
+        // 3x3 layers of the ResNet-18 chain at batch 8, 100 tiles of 64x64 and 144 chunks, are 1.4 us faster
+        // each on 32x32 tiles inside the chain)
         // (a 64x64 tile with 256-byte steps in two stages is 4-18 % faster on deep reductions when a layer
         // is timed alone, but slower inside a sequence of layers, where every launch starts on cold caches)
         if (tile < 0) {
             const long n64 = (long)cdiv(rows, 64) * cdiv(cols, 64);
-            tile = (n64 >= 160 || (n64 >= 96 && kchunks > 32)) ? 3 : 4;
+            tile = (n64 >= 160 || (n64 >= 96 && kchunks > 160)) ? 3 : 4;
         }
     }
     // 64-byte pixels (64 int8 or 32 fp16 channels): the small tile with 64-byte steps.  The shifted direct read
@@ -99,7 +101,8 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
     //  * Operand rows that are contiguous reduction bytes (packed activations, plain matmul): from 32 chunks of
     //    reduction on and up to 128 tiles of 32x32, whatever the pixel size -- fastest on 28 of the 32 small Table I
     //    cases (both types; 3.3-5.7 us against 3.9-6.9 us for the best other tile and split), on the stride-2 layers of
-    //    the ResNet-50 set and through the ResNet-18 chain.
+    //    the ResNet-50 set and through the ResNet-18 chain; up to 256 tiles of 32x32 when the reduction is 256 chunks
+    //    or more (the 512-channel 3x3 layers of that chain at batch 8: 208 tiles, -1.1 us each inside the chain).
     //  * Direct reads: a 16-pixel tile takes 16 bytes from each 128-byte line of a channel row, so its steps cost
     //    0.26-0.38 us against 0.17 us on packed rows; it pays up to 64 tiles of 32x32 and for four to ten steps
     //    (ResNet-50 batch-1 step: -1.1 us on each 256-channel 3x3 layer at 14x14, -0.5 us on 1024 -> 256 at 14x14,
@@ -108,7 +111,7 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
     if (tile == 4 || tile == 9) {
         const long n32 = (long)cdiv(rows, 32) * cdiv(cols, 32);
         const bool contiguous = bsrc == BSRC_PLAIN || bsrc == BSRC_GATHER;
-        const bool pick = contiguous ? (n32 <= 128 && kchunks >= 32)
+        const bool pick = contiguous ? ((n32 <= 128 && kchunks >= 32) || (n32 <= 256 && kchunks >= 256))
                                      : (tile == 4 && n32 <= 64 && kchunks >= 64 && kchunks <= 160 &&
                                         (bsrc != BSRC_NCHWS || (cb > 0 && cb % 16 == 0)));
         if (pick && tile_fits(12, dtype, bsrc)) tile = 12;
