@@ -93,7 +93,9 @@ TileChoice select_tile(int rows, int cols, int kchunks, int dtype, int bsrc, boo
     // tap walk instead of the per-lane one (config 1, 64 -> 64 channels 3x3 at 56x56: 3.9 -> 3.5 us)
     // (for the gather only while the reduction is at most 2 KiB: beyond that twice the steps cost more than the
     // per-lane tap walk; Table I layers, both types)
-    if (tile == 4 && cb > 0 && cb % 8 != 0 && cb % 4 == 0 &&
+    // (also in place of the 64x64 tile on packed activations: the 64-channel 3x3 layers of the ResNet-18 chain at
+    // batch 8, 392 tiles of 64x64, are 1 us faster each with one tap per step inside the chain)
+    if ((tile == 4 || (tile == 3 && bsrc == BSRC_GATHER)) && cb > 0 && cb % 8 != 0 && cb % 4 == 0 &&
         (bsrc == BSRC_NCHWS || (bsrc == BSRC_GATHER && kchunks <= 128)))
         tile = 9;
     // A 1x1 direct read whose whole reduction is 64 bytes (64 int8 / 32 fp16 channels): one 64-byte step instead of a
