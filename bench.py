@@ -320,6 +320,16 @@ def phase_probe(torch, unit, wl, dtype="i8", n=1, config_id=3):
         # (only without a reduction split: its slices share a probe region, and the cycle counters of different XCDs differ)
         r["loop_clock_MHz"] = (round(float((cyc[:, 2] - cyc[:, 1]).mean() / max((rt[:, 2] - rt[:, 1]).mean(), 1e-9)))
                                if info.split_k == 1 else None)
+        # small-tile step loop: mean cycles per step a wave waits for its own loads, at the barrier, and for its
+        # fragment reads (sums kept by the instrumented kernel in cycle slots 3-6)
+        steps_run = cyc[:, 6]
+        if steps_run.min() > 0:
+            r["steps"] = int(steps_run.max())
+            loop_cyc = (cyc[:, 2] - cyc[:, 1]) / steps_run
+            r["cycles_per_step"] = {"total": round(float(loop_cyc.mean())) if info.split_k == 1 else None,
+                                    "wait_loads": round(float((cyc[:, 3] / steps_run).mean())),
+                                    "barrier": round(float((cyc[:, 4] / steps_run).mean())),
+                                    "wait_fragments": round(float((cyc[:, 5] / steps_run).mean()))}
         prev_end = end
         rows.append(r)
         for k in keys:

@@ -110,6 +110,10 @@ struct IgemmArgs {
 // (real time) at the end.  Compiled out of the product.
 #ifdef UNIT_PROBE
 #define UNIT_STAMP(i) do { if (g.probe) { unit_pt[i] = __builtin_readcyclecounter(); unit_pr[i] = __builtin_amdgcn_s_memrealtime(); } } while (0)
+// (small-tile step loop only) cycles a wave spends waiting for its own loads / at the barrier / for its fragment reads,
+// summed over the steps (the cycle counter is a scalar memory read: its result is only used after the fragment wait)
+#define UNIT_CYC() ((unsigned)__builtin_readcyclecounter())
+#define UNIT_ACC(sum, from, to) do { sum += (to) - (from); } while (0)
 #else
 #define UNIT_STAMP(i) do { } while (0)
 #endif
@@ -346,6 +350,7 @@ igemm_kernel(const IgemmArgs g)
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
 #ifdef UNIT_PROBE
     unsigned long long unit_pt[8] = {0, 0, 0, 0, 0, 0, 0, 0}, unit_pr[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned unit_w_vm = 0, unit_w_bar = 0, unit_w_frag = 0, unit_n_steps = 0;
 #endif
     UNIT_STAMP(0);
 
@@ -918,10 +923,24 @@ igemm_kernel(const IgemmArgs g)
                 constexpr int STG = decltype(stage_c)::value;
                 constexpr int next_stage = (STG + 1) % NST;
                 constexpr int prev_stage = (STG + NST - 1) % NST;
+#ifdef UNIT_PROBE
+                const unsigned unit_c0 = UNIT_CYC();
+#endif
                 UNIT_WAIT_VM((NST >= 3 ? NST - 3 : 0) * C::LPT);   // own part of the next tile has landed
+#ifdef UNIT_PROBE
+                const unsigned unit_c1 = UNIT_CYC();
+#endif
                 UNIT_BARRIER();
+#ifdef UNIT_PROBE
+                const unsigned unit_c2 = UNIT_CYC();
+#endif
 #pragma unroll
                 for (int s2 = 0; s2 < NS; ++s2) finish_frags(SET * NS + s2);   // (read one step ago)
+#ifdef UNIT_PROBE
+                const unsigned unit_c3 = UNIT_CYC();
+                UNIT_ACC(unit_w_vm, unit_c0, unit_c1);  UNIT_ACC(unit_w_bar, unit_c1, unit_c2);
+                UNIT_ACC(unit_w_frag, unit_c2, unit_c3);  ++unit_n_steps;
+#endif
                 __builtin_amdgcn_sched_barrier(0);
                 if (BSRC == BSRC_NCHWS) advance_reader();
                 if (EDGE1) rt_cb += NCH;
@@ -1159,6 +1178,8 @@ igemm_kernel(const IgemmArgs g)
             unsigned long long *o = g.probe + ((size_t)blockIdx.x * NW + wave) * 16;
 #pragma unroll
             for (int i = 0; i < 8; ++i) { o[i] = unit_pt[i];  o[8 + i] = unit_pr[i]; }
+            // (cycle stamps 3-6 are not used by the readers: the step loop's wait sums go there)
+            o[3] = unit_w_vm;  o[4] = unit_w_bar;  o[5] = unit_w_frag;  o[6] = unit_n_steps;
         }
     }
 #endif
