@@ -32,7 +32,7 @@ HBM_GBS = 8000.0
 # HBM-side bytes per launch (per step for the layer set) of the main kernel, from the committed
 # rocprofv3 counter runs (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, factors from a 256 MiB copy in the
 # same run); files profiles/igemm_*.md.  Not measurable live, so carried as constants.
-TRAFFIC = {"resnet50_i8_b1": 137.0e6, "gemm_i8_4096": 167.9e6, "gemm_f16_4096": 268.6e6, "large_conv_i8": 138.7e6}
+TRAFFIC = {"resnet50_i8_b1": 139.9e6, "gemm_i8_4096": 167.9e6, "gemm_f16_4096": 268.6e6, "large_conv_i8": 138.7e6}
 COLD_BYTES = 512 << 20     # the cold step rotates over layer-buffer sets totalling more than this
 
 
