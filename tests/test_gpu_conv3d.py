@@ -38,7 +38,7 @@ def test_conv3d_parity(case):
     assert unit.unit_conv3d_out_dims(desc) == ref.shape[2:]
     xd, wd, xhd, whd = dev(x), dev(w), dev(xh), dev(wh)
     kred = c * t * r * s
-    for tile, split in [(None, None), (0, 1), (1, 2), (3, 1), (4, 2), (5, 1), (6, 1), (7, 1), (8, 1), (9, 2)]:
+    for tile, split in [(None, None), (0, 1), (1, 2), (3, 1), (4, 2), (5, 1), (6, 1), (7, 1), (8, 1), (9, 2), (10, 1), (11, 1), (12, 1), (12, 2)]:
         announce("conv3d", case, "tile", tile, "split", split)
         with forced(tile=tile, split=split):
             y = torch.full(ref.shape, -7, dtype=torch.int32, device="cuda:0")
